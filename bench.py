@@ -1,0 +1,178 @@
+"""Benchmark of the partition decode hot path on one MI355X.
+
+One step = one mdi_decode_step of the partition (all layers: norm, fused QKV +
+RoPE + KV append, paged attention, output projection, MLP) for one of the N
+samples in flight, visited round-robin so that consecutive steps read different
+KV caches (the rotating-cache access pattern, Sec. III-D).  Inputs, weights and
+caches are resident in HBM before the timed region; prompts are prefilled
+(first visit) before it and timed separately.
+
+Prints ONE JSON line (see the keys below).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1600)
+    ap.add_argument("--warmup", type=int, default=80)
+    ap.add_argument("--workload", type=int, default=4, help="index into the five benchmark configs (1-5)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ctx-sweep", action="store_true", help="also time decode at the middle and end context")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, w, lo, hi, seed, S):
+    """The oracle as it stands, timed on this host: a short first visit plus a few decode steps."""
+    import numpy as np
+    from oracle import mdi_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    op = O.Partition(cfg, w, lo, hi)
+    T, n_dec = 128, 8
+    a = S.make_activations(cfg, seed, 0, T)
+    t0 = time.perf_counter()
+    op.prefill(0, a)
+    t1 = time.perf_counter()
+    for step in range(n_dec):
+        op.decode_step(0, S.make_activations(cfg, seed, 0, 1, step=step + 1)[0])
+    t2 = time.perf_counter()
+    return {"value": n_dec / (t2 - t1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"float64 numpy oracle, same partition and weights, 1 sample: first visit of {T} tokens "
+                      f"({t1 - t0:.1f} s, not counted) then {n_dec} decode steps at context {T}+ ({t2 - t1:.1f} s)",
+            "host_cores_available": len(os.sched_getaffinity(0))}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one partition per GPU is the multi-GPU design; "
+              "no collectives or second device are used). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2505_18164_amd import mdi, synth as S
+
+    wl = S.WORKLOADS[args.workload]
+    cfg, seed = wl["cfg"](), S.workload_seed(args.workload)
+    lo, hi = wl["parts"][0]
+    n_seqs, prompt = wl["n_seqs"], wl["prompt"]
+    embed = lo == 0
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.perf_counter()
+    w = S.make_weights(cfg, seed, lo, hi, embed=embed, head=False)
+    part = mdi.Partition(cfg, w, lo, hi, has_embed=embed, max_seqs=n_seqs, kv_page_tokens=64,
+                         max_prefill=max(prompt, cfg["max_ctx"] - 8 if args.ctx_sweep else prompt))
+    setup_s = time.perf_counter() - t0
+    d = cfg["d_model"]
+    tdt = part.tdtype
+
+    def first_inputs(T):
+        if embed:
+            return [torch.from_numpy(p).to(dev) for p in S.make_prompts(cfg, seed, n_seqs, T)]
+        g = torch.Generator(device=dev).manual_seed(seed + 2)
+        return [torch.randn((T, d), generator=g, device=dev, dtype=torch.float32).to(tdt) for _ in range(n_seqs)]
+
+    def step_inputs():
+        if embed:
+            return [torch.randint(0, cfg["vocab"], (1,), device=dev, dtype=torch.int32) for _ in range(n_seqs)]
+        g = torch.Generator(device=dev).manual_seed(seed + 3)
+        return [torch.randn((d,), generator=g, device=dev, dtype=torch.float32).to(tdt) for _ in range(n_seqs)]
+
+    def run(T, steps, warmup):
+        """Prefill all samples at T tokens, then warm up and time `steps` decode steps."""
+        for s in range(n_seqs):
+            part.seq_reset(s)
+        ins = first_inputs(T)
+        outs = [torch.empty((T, d), dtype=tdt, device=dev) for _ in range(n_seqs)]
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for s in range(n_seqs):
+            part.prefill(s, ins[s], outs[s])
+        e1.record()
+        torch.cuda.synchronize()
+        prefill_ms = e0.elapsed_time(e1) / n_seqs
+        xs = step_inputs()
+        out = torch.empty((d,), dtype=tdt, device=dev)
+        for k in range(warmup):
+            part.decode_step(k % n_seqs, xs[k % n_seqs], out)
+        torch.cuda.synchronize()
+        ctx_first = part.seq_len(0) + 1
+        e0.record()
+        for k in range(steps):
+            part.decode_step((warmup + k) % n_seqs, xs[k % n_seqs], out)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        ctx_last = max(part.seq_len(s) for s in range(n_seqs))
+        ctx_mean = (ctx_first + ctx_last) // 2
+        nbytes = part.step_bytes(ctx_mean)
+        return dict(ctx=ctx_mean, ms_per_step=ms, tokens_per_s=1000.0 / ms, bytes_per_step=nbytes,
+                    gbs=nbytes / ms / 1e6, prefill_ms=prefill_ms)
+
+    main_run = run(prompt, args.steps, args.warmup)
+    n_local = hi - lo
+    params = sum(a * b for a, b in S.layer_tensor_shapes(cfg).values())
+    prefill_flops = n_local * (2.0 * prompt * params + 2.0 * prompt * prompt * cfg["n_head"] * cfg["head_dim"])
+    prefill_tflops = prefill_flops / (main_run["prefill_ms"] * 1e-3) / 1e12
+
+    # dominant kernel: the MLP up(+gate) projection GEMV, timed with HIP events inside the library
+    us, kbytes = part.time_kernel(2, 50)
+    roofline = {"bound": "hbm", "kernel": "k_gemv MLP up+gate projection", "achieved": kbytes / us / 1e3,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kbytes / us / 1e3 / HBM_PEAK_GBS, "traffic": None,
+                "avg_launch_us": us, "bytes_per_launch": kbytes}
+    kernels = {}
+    for which, name in ((1, "attn_out_proj"), (2, "mlp_up"), (3, "mlp_down")):
+        u_, b_ = part.time_kernel(which, 50)
+        kernels[name] = {"avg_us": u_, "GB/s": b_ / u_ / 1e3}
+
+    sweep = None
+    if args.ctx_sweep:
+        sweep = []
+        for T in (prompt + wl["n_new"] // 2, prompt + wl["n_new"] - 8 - 400 // n_seqs):
+            r = run(T, 400, 40)
+            sweep.append({k: r[k] for k in ("ctx", "ms_per_step", "tokens_per_s", "gbs")})
+
+    result = {
+        "metric": f"decode tokens/s per partition ({n_seqs} seqs in flight)",
+        "value": main_run["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_run["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg["dtype"] == S.DT_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": wl["name"], "layers": [lo, hi], "seqs_in_flight": n_seqs, "prompt": prompt,
+                   "context_during_timing": main_run["ctx"], "kv_page_tokens": 64},
+        "step_bytes": main_run["bytes_per_step"], "step_GBps": main_run["gbs"],
+        "step_frac_of_hbm_peak": main_run["gbs"] / HBM_PEAK_GBS,
+        "roofline": roofline, "kernels": kernels,
+        "prefill": {"tokens": prompt, "ms_per_sample": main_run["prefill_ms"], "TFLOP/s": prefill_tflops,
+                    "frac_of_bf16_mfma_peak": prefill_tflops / MFMA_BF16_PEAK_TFLOPS},
+        "setup_s": setup_s,
+    }
+    if sweep:
+        result["ctx_sweep"] = sweep
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, w, lo, hi, seed, S)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

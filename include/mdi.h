@@ -1,0 +1,210 @@
+/*
+ * libmdi -- one node's model partition for model-distributed LLM inference on
+ * AMD MI355X (gfx950).
+ *
+ * The paper's problem statement (Sec. III-A): a node owns a contiguous chunk of
+ * the decoder, receives the intermediate activations of sample n from the
+ * previous node, runs them through its local layers using the n-th KV cache
+ * (Sec. III-D, "rotating KV caches"), and hands the result to the next node.
+ * A sample's first visit carries the whole prompt and builds the cache
+ * (Alg. 1 / Alg. 2, "first iteration"); every later visit carries only the
+ * newest token's activation (Sec. III-D).  The starter node additionally owns
+ * the embedding and the output layers (final norm + vocabulary projection,
+ * Sec. III-B), which hold no KV state (Sec. III-E).
+ *
+ * This header is the whole boundary: plain C, POD structs, raw pointers.
+ * Unless a parameter says "host", every data pointer is a DEVICE pointer that
+ * the caller allocated (the library allocates no device memory at all; its
+ * working set lives in the caller-provided arena).  All compute calls enqueue
+ * work on the partition's HIP stream and return without waiting; argument and
+ * state errors are detected on the host before anything is enqueued.
+ *
+ * Thread-safety: calls on one partition must be serialised by the caller;
+ * different partitions share no mutable state and may be driven concurrently.
+ */
+#ifndef MDI_H
+#define MDI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MDI_ABI_VERSION 1u
+#define MDI_API __attribute__((visibility("default")))
+
+typedef struct mdi_partition mdi_partition; /* opaque host object */
+
+typedef enum {
+  MDI_OK = 0,
+  MDI_ERR_ARG = -1,   /* null pointer, index out of range, unsupported shape          */
+  MDI_ERR_STATE = -2, /* decode before the first visit, prefill of a live sequence     */
+  MDI_ERR_CTX = -3,   /* the call would grow a sequence beyond max_ctx                 */
+  MDI_ERR_NOMEM = -4, /* arena too small, or the KV page pool is exhausted             */
+  MDI_ERR_HIP = -5    /* a HIP runtime call or kernel launch reported an error         */
+} mdi_status;
+
+enum { MDI_NORM_LAYERNORM = 0, MDI_NORM_RMSNORM = 1 };
+enum { MDI_MLP_GELU_TANH = 0, MDI_MLP_GELU_ERF = 1, MDI_MLP_SWIGLU = 2 };
+enum { MDI_POS_LEARNED = 0, MDI_POS_ROPE = 1 };
+enum { MDI_F32 = 0, MDI_BF16 = 1 };
+enum { MDI_HAS_EMBED = 1u, MDI_HAS_HEAD = 2u };
+
+/*
+ * Model and cache geometry.  Passed by pointer (host), copied at create.
+ *
+ * dtype selects the storage type of weight matrices, embeddings, KV cache
+ * entries and of the activations crossing this boundary (acts_in / acts_out):
+ * MDI_F32 = IEEE binary32, MDI_BF16 = bfloat16 bit patterns.  Norm gains,
+ * norm biases and linear biases are always binary32.  Every accumulation
+ * (dot products, norms, softmax) is binary32 in both modes.
+ */
+typedef struct mdi_config {
+  uint32_t abi_version;    /* MDI_ABI_VERSION */
+  uint32_t n_layer;        /* layers of the WHOLE model (layer_hi is checked against it) */
+  uint32_t d_model;        /* embedding dimension; multiple of 8                        */
+  uint32_t n_head;         /* query heads H; n_head * head_dim may differ from d_model  */
+  uint32_t n_kv_head;      /* key/value heads K; H % K == 0 (grouped-query attention)    */
+  uint32_t head_dim;       /* h; multiple of 8, at most 256                             */
+  uint32_t d_ff;           /* MLP width F; multiple of 8                                */
+  uint32_t vocab;          /* V                                                         */
+  uint32_t max_ctx;        /* longest sequence (prompt + generated) a cache may hold     */
+  uint32_t max_seqs;       /* number of samples in flight = number of KV caches          */
+  uint32_t kv_page_tokens; /* tokens per KV page; 0 = 16                                */
+  uint32_t kv_pages;       /* pages in the pool; 0 = max_seqs * ceil(max_ctx / page)     */
+  uint32_t max_prefill;    /* longest first visit T; 0 = max_ctx (sizes prefill scratch) */
+  uint32_t norm_kind;      /* MDI_NORM_*                                                */
+  float norm_eps;
+  uint32_t mlp_kind;       /* MDI_MLP_*                                                 */
+  uint32_t pos_kind;       /* MDI_POS_*: learned absolute table added at embed, or RoPE  */
+  float rope_base;         /* RoPE: angle of pair i at position p is p * base^(-2i/h),
+                              pairing element i with element i + h/2 of each head        */
+  uint32_t has_bias;       /* linear layers carry biases (GPT-2 family)                 */
+  uint32_t tie_embed;      /* vocabulary projection shares the embedding matrix          */
+  uint32_t dtype;          /* MDI_F32 | MDI_BF16                                        */
+} mdi_config;
+
+/*
+ * Source weights of one decoder layer, device pointers, `[out_features,
+ * in_features]` row-major, contiguous, in cfg.dtype; vectors in binary32.
+ * Pointers that do not apply (biases when has_bias == 0, ln*_b for RMSNorm,
+ * w_gate for GELU MLPs) are NULL.  A NULL bias with has_bias == 1 means zero.
+ */
+typedef struct mdi_layer_weights {
+  const void *ln1_g, *ln1_b; /* [d] pre-attention norm                                  */
+  const void *wq, *wk, *wv;  /* [H*h, d], [K*h, d], [K*h, d]                            */
+  const void *bq, *bk, *bv;  /* [H*h], [K*h], [K*h]                                     */
+  const void *wo, *bo;       /* [d, H*h], [d]                                           */
+  const void *ln2_g, *ln2_b; /* [d] pre-MLP norm                                        */
+  const void *w_gate;        /* SwiGLU gate [F, d]                                      */
+  const void *w_up, *b_up;   /* SwiGLU up / GELU first matrix [F, d], [F]               */
+  const void *w_down, *b_down; /* [d, F], [d]                                           */
+} mdi_layer_weights;
+
+typedef struct mdi_weights {
+  const void *wte;     /* [V, d] token embedding; needed with MDI_HAS_EMBED, and with
+                          MDI_HAS_HEAD when tie_embed                                   */
+  const void *wpe;     /* [max_ctx, d] learned positions; MDI_HAS_EMBED + MDI_POS_LEARNED */
+  const void *lnf_g, *lnf_b; /* [d] final norm; MDI_HAS_HEAD                            */
+  const void *lm_head; /* [V, d]; MDI_HAS_HEAD and not tie_embed                        */
+  const mdi_layer_weights *layers; /* HOST array of layer_hi - layer_lo entries          */
+} mdi_weights;
+
+/*
+ * Size in bytes of the device arena a partition needs (packed weights, KV page
+ * pool, page tables, scratch).  arena_bytes: host pointer, written on MDI_OK.
+ */
+MDI_API mdi_status mdi_partition_bytes(const mdi_config *cfg, uint32_t layer_lo, uint32_t layer_hi,
+                               uint32_t flags, size_t *arena_bytes);
+
+/*
+ * Build the chunk of layers [layer_lo, layer_hi) (Sec. III-B).  flags:
+ * MDI_HAS_EMBED = inputs are int32 token ids (starter's input portion);
+ * MDI_HAS_HEAD = mdi_sample_greedy is available (starter's output portion).
+ * layer_lo == layer_hi is legal only with MDI_HAS_HEAD and without
+ * MDI_HAS_EMBED: an output portion without transformer blocks (Sec. III-E).
+ *
+ * The weights are copied, repacked, into `arena` (256-byte aligned device
+ * memory of at least mdi_partition_bytes() bytes, owned by the caller and kept
+ * alive until destroy); the copies are enqueued on `hip_stream`
+ * (a hipStream_t; NULL = the default stream), so the sources may be freed once
+ * that stream has drained.  *out receives the new handle.
+ */
+MDI_API mdi_status mdi_partition_create(const mdi_config *cfg, uint32_t layer_lo, uint32_t layer_hi,
+                                const mdi_weights *weights, uint32_t flags, void *arena,
+                                size_t arena_bytes, void *hip_stream, mdi_partition **out);
+
+/*
+ * First visit of sample seq_id (Alg. 1 round 0 / Alg. 2 "n-th KV cache is
+ * None"): initialise its cache and forward all T prompt positions.
+ * acts_in: int32[T] token ids with MDI_HAS_EMBED, else [T, d] in cfg.dtype.
+ * acts_out: [T, d] in cfg.dtype, row-major.  acts_in and acts_out must not overlap.
+ * Errors: MDI_ERR_STATE if the sequence is live, MDI_ERR_CTX if T > max_ctx,
+ * MDI_ERR_ARG if T == 0, T > max_prefill or seq_id >= max_seqs,
+ * MDI_ERR_NOMEM if the page pool cannot hold T more tokens.
+ */
+MDI_API mdi_status mdi_prefill(mdi_partition *part, uint32_t seq_id, const void *acts_in, uint32_t T,
+                       void *acts_out);
+
+/*
+ * Later visit (Sec. III-D): forward only the newest position through the local
+ * layers, reading and extending KV cache seq_id.  The position is implicit:
+ * the partition counts each sequence's length, as the paper's message carries
+ * only the sample id (Sec. III-E).
+ * act_in: int32[1] token id with MDI_HAS_EMBED, else [d] in cfg.dtype.
+ * act_out: [d] in cfg.dtype.
+ * Errors: MDI_ERR_STATE before the first visit, MDI_ERR_CTX when the cache is
+ * full, MDI_ERR_NOMEM when no page is free.
+ */
+MDI_API mdi_status mdi_decode_step(mdi_partition *part, uint32_t seq_id, const void *act_in,
+                           void *act_out);
+
+/*
+ * Output layers (Alg. 1 "process output layers ... get token", with greedy
+ * argmax in place of sampling): final norm, vocabulary projection, argmax
+ * (lowest index on exact ties).  Needs MDI_HAS_HEAD; touches no KV state.
+ * act_in: [d] in cfg.dtype (the last block's output for the newest position).
+ * token_out: int32[1].  logits_out: float[V] or NULL.
+ */
+MDI_API mdi_status mdi_sample_greedy(mdi_partition *part, uint32_t seq_id, const void *act_in,
+                             int32_t *token_out, float *logits_out);
+
+/* Drop sample seq_id's cache (its pages return to the pool); it may be prefilled again. */
+MDI_API mdi_status mdi_seq_reset(mdi_partition *part, uint32_t seq_id);
+
+/* Tokens currently cached for seq_id (0 = no cache yet).  len: host pointer. */
+MDI_API mdi_status mdi_seq_len(const mdi_partition *part, uint32_t seq_id, uint32_t *len);
+
+/*
+ * Bytes one decode step of this partition must move at context length ctx
+ * (packed weights + KV read for ctx positions + KV write + activation in/out),
+ * and the same for one mdi_sample_greedy call (ctx ignored when head != 0).
+ * bytes: host pointer.
+ */
+MDI_API mdi_status mdi_step_bytes(const mdi_partition *part, uint32_t ctx, int head, uint64_t *bytes);
+
+/*
+ * Measurement aid for the bandwidth roofline: time one kind of decode kernel in
+ * isolation with HIP events on the partition's stream.  One repetition launches
+ * the kernel once for every local layer in turn (so consecutive launches stream
+ * different weights and nothing is served from a cache), `reps` repetitions
+ * are timed back to back, and the call waits for them.  which: 1 = attention
+ * output projection, 2 = MLP up (+gate) projection, 3 = MLP down projection.
+ * They read and write only the partition's scratch vectors (no KV state).
+ * avg_us / bytes_per_launch: host pointers; mean duration of one launch in
+ * microseconds and the matrix bytes one launch must read.
+ */
+MDI_API mdi_status mdi_time_kernel(mdi_partition *part, int which, uint32_t reps, float *avg_us,
+                                   uint64_t *bytes_per_launch);
+
+/* Frees the host object; the arena stays with the caller. */
+MDI_API void mdi_partition_destroy(mdi_partition *part);
+
+MDI_API const char *mdi_strerror(mdi_status st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MDI_H */

@@ -280,19 +280,23 @@ def generate(parts, prompts, n_new, trace=None):
     at the end) owns the output layers.  Each sample gets exactly n_new new
     tokens, i.e. n_new + 1 rounds of Alg. 1; the token of the last round is not
     fed back.  Messages travel stage to stage in the order the starter emits
-    them, which is what FIFO queues on a ring give.  Returns (tokens, logits):
-    per sample the list of new token ids and the logits rows they came from.
+    them, which is what FIFO queues on a ring give.  Returns (tokens, logits,
+    hidden): per sample the list of new token ids, the logits rows they came
+    from, and the activations (last block's output) those were computed from.
     """
     head = parts[-1]
     blocks = [p for p in parts if p.hi > p.lo]
     toks = [[] for _ in prompts]
     logit_rows = [[] for _ in prompts]
+    hidden_rows = [[] for _ in prompts]
     inbox = {}                                         # sample -> activation back at the starter
     for k, n, r, runs_head, runs_fwd, is_prefill in starter_schedule(len(prompts), n_new + 1):
         if runs_head:
-            t, lg = head.sample_greedy(inbox.pop(n))
+            x = inbox.pop(n)
+            t, lg = head.sample_greedy(x)
             toks[n].append(t)
             logit_rows[n].append(lg)
+            hidden_rows[n].append(x)
         if runs_fwd:
             msg = prompts[n] if is_prefill else np.array([toks[n][-1]], dtype=np.int32)
             for si, p in enumerate(blocks):           # Alg. 2 on every stage of the ring
@@ -300,7 +304,7 @@ def generate(parts, prompts, n_new, trace=None):
                     trace.append((k, n, si, "prefill" if is_prefill else "decode"))
                 msg = p.prefill(n, msg) if is_prefill else p.decode_step(n, msg)
             inbox[n] = msg[-1] if is_prefill else msg
-    return toks, logit_rows
+    return toks, logit_rows, hidden_rows
 
 
 def pipeline_ticks(n_samples, n_nodes, n_rounds):

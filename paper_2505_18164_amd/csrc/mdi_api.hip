@@ -1,0 +1,488 @@
+// Host side of libmdi: the C ABI of include/mdi.h, arena carving, weight
+// repacking, per-sample cache bookkeeping and the launch sequences of a first
+// visit (prefill) and a later visit (decode step) of a sample (Alg. 1, Alg. 2).
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "mdi_internal.h"
+
+using namespace mdi;
+
+namespace {
+
+struct LayerPacked {
+  const float *ln1_g = nullptr, *ln1_b = nullptr, *ln2_g = nullptr, *ln2_b = nullptr;
+  const void *wqkv = nullptr, *wo = nullptr, *wup = nullptr, *wdown = nullptr;
+  const float *bqkv = nullptr, *bo = nullptr, *bup = nullptr, *bdown = nullptr;
+  char* kv = nullptr;  // this layer's pages: [page][K][2][pt][h]
+};
+
+// Walks the arena in a fixed order; with base == nullptr it only measures.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base((char*)b) {}
+  void* take(size_t bytes) {
+    off = (off + 255) & ~(size_t)255;
+    void* p = base ? base + off : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+}  // namespace
+
+struct mdi_partition {
+  mdi_config cfg;
+  uint32_t lo, hi, flags;
+  int n_local;
+  int esz;            // bytes per stored element
+  int pt, n_pages, pages_per_seq;
+  int Tm;             // longest first visit
+  hipStream_t stream;
+  std::vector<LayerPacked> layers;
+  const void *wte = nullptr, *wpe = nullptr, *lm_head = nullptr;
+  const float *lnf_g = nullptr, *lnf_b = nullptr;
+  float2* rope = nullptr;
+  int32_t* tables = nullptr;
+  // decode scratch
+  float *xres = nullptr, *q = nullptr, *o = nullptr, *u = nullptr, *part = nullptr, *amax_val = nullptr;
+  int* amax_idx = nullptr;
+  unsigned* counters = nullptr;  // [H] attention + [1] argmax
+  // prefill scratch
+  float *p_xres = nullptr, *p_qkv = nullptr, *p_q = nullptr;
+  void *p_xn = nullptr, *p_o = nullptr, *p_u = nullptr;
+  // host bookkeeping
+  std::vector<uint32_t> seq_len;
+  std::vector<int32_t> host_tables;   // mirror of `tables`, source of the async page-table copies
+  std::vector<int32_t> free_pages;
+  size_t arena_bytes = 0;
+};
+
+namespace {
+
+int act_kind(const mdi_config& c) { return c.dtype == MDI_BF16 ? IN_BF16 : IN_F32; }
+
+mdi_status check_config(const mdi_config* c, uint32_t lo, uint32_t hi, uint32_t flags) {
+  if (!c || c->abi_version != MDI_ABI_VERSION) return MDI_ERR_ARG;
+  if (!c->n_layer || !c->d_model || !c->n_head || !c->n_kv_head || !c->head_dim || !c->d_ff || !c->vocab) return MDI_ERR_ARG;
+  if (!c->max_ctx || !c->max_seqs) return MDI_ERR_ARG;
+  if (c->d_model % 8 || c->d_ff % 8) return MDI_ERR_ARG;
+  const uint32_t h = c->head_dim;
+  if (h < 8 || h > 256 || (h & (h - 1))) return MDI_ERR_ARG;   // a token's head vector maps to 2^k lanes
+  if (c->n_head % c->n_kv_head) return MDI_ERR_ARG;
+  if (c->norm_kind > MDI_NORM_RMSNORM || c->mlp_kind > MDI_MLP_SWIGLU || c->pos_kind > MDI_POS_ROPE) return MDI_ERR_ARG;
+  if (c->dtype > MDI_BF16) return MDI_ERR_ARG;
+  if (!(c->norm_eps >= 0.f)) return MDI_ERR_ARG;
+  if (c->pos_kind == MDI_POS_ROPE && !(c->rope_base > 0.f)) return MDI_ERR_ARG;
+  if (c->max_prefill > c->max_ctx) return MDI_ERR_ARG;
+  if (flags & ~(uint32_t)(MDI_HAS_EMBED | MDI_HAS_HEAD)) return MDI_ERR_ARG;
+  if (hi > c->n_layer || lo > hi) return MDI_ERR_ARG;
+  if (lo == hi && ((flags & MDI_HAS_EMBED) || !(flags & MDI_HAS_HEAD))) return MDI_ERR_ARG;
+  if ((flags & MDI_HAS_EMBED) && lo != 0) return MDI_ERR_ARG;  // token ids enter at layer 0 only
+  return MDI_OK;
+}
+
+// Lays the partition out in the arena.  Called with p->... unset pointers when measuring.
+size_t carve(mdi_partition* p, void* arena) {
+  const mdi_config& c = p->cfg;
+  const size_t B = p->esz, d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff, V = c.vocab;
+  const bool ln = c.norm_kind == MDI_NORM_LAYERNORM, swiglu = c.mlp_kind == MDI_MLP_SWIGLU;
+  const size_t nqkv = (H + 2 * K) * h, nup = swiglu ? 2 * F : F;
+  Carver cv(arena);
+  p->layers.assign(p->n_local, LayerPacked());
+  for (auto& L : p->layers) {
+    L.ln1_g = (float*)cv.take(d * 4);
+    if (ln) L.ln1_b = (float*)cv.take(d * 4);
+    L.wqkv = cv.take(nqkv * d * B);
+    if (c.has_bias) L.bqkv = (float*)cv.take(nqkv * 4);
+    L.wo = cv.take(d * H * h * B);
+    if (c.has_bias) L.bo = (float*)cv.take(d * 4);
+    L.ln2_g = (float*)cv.take(d * 4);
+    if (ln) L.ln2_b = (float*)cv.take(d * 4);
+    L.wup = cv.take(nup * d * B);
+    if (c.has_bias && !swiglu) L.bup = (float*)cv.take(F * 4);
+    L.wdown = cv.take(d * F * B);
+    if (c.has_bias && !swiglu) L.bdown = (float*)cv.take(d * 4);
+  }
+  const bool embed = p->flags & MDI_HAS_EMBED, head = p->flags & MDI_HAS_HEAD;
+  if (embed || (head && c.tie_embed)) p->wte = cv.take(V * d * B);
+  if (embed && c.pos_kind == MDI_POS_LEARNED) p->wpe = cv.take((size_t)c.max_ctx * d * B);
+  if (head) {
+    p->lnf_g = (float*)cv.take(d * 4);
+    if (ln) p->lnf_b = (float*)cv.take(d * 4);
+    p->lm_head = c.tie_embed ? p->wte : cv.take(V * d * B);
+    p->amax_val = (float*)cv.take(1024 * 4);
+    p->amax_idx = (int*)cv.take(1024 * 4);
+  }
+  p->counters = (unsigned*)cv.take((H + 1) * 4);
+  if (p->n_local) {
+    if (c.pos_kind == MDI_POS_ROPE) p->rope = (float2*)cv.take((size_t)c.max_ctx * (h / 2) * sizeof(float2));
+    const size_t layer_pool = (size_t)p->n_pages * K * 2 * p->pt * h * B;
+    for (auto& L : p->layers) L.kv = (char*)cv.take(layer_pool);
+    p->tables = (int32_t*)cv.take((size_t)c.max_seqs * p->pages_per_seq * 4);
+    p->xres = (float*)cv.take(d * 4);
+    p->q = (float*)cv.take(H * h * 4);
+    p->o = (float*)cv.take(H * h * 4);
+    p->u = (float*)cv.take(F * 4);
+    p->part = (float*)cv.take(H * kMaxSplits * (h + 2) * 4);
+    const size_t T = p->Tm;
+    p->p_xres = (float*)cv.take(T * d * 4);
+    p->p_xn = cv.take(T * d * B);
+    p->p_qkv = (float*)cv.take(T * nqkv * 4);
+    p->p_q = (float*)cv.take(T * H * h * 4);
+    p->p_o = cv.take(T * H * h * B);
+    p->p_u = cv.take(T * F * B);
+  }
+  return (cv.off + 255) & ~(size_t)255;
+}
+
+void init_geometry(mdi_partition* p, const mdi_config* cfg, uint32_t lo, uint32_t hi, uint32_t flags) {
+  p->cfg = *cfg;
+  p->lo = lo; p->hi = hi; p->flags = flags;
+  p->n_local = (int)(hi - lo);
+  p->esz = cfg->dtype == MDI_BF16 ? 2 : 4;
+  p->pt = cfg->kv_page_tokens ? (int)cfg->kv_page_tokens : 16;
+  p->pages_per_seq = ((int)cfg->max_ctx + p->pt - 1) / p->pt;
+  p->n_pages = cfg->kv_pages ? (int)cfg->kv_pages : (int)cfg->max_seqs * p->pages_per_seq;
+  p->Tm = cfg->max_prefill ? (int)cfg->max_prefill : (int)cfg->max_ctx;
+}
+
+// device-to-device copy of a [rows, cols] matrix into rows r*mul + off of dst
+void put_rows(mdi_partition* p, const void* src, const void* dst, size_t rows, size_t cols, int esz, long mul = 1, long off = 0) {
+  if (!src || !dst) return;
+  launch_copy_rows(p->stream, esz, src, const_cast<void*>(dst), (long)rows, (long)cols, mul, off);
+}
+
+mdi_status hip_status() { return hipGetLastError() == hipSuccess ? MDI_OK : MDI_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+mdi_status mdi_partition_bytes(const mdi_config* cfg, uint32_t layer_lo, uint32_t layer_hi, uint32_t flags, size_t* arena_bytes) {
+  if (!arena_bytes) return MDI_ERR_ARG;
+  const mdi_status st = check_config(cfg, layer_lo, layer_hi, flags);
+  if (st != MDI_OK) return st;
+  mdi_partition tmp;
+  init_geometry(&tmp, cfg, layer_lo, layer_hi, flags);
+  *arena_bytes = carve(&tmp, nullptr);
+  return MDI_OK;
+}
+
+mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32_t layer_hi, const mdi_weights* w,
+                                uint32_t flags, void* arena, size_t arena_bytes, void* hip_stream, mdi_partition** out) {
+  if (!out) return MDI_ERR_ARG;
+  *out = nullptr;
+  mdi_status st = check_config(cfg, layer_lo, layer_hi, flags);
+  if (st != MDI_OK) return st;
+  if (!w || !arena || ((uintptr_t)arena & 255)) return MDI_ERR_ARG;
+  const bool embed = flags & MDI_HAS_EMBED, head = flags & MDI_HAS_HEAD;
+  const bool ln = cfg->norm_kind == MDI_NORM_LAYERNORM, swiglu = cfg->mlp_kind == MDI_MLP_SWIGLU;
+  if (layer_hi > layer_lo && !w->layers) return MDI_ERR_ARG;
+  if ((embed || (head && cfg->tie_embed)) && !w->wte) return MDI_ERR_ARG;
+  if (embed && cfg->pos_kind == MDI_POS_LEARNED && !w->wpe) return MDI_ERR_ARG;
+  if (head && (!w->lnf_g || (!cfg->tie_embed && !w->lm_head))) return MDI_ERR_ARG;
+  for (uint32_t i = 0; i < layer_hi - layer_lo; ++i) {
+    const mdi_layer_weights& s = w->layers[i];
+    if (!s.ln1_g || !s.ln2_g || !s.wq || !s.wk || !s.wv || !s.wo || !s.w_up || !s.w_down) return MDI_ERR_ARG;
+    if (swiglu && !s.w_gate) return MDI_ERR_ARG;
+  }
+  mdi_partition* p = new (std::nothrow) mdi_partition();
+  if (!p) return MDI_ERR_NOMEM;
+  init_geometry(p, cfg, layer_lo, layer_hi, flags);
+  p->stream = (hipStream_t)hip_stream;
+  const size_t need = carve(p, arena);
+  if (need > arena_bytes) { delete p; return MDI_ERR_NOMEM; }
+  p->arena_bytes = arena_bytes;
+
+  const mdi_config& c = p->cfg;
+  const size_t d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff, V = c.vocab;
+  const int B = p->esz;
+  for (int i = 0; i < p->n_local; ++i) {
+    const mdi_layer_weights& s = w->layers[i];
+    LayerPacked& L = p->layers[i];
+    put_rows(p, s.ln1_g, L.ln1_g, 1, d, 4);
+    put_rows(p, s.ln2_g, L.ln2_g, 1, d, 4);
+    if (ln) {
+      if (s.ln1_b) put_rows(p, s.ln1_b, L.ln1_b, 1, d, 4); else launch_fill_f32(p->stream, (float*)L.ln1_b, d, 0.f);
+      if (s.ln2_b) put_rows(p, s.ln2_b, L.ln2_b, 1, d, 4); else launch_fill_f32(p->stream, (float*)L.ln2_b, d, 0.f);
+    }
+    // fused QKV matrix: query rows, then key rows, then value rows
+    char* wqkv = (char*)L.wqkv;
+    put_rows(p, s.wq, wqkv, H * h, d, B);
+    put_rows(p, s.wk, wqkv + H * h * d * B, K * h, d, B);
+    put_rows(p, s.wv, wqkv + (H + K) * h * d * B, K * h, d, B);
+    put_rows(p, s.wo, L.wo, d, H * h, B);
+    if (swiglu) {   // gate and up rows interleaved: row 2f = gate_f, row 2f+1 = up_f
+      put_rows(p, s.w_gate, L.wup, F, d, B, 2, 0);
+      put_rows(p, s.w_up, L.wup, F, d, B, 2, 1);
+    } else {
+      put_rows(p, s.w_up, L.wup, F, d, B);
+    }
+    put_rows(p, s.w_down, L.wdown, d, F, B);
+    if (c.has_bias) {
+      float* bq = (float*)L.bqkv;
+      launch_fill_f32(p->stream, bq, (H + 2 * K) * h, 0.f);
+      put_rows(p, s.bq, bq, 1, H * h, 4);
+      put_rows(p, s.bk, bq + H * h, 1, K * h, 4);
+      put_rows(p, s.bv, bq + (H + K) * h, 1, K * h, 4);
+      launch_fill_f32(p->stream, (float*)L.bo, d, 0.f);
+      put_rows(p, s.bo, L.bo, 1, d, 4);
+      if (!swiglu) {
+        launch_fill_f32(p->stream, (float*)L.bup, F, 0.f);
+        put_rows(p, s.b_up, L.bup, 1, F, 4);
+        launch_fill_f32(p->stream, (float*)L.bdown, d, 0.f);
+        put_rows(p, s.b_down, L.bdown, 1, d, 4);
+      }
+    }
+  }
+  if (p->wte) put_rows(p, w->wte, p->wte, V, d, B);
+  if (p->wpe) put_rows(p, w->wpe, p->wpe, c.max_ctx, d, B);
+  if (head) {
+    put_rows(p, w->lnf_g, p->lnf_g, 1, d, 4);
+    if (ln) { if (w->lnf_b) put_rows(p, w->lnf_b, p->lnf_b, 1, d, 4); else launch_fill_f32(p->stream, (float*)p->lnf_b, d, 0.f); }
+    if (!c.tie_embed) put_rows(p, w->lm_head, p->lm_head, V, d, B);
+  }
+  launch_fill_u32(p->stream, p->counters, H + 1, 0u);
+  if (p->rope) launch_rope_table(p->stream, p->rope, (int)c.max_ctx, (int)h, (double)c.rope_base);
+
+  p->seq_len.assign(c.max_seqs, 0u);
+  if (p->n_local) {
+    p->host_tables.assign((size_t)c.max_seqs * p->pages_per_seq, 0);
+    launch_fill_u32(p->stream, (uint32_t*)p->tables, (long)p->host_tables.size(), 0u);
+    p->free_pages.resize(p->n_pages);
+    for (int i = 0; i < p->n_pages; ++i) p->free_pages[i] = p->n_pages - 1 - i;   // page 0 is handed out first
+  }
+  st = hip_status();
+  if (st != MDI_OK) { delete p; return st; }
+  *out = p;
+  return MDI_OK;
+}
+
+mdi_status mdi_prefill(mdi_partition* p, uint32_t seq, const void* acts_in, uint32_t T, void* acts_out) {
+  if (!p || !acts_in || !acts_out || !p->n_local) return MDI_ERR_ARG;
+  const mdi_config& c = p->cfg;
+  if (seq >= c.max_seqs || T == 0) return MDI_ERR_ARG;
+  if (p->seq_len[seq]) return MDI_ERR_STATE;
+  if (T > c.max_ctx) return MDI_ERR_CTX;
+  if (T > (uint32_t)p->Tm) return MDI_ERR_ARG;
+  const int need = ((int)T + p->pt - 1) / p->pt;
+  if ((int)p->free_pages.size() < need) return MDI_ERR_NOMEM;
+  int32_t* row = p->host_tables.data() + (size_t)seq * p->pages_per_seq;
+  for (int i = 0; i < need; ++i) { row[i] = p->free_pages.back(); p->free_pages.pop_back(); }
+  int32_t* drow = p->tables + (size_t)seq * p->pages_per_seq;
+  if (hipMemcpyAsync(drow, row, (size_t)need * 4, hipMemcpyHostToDevice, p->stream) != hipSuccess) return MDI_ERR_HIP;
+
+  hipStream_t s = p->stream;
+  const int d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff;
+  const int ak = act_kind(c);
+  const bool embed = p->flags & MDI_HAS_EMBED, swiglu = c.mlp_kind == MDI_MLP_SWIGLU;
+  RowsInArgs ri{acts_in, embed ? IN_TOKEN : ak, p->wte, p->wpe, (int)c.dtype, (int)T, d, p->p_xres};
+  launch_rows_input(s, ri);
+  for (int i = 0; i < p->n_local; ++i) {
+    const LayerPacked& L = p->layers[i];
+    NormRowsArgs n1{p->p_xres, (int)T, d, (int)c.norm_kind, L.ln1_g, L.ln1_b, c.norm_eps, p->p_xn, ak};
+    launch_norm_rows(s, n1);
+    GemmArgs g1{p->p_xn, L.wqkv, L.bqkv, (int)T, (H + 2 * K) * h, d, p->p_qkv, nullptr};
+    launch_gemm(s, c.dtype, GEPI_F32_BIAS, g1);
+    RopeScatterArgs rs{p->p_qkv, (int)T, H, K, h, p->pt, p->rope, p->p_q, L.kv, drow, (int)c.dtype};
+    launch_rope_scatter(s, rs);
+    AttnArgs at{};
+    at.q = p->p_q; at.q_stride = (long)H * h; at.pool = L.kv; at.table = drow;
+    at.ctx0 = 1; at.n_q = (int)T; at.H = H; at.K = K; at.h = h; at.pt = p->pt;
+    at.chunk = (int)c.max_ctx; at.n_splits = 1; at.scale = 1.f / sqrtf((float)h);
+    at.part = p->part; at.counters = p->counters; at.out = p->p_o; at.out_stride = (long)H * h; at.out_kind = ak;
+    launch_attn(s, c.dtype, at);
+    GemmArgs g2{p->p_o, L.wo, L.bo, (int)T, d, H * h, p->p_xres, nullptr};
+    launch_gemm(s, c.dtype, GEPI_RESID, g2);
+    NormRowsArgs n2{p->p_xres, (int)T, d, (int)c.norm_kind, L.ln2_g, L.ln2_b, c.norm_eps, p->p_xn, ak};
+    launch_norm_rows(s, n2);
+    GemmArgs g3{p->p_xn, L.wup, L.bup, (int)T, swiglu ? 2 * F : F, d, nullptr, p->p_u};
+    launch_gemm(s, c.dtype, swiglu ? GEPI_SWIGLU : (c.mlp_kind == MDI_MLP_GELU_TANH ? GEPI_GELU_TANH : GEPI_GELU_ERF), g3);
+    GemmArgs g4{p->p_u, L.wdown, L.bdown, (int)T, d, F, p->p_xres, i == p->n_local - 1 ? acts_out : nullptr};
+    launch_gemm(s, c.dtype, GEPI_RESID, g4);
+  }
+  p->seq_len[seq] = T;
+  return hip_status();
+}
+
+mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, void* act_out) {
+  if (!p || !act_in || !act_out || !p->n_local) return MDI_ERR_ARG;
+  const mdi_config& c = p->cfg;
+  if (seq >= c.max_seqs) return MDI_ERR_ARG;
+  const int len = (int)p->seq_len[seq];
+  if (!len) return MDI_ERR_STATE;
+  if ((uint32_t)len + 1 > c.max_ctx) return MDI_ERR_CTX;
+  int32_t* row = p->host_tables.data() + (size_t)seq * p->pages_per_seq;
+  int32_t* drow = p->tables + (size_t)seq * p->pages_per_seq;
+  const int pidx = len / p->pt, slot = len % p->pt;
+  int32_t* new_entry = nullptr;
+  if (slot == 0) {
+    if (p->free_pages.empty()) return MDI_ERR_NOMEM;
+    row[pidx] = p->free_pages.back();
+    p->free_pages.pop_back();
+    new_entry = drow + pidx;
+  }
+  const int page = row[pidx];
+
+  hipStream_t s = p->stream;
+  const int d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff;
+  const int ak = act_kind(c);
+  const bool embed = p->flags & MDI_HAS_EMBED, swiglu = c.mlp_kind == MDI_MLP_SWIGLU;
+  InputArgs ia{act_in, embed ? IN_TOKEN : ak, p->wte, p->wpe, (int)c.dtype, len, d, p->xres, new_entry, page};
+  launch_input(s, ia);
+
+  const int ctx = len + 1;
+  // context split: enough workgroups to cover the chip, at least 64 tokens each
+  int want = 512 / H * (H / K);   // splits so that (H/G) * splits is about 512 workgroups
+  want = std::max(1, std::min(want, kMaxSplits));
+  int chunk = (ctx + want - 1) / want;
+  chunk = std::max(64, (chunk + 63) / 64 * 64);
+  const int n_splits = (ctx + chunk - 1) / chunk;
+  const long pt_h = (long)p->pt * h;
+
+  for (int i = 0; i < p->n_local; ++i) {
+    const LayerPacked& L = p->layers[i];
+    GemvArgs qa{};
+    qa.W = L.wqkv; qa.bias = L.bqkv; qa.N = (H + 2 * K) * h; qa.Kd = d;
+    qa.x = p->xres; qa.x_kind = IN_F32; qa.norm_kind = c.norm_kind; qa.g = L.ln1_g; qa.b = L.ln1_b; qa.eps = c.norm_eps;
+    qa.out = p->q; qa.H = H; qa.K = K; qa.h = h;
+    qa.rope = p->rope ? p->rope + (size_t)len * (h / 2) : nullptr;
+    qa.kv_tok = L.kv + ((size_t)page * K * 2 * pt_h + (size_t)slot * h) * p->esz;
+    qa.pt_h = pt_h;
+    launch_gemv(s, c.dtype, PRO_NORM, EPI_QKV, qa);
+
+    AttnArgs at{};
+    at.q = p->q; at.q_stride = 0; at.pool = L.kv; at.table = drow;
+    at.ctx0 = ctx; at.n_q = 1; at.H = H; at.K = K; at.h = h; at.pt = p->pt;
+    at.chunk = chunk; at.n_splits = n_splits; at.scale = 1.f / sqrtf((float)h);
+    at.part = p->part; at.counters = p->counters; at.out = p->o; at.out_stride = 0; at.out_kind = IN_F32;
+    launch_attn(s, c.dtype, at);
+
+    GemvArgs oa{};
+    oa.W = L.wo; oa.bias = L.bo; oa.N = d; oa.Kd = H * h;
+    oa.x = p->o; oa.x_kind = IN_F32;
+    oa.out = p->xres; oa.resid = p->xres;
+    launch_gemv(s, c.dtype, PRO_COPY, EPI_RESID, oa);
+
+    GemvArgs ua{};
+    ua.W = L.wup; ua.bias = L.bup; ua.N = swiglu ? 2 * F : F; ua.Kd = d;
+    ua.x = p->xres; ua.x_kind = IN_F32; ua.norm_kind = c.norm_kind; ua.g = L.ln2_g; ua.b = L.ln2_b; ua.eps = c.norm_eps;
+    ua.out = p->u;
+    launch_gemv(s, c.dtype, PRO_NORM, swiglu ? EPI_SWIGLU : (c.mlp_kind == MDI_MLP_GELU_TANH ? EPI_GELU_TANH : EPI_GELU_ERF), ua);
+
+    GemvArgs da{};
+    da.W = L.wdown; da.bias = L.bdown; da.N = d; da.Kd = F;
+    da.x = p->u; da.x_kind = IN_F32;
+    da.out = p->xres; da.resid = p->xres;
+    if (i == p->n_local - 1) { da.act_out = act_out; da.act_kind = ak; }
+    launch_gemv(s, c.dtype, PRO_COPY, EPI_RESID, da);
+  }
+  p->seq_len[seq] = (uint32_t)ctx;
+  return hip_status();
+}
+
+mdi_status mdi_sample_greedy(mdi_partition* p, uint32_t seq, const void* act_in, int32_t* token_out, float* logits_out) {
+  if (!p || !act_in || !token_out) return MDI_ERR_ARG;
+  if (!(p->flags & MDI_HAS_HEAD)) return MDI_ERR_STATE;
+  const mdi_config& c = p->cfg;
+  if (seq >= c.max_seqs) return MDI_ERR_ARG;
+  GemvArgs a{};
+  a.W = p->lm_head; a.N = (int)c.vocab; a.Kd = (int)c.d_model;
+  a.x = act_in; a.x_kind = act_kind(c); a.norm_kind = c.norm_kind; a.g = p->lnf_g; a.b = p->lnf_b; a.eps = c.norm_eps;
+  a.out = logits_out; a.amax_val = p->amax_val; a.amax_idx = p->amax_idx;
+  a.counter = p->counters + c.n_head; a.token_out = token_out;
+  launch_gemv(p->stream, c.dtype, PRO_NORM, EPI_LOGITS, a);
+  return hip_status();
+}
+
+mdi_status mdi_seq_reset(mdi_partition* p, uint32_t seq) {
+  if (!p || seq >= p->cfg.max_seqs) return MDI_ERR_ARG;
+  const int len = (int)p->seq_len[seq];
+  if (len && p->n_local) {
+    const int used = (len + p->pt - 1) / p->pt;
+    const int32_t* row = p->host_tables.data() + (size_t)seq * p->pages_per_seq;
+    for (int i = used - 1; i >= 0; --i) p->free_pages.push_back(row[i]);
+  }
+  p->seq_len[seq] = 0;
+  return MDI_OK;
+}
+
+mdi_status mdi_seq_len(const mdi_partition* p, uint32_t seq, uint32_t* len) {
+  if (!p || !len || seq >= p->cfg.max_seqs) return MDI_ERR_ARG;
+  *len = p->seq_len[seq];
+  return MDI_OK;
+}
+
+mdi_status mdi_step_bytes(const mdi_partition* p, uint32_t ctx, int head, uint64_t* bytes) {
+  if (!p || !bytes) return MDI_ERR_ARG;
+  const mdi_config& c = p->cfg;
+  const uint64_t B = p->esz, d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff, V = c.vocab;
+  if (head) {
+    if (!(p->flags & MDI_HAS_HEAD)) return MDI_ERR_STATE;
+    *bytes = V * d * B + d * B + 4;
+    return MDI_OK;
+  }
+  const uint64_t mlp = (c.mlp_kind == MDI_MLP_SWIGLU ? 3 : 2) * d * F;
+  const uint64_t layer = ((H + 2 * K) * h * d + d * H * h + mlp) * B;
+  const uint64_t kv_tok = 2 * K * h * B;
+  *bytes = (uint64_t)p->n_local * (layer + kv_tok * ctx + kv_tok) + 2 * d * B;
+  return MDI_OK;
+}
+
+mdi_status mdi_time_kernel(mdi_partition* p, int which, uint32_t reps, float* avg_us, uint64_t* bytes_per_launch) {
+  if (!p || !avg_us || !bytes_per_launch || !p->n_local || !reps || which < 1 || which > 3) return MDI_ERR_ARG;
+  const mdi_config& c = p->cfg;
+  const int d = c.d_model, H = c.n_head, h = c.head_dim, F = c.d_ff;
+  const bool swiglu = c.mlp_kind == MDI_MLP_SWIGLU;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return MDI_ERR_HIP;
+  auto once = [&]() {
+    for (int i = 0; i < p->n_local; ++i) {
+      const LayerPacked& L = p->layers[i];
+      GemvArgs a{};
+      if (which == 1) {
+        a.W = L.wo; a.bias = L.bo; a.N = d; a.Kd = H * h; a.x = p->o; a.x_kind = IN_F32; a.out = p->xres; a.resid = p->xres;
+        launch_gemv(p->stream, c.dtype, PRO_COPY, EPI_RESID, a);
+      } else if (which == 2) {
+        a.W = L.wup; a.bias = L.bup; a.N = swiglu ? 2 * F : F; a.Kd = d; a.x = p->xres; a.x_kind = IN_F32;
+        a.norm_kind = c.norm_kind; a.g = L.ln2_g; a.b = L.ln2_b; a.eps = c.norm_eps; a.out = p->u;
+        launch_gemv(p->stream, c.dtype, PRO_NORM, swiglu ? EPI_SWIGLU : (c.mlp_kind == MDI_MLP_GELU_TANH ? EPI_GELU_TANH : EPI_GELU_ERF), a);
+      } else {
+        a.W = L.wdown; a.bias = L.bdown; a.N = d; a.Kd = F; a.x = p->u; a.x_kind = IN_F32; a.out = p->xres; a.resid = p->xres;
+        launch_gemv(p->stream, c.dtype, PRO_COPY, EPI_RESID, a);
+      }
+    }
+  };
+  once();   // warm-up
+  bool ok = hipEventRecord(e0, p->stream) == hipSuccess;
+  for (uint32_t r = 0; r < reps; ++r) once();
+  ok = ok && hipEventRecord(e1, p->stream) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+  float ms = 0.f;
+  ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (!ok) return MDI_ERR_HIP;
+  *avg_us = ms * 1000.f / ((float)reps * (float)p->n_local);
+  const uint64_t B = p->esz;
+  *bytes_per_launch = which == 1 ? (uint64_t)d * H * h * B : which == 2 ? (uint64_t)(swiglu ? 2 : 1) * F * d * B : (uint64_t)d * F * B;
+  return hip_status();
+}
+
+void mdi_partition_destroy(mdi_partition* p) { delete p; }
+
+const char* mdi_strerror(mdi_status st) {
+  switch (st) {
+    case MDI_OK: return "ok";
+    case MDI_ERR_ARG: return "invalid argument";
+    case MDI_ERR_STATE: return "call not valid in the sequence's or partition's state";
+    case MDI_ERR_CTX: return "context length exceeded";
+    case MDI_ERR_NOMEM: return "arena too small or KV page pool exhausted";
+    case MDI_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,125 @@
+// Internal declarations shared by the translation units of libmdi.
+// Each .hip file owns its kernels and exposes host-side launchers declared here.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mdi.h"
+
+namespace mdi {
+
+constexpr int kBlock = 256;          // threads per workgroup (4 wavefronts of 64)
+constexpr int kWave = 64;
+constexpr int kMaxSplits = 64;       // context splits of single-query attention
+
+typedef uint16_t bf16_t;             // bfloat16 bit pattern
+
+// ---- input of a step ------------------------------------------------------
+enum InKind { IN_TOKEN = 0, IN_F32 = 1, IN_BF16 = 2 };
+
+// ---- weight-streaming GEMV family (decode; Sec. III-D: one position per visit)
+enum Prologue { PRO_COPY = 0, PRO_NORM = 1 };
+enum Epilogue { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_GELU_TANH = 3, EPI_GELU_ERF = 4, EPI_LOGITS = 5 };
+
+struct GemvArgs {
+  const void* W;        // [N, Kd] row-major, storage dtype
+  const float* bias;    // [N] or nullptr
+  int N, Kd;
+  // prologue: vector of Kd values, fp32 or bf16, optionally normalised
+  const void* x;
+  int x_kind;           // IN_F32 | IN_BF16
+  int norm_kind;        // MDI_NORM_*, used when the kernel's prologue is PRO_NORM
+  const float* g;       // norm gain [Kd]
+  const float* b;       // norm bias [Kd] or nullptr
+  float eps;
+  // epilogue
+  float* out;           // EPI_QKV: q[H*h]; EPI_RESID: x (updated in place); SWIGLU/GELU: u[F]; LOGITS: logits or nullptr
+  const float* resid;   // EPI_RESID: residual input [N]
+  void* act_out;        // EPI_RESID: optional copy in storage dtype [N] (hand-off to the next stage)
+  int act_kind;         // IN_F32 | IN_BF16
+  // EPI_QKV
+  int H, K, h;
+  const float2* rope;   // (cos, sin)[h/2] of the current position, or nullptr
+  void* kv_tok;         // address of K[kv head 0][slot][0] for this layer/page; V follows at +pt_h elements
+  long pt_h;            // page_tokens * head_dim
+  // EPI_LOGITS
+  float* amax_val;      // [gridDim.x] per-workgroup best
+  int* amax_idx;
+  unsigned* counter;    // arrival counter, zero between calls
+  int32_t* token_out;
+};
+
+void launch_gemv(hipStream_t s, int dtype, int pro, int epi, const GemvArgs& a);
+int gemv_grid(int N);   // workgroups launch_gemv uses for N rows (sizes the argmax partials)
+
+struct InputArgs {
+  const void* in; int in_kind;       // token id / fp32 / bf16 vector
+  const void* wte; const void* wpe;  // storage dtype
+  int dtype; int pos; int d;
+  float* xres;                       // [d] fp32 residual stream
+  int32_t* table_entry; int new_page; // page-table slot to fill before attention (or nullptr)
+};
+void launch_input(hipStream_t s, const InputArgs& a);
+
+struct AttnArgs {
+  const float* q;          // [n_q][H*h] fp32, rotated
+  long q_stride;
+  const void* pool;        // this layer's pages: [page][K][2][pt][h], storage dtype
+  const int32_t* table;    // this sequence's page ids
+  int ctx0;                // keys visible to query row 0 (query row y sees ctx0 + y)
+  int n_q;                 // query rows (1 for decode)
+  int H, K, h, pt;
+  int chunk, n_splits;     // context split (n_splits == 1 when n_q > 1)
+  float scale;
+  float* part;             // [H][kMaxSplits][h + 2] split partials
+  unsigned* counters;      // [H] arrival counters, zero between calls
+  void* out;               // [n_q][H*h]
+  long out_stride;
+  int out_kind;            // IN_F32 | IN_BF16
+};
+void launch_attn(hipStream_t s, int dtype, const AttnArgs& a);
+
+// ---- prefill (first visit: T positions at once; Alg. 2) -------------------
+struct RowsInArgs {
+  const void* in; int in_kind; const void* wte; const void* wpe; int dtype;
+  int T, d; float* xres;
+};
+void launch_rows_input(hipStream_t s, const RowsInArgs& a);
+
+struct NormRowsArgs {
+  const float* x; int T, d; int norm_kind; const float* g; const float* b; float eps;
+  void* out; int out_kind;
+};
+void launch_norm_rows(hipStream_t s, const NormRowsArgs& a);
+
+enum GemmEpi { GEPI_F32_BIAS = 0, GEPI_RESID = 1, GEPI_SWIGLU = 2, GEPI_GELU_TANH = 3, GEPI_GELU_ERF = 4 };
+struct GemmArgs {
+  const void* A;     // [T, Kd] storage dtype
+  const void* W;     // [N, Kd] storage dtype
+  const float* bias; // [N] or nullptr
+  int T, N, Kd;
+  float* out_f32;    // GEPI_F32_BIAS: [T, N]; GEPI_RESID: residual stream [T, N], updated in place
+  void* out_act;     // SWIGLU: [T, N/2]; GELU: [T, N]; RESID: optional hand-off copy [T, N]; storage dtype
+};
+void launch_gemm(hipStream_t s, int dtype, int epi, const GemmArgs& a);
+
+struct RopeScatterArgs {
+  const float* qkv;  // [T, (H+2K)h] fp32
+  int T, H, K, h, pt;
+  const float2* rope;     // [max_ctx][h/2] or nullptr
+  float* q_out;           // [T, H*h] fp32
+  void* pool;             // this layer's pages
+  const int32_t* table;
+  int dtype;
+};
+void launch_rope_scatter(hipStream_t s, const RopeScatterArgs& a);
+
+// ---- set-up ---------------------------------------------------------------
+void launch_rope_table(hipStream_t s, float2* table, int max_ctx, int h, double base);
+// dst[r*dst_stride_rows + ...]: copy `rows` rows of `cols` elements, dst row = r*row_mul + row_off
+void launch_copy_rows(hipStream_t s, int elem_bytes, const void* src, void* dst, long rows, long cols, long row_mul, long row_off);
+void launch_fill_f32(hipStream_t s, float* dst, long n, float v);
+void launch_fill_u32(hipStream_t s, uint32_t* dst, long n, uint32_t v);
+
+}  // namespace mdi

@@ -1,0 +1,320 @@
+// First-visit kernels: all T prompt positions of a sample go through the local
+// layers at once and fill the sample's KV cache (Alg. 1 round 0, Alg. 2 "first
+// iteration for current sample").  With T rows the linear layers are dense
+// contractions, so in bf16 mode they run on the matrix cores
+// (v_mfma_f32_32x32x16_bf16, LDS-tiled); fp32 mode keeps exact fp32 products on
+// the vector ALUs.
+#include "device_utils.h"
+
+namespace mdi {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_rows_input(RowsInArgs a) {
+  const int t = blockIdx.x;
+  float* xr = a.xres + (long)t * a.d;
+  if (a.in_kind == IN_TOKEN) {
+    const long tok = ((const int32_t*)a.in)[t];
+    const int wk = a.dtype == MDI_BF16 ? IN_BF16 : IN_F32;
+    for (int i = threadIdx.x; i < a.d; i += kBlock) {
+      float v = load_kind(a.wte, wk, tok * a.d + i);
+      if (a.wpe) v += load_kind(a.wpe, wk, (long)t * a.d + i);
+      xr[i] = v;
+    }
+  } else {
+    for (int i = threadIdx.x; i < a.d; i += kBlock) xr[i] = load_kind(a.in, a.in_kind, (long)t * a.d + i);
+  }
+}
+void launch_rows_input(hipStream_t s, const RowsInArgs& a) {
+  hipLaunchKernelGGL(k_rows_input, dim3(a.T), dim3(kBlock), 0, s, a);
+}
+
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_norm_rows(NormRowsArgs a) {
+  __shared__ float red[8];
+  const int t = blockIdx.x, d = a.d;
+  const float* x = a.x + (long)t * d;
+  float mean = 0.f, rstd;
+  if (a.norm_kind == MDI_NORM_LAYERNORM) {
+    float s = 0.f;
+    for (int i = threadIdx.x; i < d; i += kBlock) s += x[i];
+    mean = block_sum(s, red) / (float)d;
+    float s2 = 0.f;
+    for (int i = threadIdx.x; i < d; i += kBlock) { const float c = x[i] - mean; s2 += c * c; }
+    rstd = 1.f / sqrtf(block_sum(s2, red) / (float)d + a.eps);
+  } else {
+    float s2 = 0.f;
+    for (int i = threadIdx.x; i < d; i += kBlock) s2 += x[i] * x[i];
+    rstd = 1.f / sqrtf(block_sum(s2, red) / (float)d + a.eps);
+  }
+  for (int i = threadIdx.x; i < d; i += kBlock) {
+    float v = (x[i] - mean) * rstd * a.g[i];
+    if (a.b) v += a.b[i];
+    store_kind(a.out, a.out_kind, (long)t * d + i, v);
+  }
+}
+void launch_norm_rows(hipStream_t s, const NormRowsArgs& a) {
+  hipLaunchKernelGGL(k_norm_rows, dim3(a.T), dim3(kBlock), 0, s, a);
+}
+
+// ---------------------------------------------------------------------------
+// Epilogue shared by both GEMM kernels.  (t, n) is the output coordinate, v the
+// accumulated dot product, partner the value of column n^1 (SwiGLU pairs).
+template <int EPI>
+__device__ __forceinline__ void gemm_store(const GemmArgs& a, int out_kind, int t, int n, float v, float partner) {
+  if (t >= a.T || n >= a.N) return;
+  if (EPI == GEPI_SWIGLU) {
+    if (n & 1) return;
+    store_kind(a.out_act, out_kind, (long)t * (a.N >> 1) + (n >> 1), silu_f(v) * partner);
+    return;
+  }
+  if (a.bias) v += a.bias[n];
+  const long o = (long)t * a.N + n;
+  if (EPI == GEPI_F32_BIAS) {
+    a.out_f32[o] = v;
+  } else if (EPI == GEPI_RESID) {
+    v += a.out_f32[o];
+    a.out_f32[o] = v;
+    if (a.out_act) store_kind(a.out_act, out_kind, o, v);
+  } else if (EPI == GEPI_GELU_TANH) {
+    store_kind(a.out_act, out_kind, o, gelu_tanh_f(v));
+  } else {
+    store_kind(a.out_act, out_kind, o, gelu_erf_f(v));
+  }
+}
+
+// ---------------------------------------------------------------------------
+// bf16 GEMM on MFMA: C[T, N] = A[T, Kd] * W[N, Kd]^T, fp32 accumulate.
+// Workgroup tile 128 (tokens) x 128 (weight rows), K step 64; four wavefronts in
+// a 2 x 2 arrangement, each owning 64 x 64 = 2 x 2 MFMA tiles of 32 x 32.
+// Both operands are K-contiguous, so a lane's MFMA fragment (8 consecutive k of
+// one row) is one 16-byte LDS read; LDS rows are padded by 16 bytes to spread
+// the banks.  Global loads for step k+1 are issued into registers before the
+// MFMAs of step k.
+constexpr int BM = 128, BN = 128, BK = 64, LDS_STRIDE = BK + 8;
+
+template <int EPI>
+__global__ __launch_bounds__(kBlock) void k_gemm_bf16(GemmArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16_t As[BM * LDS_STRIDE];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LDS_STRIDE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const bf16_t* A = (const bf16_t*)a.A;
+  const bf16_t* W = (const bf16_t*)a.W;
+  const int Kd = a.Kd;
+
+  // each thread moves 4 + 4 pieces of 16 bytes per K step: piece p covers row p/8, k-offset (p%8)*8
+  uint4 ra[4], rb[4];
+  auto gload = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int p = tid + i * kBlock, r = p >> 3, kk = k0 + (p & 7) * 8;
+      const int ar = min(m0 + r, a.T - 1), br = min(n0 + r, a.N - 1);
+      const uint4 z = {0u, 0u, 0u, 0u};
+      ra[i] = kk < Kd ? *reinterpret_cast<const uint4*>(A + (long)ar * Kd + kk) : z;
+      rb[i] = kk < Kd ? *reinterpret_cast<const uint4*>(W + (long)br * Kd + kk) : z;
+    }
+  };
+  auto sstore = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int p = tid + i * kBlock, r = p >> 3, kk = (p & 7) * 8;
+      *reinterpret_cast<uint4*>(As + r * LDS_STRIDE + kk) = ra[i];
+      *reinterpret_cast<uint4*>(Bs + r * LDS_STRIDE + kk) = rb[i];
+    }
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  gload(0);
+  for (int k0 = 0; k0 < Kd; k0 += BK) {
+    __syncthreads();            // previous step's LDS reads are done
+    sstore();
+    __syncthreads();
+    if (k0 + BK < Kd) gload(k0 + BK);
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += 16) {
+      const int kk = ks + (lane >> 5) * 8;
+      bf16x8 fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        fa[i] = *reinterpret_cast<const bf16x8*>(As + (wm + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
+        fb[i] = *reinterpret_cast<const bf16x8*>(Bs + (wn + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // accumulator layout of the 32x32 MFMA: register r of lane l holds
+  // C[row = 8*(r/4) + 4*(l/32) + r%4][col = l%32]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int t = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int n = n0 + wn + j * 32 + (lane & 31);
+        const float v = acc[i][j][r];
+        const float partner = EPI == GEPI_SWIGLU ? __shfl_xor(v, 1, 64) : 0.f;
+        gemm_store<EPI>(a, IN_BF16, t, n, v, partner);
+      }
+}
+
+// ---------------------------------------------------------------------------
+// fp32 GEMM on the vector ALUs (exact fp32 products; used by the fp32 mode whose
+// parity bar is 1e-4).  64 x 64 tile, K step 16, each thread a 4 x 4 block.
+template <int EPI>
+__global__ __launch_bounds__(kBlock) void k_gemm_f32(GemmArgs a) {
+  __shared__ float As[16][64 + 4];
+  __shared__ float Bs[16][64 + 4];
+  const int tid = threadIdx.x;
+  const int tx = tid & 15, ty = tid >> 4;   // n block, t block
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const float* A = (const float*)a.A;
+  const float* W = (const float*)a.W;
+  const int Kd = a.Kd;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < Kd; k0 += 16) {
+    {
+      // 64 rows x 16 k per operand = 1024 values, 4 per thread (one float4 along k)
+      const int r = tid >> 2, kk = (tid & 3) * 4;
+      const int ar = min(m0 + r, a.T - 1), br = min(n0 + r, a.N - 1);
+      float4 va = {0, 0, 0, 0}, vb = {0, 0, 0, 0};
+      if (k0 + kk < Kd) {   // Kd is a multiple of 8, so a float4 never straddles the end
+        va = *reinterpret_cast<const float4*>(A + (long)ar * Kd + k0 + kk);
+        vb = *reinterpret_cast<const float4*>(W + (long)br * Kd + k0 + kk);
+      }
+      __syncthreads();
+      As[kk][r] = va.x; As[kk + 1][r] = va.y; As[kk + 2][r] = va.z; As[kk + 3][r] = va.w;
+      Bs[kk][r] = vb.x; Bs[kk + 1][r] = vb.y; Bs[kk + 2][r] = vb.z; Bs[kk + 3][r] = vb.w;
+      __syncthreads();
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      float av[4], bv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { av[i] = As[k][ty * 4 + i]; bv[i] = Bs[k][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      gemm_store<EPI>(a, IN_F32, m0 + ty * 4 + i, n0 + tx * 4 + j, acc[i][j], acc[i][j ^ 1]);
+}
+
+void launch_gemm(hipStream_t s, int dtype, int epi, const GemmArgs& a) {
+#define MDI_GEMM(K, TM, TN)                                                                     \
+  {                                                                                             \
+    const dim3 grid((a.N + TN - 1) / TN, (a.T + TM - 1) / TM), block(kBlock);                   \
+    switch (epi) {                                                                              \
+      case GEPI_F32_BIAS: hipLaunchKernelGGL((K<GEPI_F32_BIAS>), grid, block, 0, s, a); break;  \
+      case GEPI_RESID: hipLaunchKernelGGL((K<GEPI_RESID>), grid, block, 0, s, a); break;        \
+      case GEPI_SWIGLU: hipLaunchKernelGGL((K<GEPI_SWIGLU>), grid, block, 0, s, a); break;      \
+      case GEPI_GELU_TANH: hipLaunchKernelGGL((K<GEPI_GELU_TANH>), grid, block, 0, s, a); break;\
+      default: hipLaunchKernelGGL((K<GEPI_GELU_ERF>), grid, block, 0, s, a); break;             \
+    }                                                                                           \
+  }
+  if (dtype == MDI_BF16) MDI_GEMM(k_gemm_bf16, BM, BN) else MDI_GEMM(k_gemm_f32, 64, 64)
+#undef MDI_GEMM
+}
+
+// ---------------------------------------------------------------------------
+// Rotate q and k by their positions, keep q in fp32 for the attention kernel
+// and scatter k, v into the sample's pages.  One workgroup per prompt position.
+__global__ __launch_bounds__(kBlock) void k_rope_scatter(RopeScatterArgs a) {
+  const int t = blockIdx.x, h = a.h, half = h >> 1;
+  const int n_heads = a.H + 2 * a.K;
+  const float* row = a.qkv + (long)t * n_heads * h;
+  const int page = a.table[t / a.pt], slot = t % a.pt;
+  const long pt_h = (long)a.pt * h;
+  const int kind = a.dtype == MDI_BF16 ? IN_BF16 : IN_F32;
+  for (int p = threadIdx.x; p < n_heads * half; p += kBlock) {
+    const int head = p / half, i = p - head * half;
+    float v0 = row[head * h + i], v1 = row[head * h + i + half];
+    if (a.rope && head < a.H + a.K) {
+      const float2 cs = a.rope[(long)t * half + i];
+      const float t0 = v0 * cs.x - v1 * cs.y, t1 = v0 * cs.y + v1 * cs.x;
+      v0 = t0; v1 = t1;
+    }
+    if (head < a.H) {
+      float* q = a.q_out + (long)t * a.H * h + head * h + i;
+      q[0] = v0; q[half] = v1;
+    } else {
+      const bool is_v = head >= a.H + a.K;
+      const int kvh = head - a.H - (is_v ? a.K : 0);
+      const long o = (((long)page * a.K + kvh) * 2 + (is_v ? 1 : 0)) * pt_h + (long)slot * h + i;
+      store_kind(a.pool, kind, o, v0);
+      store_kind(a.pool, kind, o + half, v1);
+    }
+  }
+}
+void launch_rope_scatter(hipStream_t s, const RopeScatterArgs& a) {
+  hipLaunchKernelGGL(k_rope_scatter, dim3(a.T), dim3(kBlock), 0, s, a);
+}
+
+// ---------------------------------------------------------------------------
+// set-up kernels
+__global__ void k_rope_table(float2* table, int max_ctx, int half, int h, double base) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long)max_ctx * half) return;
+  const int p = idx / half, i = idx % half;
+  const double ang = (double)p * pow(base, -2.0 * (double)i / (double)h);
+  table[idx] = make_float2((float)cos(ang), (float)sin(ang));
+}
+void launch_rope_table(hipStream_t s, float2* table, int max_ctx, int h, double base) {
+  const long n = (long)max_ctx * (h / 2);
+  hipLaunchKernelGGL(k_rope_table, dim3((n + 255) / 256), dim3(256), 0, s, table, max_ctx, h / 2, h, base);
+}
+
+template <typename T>
+__global__ void k_copy_rows(const T* src, T* dst, long rows, long cols, long row_mul, long row_off) {
+  const long n = rows * cols;
+  for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (long)gridDim.x * blockDim.x) {
+    const long r = idx / cols, c = idx - r * cols;
+    dst[(r * row_mul + row_off) * cols + c] = src[idx];
+  }
+}
+void launch_copy_rows(hipStream_t s, int elem_bytes, const void* src, void* dst, long rows, long cols, long row_mul, long row_off) {
+  const long n = rows * cols;
+  if (n == 0) return;
+  const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+  if (elem_bytes == 2)
+    hipLaunchKernelGGL(k_copy_rows<uint16_t>, dim3(blocks), dim3(256), 0, s, (const uint16_t*)src, (uint16_t*)dst, rows, cols, row_mul, row_off);
+  else
+    hipLaunchKernelGGL(k_copy_rows<uint32_t>, dim3(blocks), dim3(256), 0, s, (const uint32_t*)src, (uint32_t*)dst, rows, cols, row_mul, row_off);
+}
+
+__global__ void k_fill_u32(uint32_t* dst, long n, uint32_t v) {
+  for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (long)gridDim.x * blockDim.x) dst[idx] = v;
+}
+void launch_fill_u32(hipStream_t s, uint32_t* dst, long n, uint32_t v) {
+  if (n == 0) return;
+  const int blocks = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+  hipLaunchKernelGGL(k_fill_u32, dim3(blocks), dim3(256), 0, s, dst, n, v);
+}
+void launch_fill_f32(hipStream_t s, float* dst, long n, float v) {
+  uint32_t u;
+  __builtin_memcpy(&u, &v, 4);
+  launch_fill_u32(s, (uint32_t*)dst, n, u);
+}
+
+}  // namespace mdi

@@ -1,0 +1,83 @@
+"""Single-GPU recurrent-pipeline driver (Sec. III-C, Alg. 1 and Alg. 2).
+
+Several partitions live on one MI355X, each on its own HIP stream (the stand-in
+for a node of the ring).  Samples circulate round-robin: the starter's visit
+k serves sample k mod n_samples; a first visit forwards the whole prompt, later
+visits forward the newest token; the output layers turn the returning
+activation into the next token, which stays in device memory and is the next
+input of the embedding stage.  Hand-offs between stages are stream events (the
+analogue of the paper's FIFO queues); the host never waits inside the loop.
+No arithmetic happens here.
+"""
+from __future__ import annotations
+
+import torch
+
+
+class RecurrentPipeline:
+    def __init__(self, parts):
+        """parts: chain of mdi.Partition; parts[0] owns the embedding, parts[-1] the
+        output layers (it may be a head-only partition, the paper's starter layout)."""
+        if not (parts[0].flags & 1) or not (parts[-1].flags & 2):
+            raise ValueError("first partition needs the embedding, last the output layers")
+        self.parts = parts
+        self.blocks = [p for p in parts if p.hi > p.lo]
+        self.head = parts[-1]
+        self.device = parts[0].device
+
+    def generate(self, prompts, n_new, keep_logits=False, keep_hidden=False):
+        """prompts: list of int32 device tensors.  Returns tokens [n_seqs, n_new] (int32, device)
+        and optionally per-token logits [n_seqs, n_new, V] / final hidden states [n_seqs, n_new, d]."""
+        ns, dev = len(prompts), self.device
+        d, V = self.head.d, self.head.V
+        toks = torch.zeros((ns, n_new), dtype=torch.int32, device=dev)
+        logits = torch.zeros((ns, n_new, V), dtype=torch.float32, device=dev) if keep_logits else None
+        hidden = torch.zeros((ns, n_new, d), dtype=self.head.tdtype, device=dev) if keep_hidden else None
+        nb = len(self.blocks)
+        pre = [[torch.empty((len(prompts[s]), d), dtype=self.head.tdtype, device=dev) for _ in range(nb)] for s in range(ns)]
+        act = [[torch.empty((d,), dtype=self.head.tdtype, device=dev) for _ in range(nb)] for s in range(ns)]
+        back = [None] * ns                       # activation waiting at the starter, per sample
+        ev_back = [None] * ns
+        main = torch.cuda.current_stream(dev)
+        start = torch.cuda.Event()
+        start.record(main)
+        for p in self.parts:
+            p.stream.wait_event(start)
+        n_rounds = n_new + 1
+        for k in range(ns * n_rounds):
+            s, r = k % ns, k // ns
+            if r >= 1:                            # output layers, then the new token joins the sample
+                hs = self.head.stream
+                hs.wait_event(ev_back[s])
+                x = back[s]
+                if keep_hidden:
+                    with torch.cuda.stream(hs):
+                        hidden[s, r - 1].copy_(x)
+                self.head.sample_greedy(s, x, toks[s, r - 1:r], logits[s, r - 1] if keep_logits else None)
+                ev_tok = torch.cuda.Event()
+                ev_tok.record(hs)
+            if r < n_rounds - 1:                  # forward through the ring
+                msg = prompts[s] if r == 0 else toks[s, r - 1:r]
+                ev = ev_tok if r >= 1 else None
+                for i, p in enumerate(self.blocks):
+                    if ev is not None:
+                        p.stream.wait_event(ev)
+                    if r == 0:
+                        out = p.prefill(s, msg, pre[s][i])
+                    else:
+                        out = p.decode_step(s, msg, act[s][i])
+                    ev = torch.cuda.Event()
+                    ev.record(p.stream)
+                    msg = out
+                back[s] = msg[-1] if r == 0 else msg
+                ev_back[s] = ev
+        for p in self.parts:
+            done = torch.cuda.Event()
+            done.record(p.stream)
+            main.wait_event(done)
+        return toks, logits, hidden
+
+    def reset(self, n_seqs):
+        for p in self.blocks:
+            for s in range(n_seqs):
+                p.seq_reset(s)

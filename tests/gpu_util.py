@@ -1,0 +1,84 @@
+"""Helpers for the GPU parity tests: build the same partition on both sides."""
+import numpy as np
+import torch
+
+from oracle import mdi_oracle as O
+from paper_2505_18164_amd import mdi, synth as S
+
+
+def rel_l2(got, want):
+    got = np.asarray(got, dtype=np.float64).ravel()
+    want = np.asarray(want, dtype=np.float64).ravel()
+    return float(np.linalg.norm(got - want) / np.linalg.norm(want))
+
+
+def host(t):
+    return t.detach().float().cpu().numpy()
+
+
+def dev_acts(a, cfg):
+    return mdi.to_device(a, cfg["dtype"], "cuda:0")
+
+
+def dev_ids(ids):
+    return torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).to("cuda:0")
+
+
+def tol(cfg):
+    """The parity bar: relative L2 error of hidden states and logits against the
+    float64 oracle, 1e-4 with fp32 storage, 2e-2 with bf16 storage."""
+    return 1e-4 if cfg["dtype"] == S.DT_F32 else 2e-2
+
+
+def scale_matrices(w, k):
+    for lw in w["layers"].values():
+        for name in lw:
+            if lw[name].ndim == 2:
+                lw[name] = lw[name] * np.float32(k)
+    return w
+
+
+def pair(cfg, w, lo, hi, embed=False, head=False, max_seqs=1, **kw):
+    o = O.Partition(cfg, w, lo, hi, has_embed=embed, has_head=head)
+    g = mdi.Partition(cfg, w, lo, hi, has_embed=embed, has_head=head, max_seqs=max_seqs, **kw)
+    return o, g
+
+
+def check(got, want, cfg, what, bar=None):
+    """Assert the parity bar with a short message (no array dumps)."""
+    err = rel_l2(host(got) if isinstance(got, torch.Tensor) else got, want)
+    bar = tol(cfg) if bar is None else bar
+    if not err < bar:
+        raise AssertionError(f"{what}: rel-L2 {err:.3e} exceeds {bar:.1e}")
+    return err
+
+
+def teacher_forced(parts, prompts, tokens, want_logits=True):
+    """Run GPU partitions (a chain; the last one owns the output layers) over
+    the given prompts, feeding `tokens[s][j]` (the oracle's) as the j-th new
+    token instead of the GPU's own argmax.  Samples are visited round-robin as
+    in Alg. 1.  Returns hidden[s][j] (input of the output layers when token j
+    was produced), logits[s][j], gpu_tokens[s][j]."""
+    blocks = [p for p in parts if p.hi > p.lo]
+    head = parts[-1]
+    ns, n_new = len(prompts), len(tokens[0])
+    hidden = [[] for _ in range(ns)]
+    logits = [[] for _ in range(ns)]
+    toks = [[] for _ in range(ns)]
+    back = [None] * ns
+    for r in range(n_new + 1):
+        for s in range(ns):
+            if r >= 1:
+                x = back[s]
+                lg = torch.empty(head.V, dtype=torch.float32, device="cuda:0") if want_logits else None
+                t = head.sample_greedy(s, x, logits_out=lg)
+                hidden[s].append(host(x))
+                toks[s].append(int(t.item()))
+                if want_logits:
+                    logits[s].append(host(lg))
+            if r < n_new:
+                msg = dev_ids(prompts[s]) if r == 0 else dev_ids([tokens[s][r - 1]])
+                for p in blocks:
+                    msg = p.prefill(s, msg) if r == 0 else p.decode_step(s, msg)
+                back[s] = msg[-1] if r == 0 else msg
+    return hidden, logits, toks

@@ -1,0 +1,112 @@
+"""GPU parity on small shapes: every model variant, both storage types, ragged
+prompt lengths, page-boundary crossings; error paths of the boundary."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mdi_oracle as O
+from paper_2505_18164_amd import mdi, synth as S
+from gpu_util import check, dev_acts, dev_ids, host, pair, rel_l2, scale_matrices, tol
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = {
+    "llama_gqa": dict(),
+    "llama_mha": dict(n_kv_head=4),
+    "llama_gqa8": dict(n_head=8, n_kv_head=1, d_model=64),
+    "llama_group3": dict(n_head=6, n_kv_head=2, d_model=48),
+    "gpt2": dict(norm_kind=S.NORM_LAYERNORM, mlp_kind=S.MLP_GELU_TANH, pos_kind=S.POS_LEARNED, has_bias=1, tie_embed=1, n_kv_head=4),
+    "gelu_erf": dict(norm_kind=S.NORM_LAYERNORM, mlp_kind=S.MLP_GELU_ERF, pos_kind=S.POS_LEARNED, has_bias=1, n_kv_head=4),
+    "wide_head": dict(head_dim=64, n_head=2, n_kv_head=1, d_model=128, d_ff=264),
+}
+
+
+@pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("name", list(VARIANTS))
+def test_full_model_teacher_forced(name, dtype):
+    cfg = S.tiny(n_layer=3, dtype=dtype, max_ctx=48, **VARIANTS[name])
+    # matrices scaled up so that every sub-layer moves the residual stream by O(1);
+    # less so with bf16 storage, whose rounding noise three such layers amplify
+    w = scale_matrices(S.make_weights(cfg, 31, exercise=True), 6.0 if dtype == S.DT_F32 else 3.0)
+    o, g = pair(cfg, w, 0, 3, embed=True, head=True, max_seqs=2, kv_page_tokens=8)
+    prompts = S.make_prompts(cfg, 31, 2, 13)
+    prompts[1] = prompts[1][:5]
+    rng = np.random.default_rng(5)
+    for s in (0, 1):
+        want = o.prefill(s, prompts[s])
+        got = g.prefill(s, dev_ids(prompts[s]))
+        check(got, want, cfg, ("prefill", s))
+    V = cfg["vocab"]
+    for step in range(22):                      # crosses page boundaries at 8-token pages
+        for s in (1, 0):
+            t = int(rng.integers(0, V))
+            want = o.decode_step(s, t)
+            got = g.decode_step(s, dev_ids([t]))
+            check(got, want, cfg, ("decode", step, s))
+            # the oracle's own activation goes into both heads
+            x = S.storage_round(want.astype(np.float32), dtype)
+            wt, wl = o.sample_greedy(x)
+            lg = torch.empty(V, dtype=torch.float32, device="cuda:0")
+            gt = g.sample_greedy(s, dev_acts(x, cfg), logits_out=lg)
+            check(lg, wl, cfg, ("logits", step, s))
+            gap = np.sort(wl)[-1] - np.sort(wl)[-2]
+            if gap > 10 * np.abs(host(lg) - wl).max():
+                assert int(gt.item()) == wt
+    assert g.seq_len(0) == 13 + 22 and g.seq_len(1) == 5 + 22
+
+
+@pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
+def test_mid_partition_activations_in_and_out(dtype):
+    cfg = S.tiny(n_layer=4, dtype=dtype)
+    w = scale_matrices(S.make_weights(cfg, 8, exercise=True), 6.0 if dtype == S.DT_F32 else 3.0)
+    o, g = pair(cfg, w, 1, 3, max_seqs=1)
+    a = S.make_activations(cfg, 8, 0, 19)
+    check(g.prefill(0, dev_acts(a, cfg)), o.prefill(0, a), cfg, "prefill")
+    for step in range(5):
+        x = S.make_activations(cfg, 8, 0, 1, step=step + 1)[0]
+        check(g.decode_step(0, dev_acts(x, cfg)), o.decode_step(0, x), cfg, ("decode", step))
+
+
+def test_prefill_of_one_token_and_argmax_ties():
+    cfg = S.tiny(n_layer=1, dtype=S.DT_F32)
+    w = S.make_weights(cfg, 2)
+    o, g = pair(cfg, w, 0, 1, embed=True, head=True)
+    ids = np.array([7], dtype=np.int32)
+    assert rel_l2(host(g.prefill(0, dev_ids(ids))), o.prefill(0, ids)) < 1e-4
+    # zero activation -> all logits equal (RMSNorm of 0 is 0) -> lowest index wins
+    z = torch.zeros(cfg["d_model"], device="cuda:0")
+    assert int(g.sample_greedy(0, z).item()) == 0
+
+
+def test_error_paths_and_page_pool():
+    cfg = S.tiny(n_layer=1, dtype=S.DT_F32, max_ctx=16)
+    w = S.make_weights(cfg, 3)
+    g = mdi.Partition(cfg, w, 0, 1, has_embed=True, max_seqs=3, kv_page_tokens=8, kv_pages=3)
+    ids = dev_ids(np.arange(8))
+    out = torch.empty(cfg["d_model"], device="cuda:0")
+
+    def status(fn, *a):
+        with pytest.raises(mdi.MdiError) as e:
+            fn(*a)
+        return e.value.status
+
+    assert status(g.decode_step, 0, ids[:1], out) == mdi.MDI_ERR_STATE        # no first visit yet
+    assert status(g.prefill, 5, ids) == mdi.MDI_ERR_ARG                      # sample id out of range
+    assert status(g.sample_greedy, 0, out) == mdi.MDI_ERR_STATE              # no output layers here
+    first = host(g.prefill(0, ids))
+    assert status(g.prefill, 0, ids) == mdi.MDI_ERR_STATE                    # cache already live
+    g.prefill(1, ids)                                                        # pool: 2 of 3 pages used
+    g.decode_step(0, ids[:1], out)                                           # third page
+    assert status(g.decode_step, 1, ids[:1], out) == mdi.MDI_ERR_NOMEM       # pool exhausted
+    assert status(g.prefill, 2, ids) == mdi.MDI_ERR_NOMEM
+    for _ in range(7):
+        g.decode_step(0, ids[:1], out)
+    assert g.seq_len(0) == 16
+    assert status(g.decode_step, 0, ids[:1], out) == mdi.MDI_ERR_CTX         # cache full
+    big = dev_ids(np.zeros(17))
+    g.seq_reset(0)
+    assert g.seq_len(0) == 0
+    assert status(g.prefill, 0, big) == mdi.MDI_ERR_CTX
+    again = host(g.prefill(0, ids))                                          # pages were returned and are reusable
+    np.testing.assert_array_equal(again, first)
+    torch.cuda.synchronize()

@@ -53,7 +53,7 @@ def test_generate_visits_and_token_counts():
     prompts = S.make_prompts(cfg, 4, 2, 5)
     parts = [O.Partition(cfg, w, 0, 1, has_embed=True), O.Partition(cfg, w, 1, 3), O.Partition(cfg, w, 3, 3, has_head=True)]
     trace = []
-    toks, logits = O.generate(parts, prompts, 4, trace=trace)
+    toks, logits, hidden = O.generate(parts, prompts, 4, trace=trace)
     assert [len(t) for t in toks] == [4, 4]
     # every stage sees each sample once per round, prefill first, in sample order
     for stage in (0, 1):
@@ -64,10 +64,12 @@ def test_generate_visits_and_token_counts():
     # same tokens as one unsplit partition generating each sample on its own
     for s in range(2):
         one = O.Partition(cfg, w, 0, 3, has_embed=True, has_head=True)
-        t1, _ = O.generate([one], [prompts[s]], 4)
+        t1, _, _ = O.generate([one], [prompts[s]], 4)
         assert t1[0] == toks[s]
     # tokens are the argmax of the returned logits, and the pmf is a distribution
     for s in range(2):
         for t, lg in zip(toks[s], logits[s]):
             assert t == int(np.argmax(lg))
             np.testing.assert_allclose(O.pmf(lg).sum(), 1.0, atol=1e-12)
+        for x, lg in zip(hidden[s], logits[s]):
+            np.testing.assert_array_equal(parts[-1].logits(x), lg)

@@ -33,6 +33,7 @@ def parse():
     ap.add_argument("--workload", type=int, default=4, help="index into the five benchmark configs (1-5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ctx-sweep", action="store_true", help="also time decode at the middle and end context")
+    ap.add_argument("--decode-path", type=int, default=0, help="0 = persistent single-launch step, 1 = one kernel per operation")
     return ap.parse_args()
 
 
@@ -80,7 +81,7 @@ def main():
 
     t0 = time.perf_counter()
     w = S.make_weights(cfg, seed, lo, hi, embed=embed, head=False)
-    part = mdi.Partition(cfg, w, lo, hi, has_embed=embed, max_seqs=n_seqs, kv_page_tokens=64,
+    part = mdi.Partition(cfg, w, lo, hi, has_embed=embed, max_seqs=n_seqs, kv_page_tokens=64, decode_path=args.decode_path,
                          max_prefill=max(prompt, cfg["max_ctx"] - 8 if args.ctx_sweep else prompt))
     setup_s = time.perf_counter() - t0
     d = cfg["d_model"]
@@ -122,7 +123,7 @@ def main():
         for k in range(steps):
             part.decode_step((warmup + k) % n_seqs, xs[k % n_seqs], out)
         e1.record()
-        torch.cuda.synchronize()
+        part.sync()
         ms = e0.elapsed_time(e1) / steps
         ctx_last = max(part.seq_len(s) for s in range(n_seqs))
         ctx_mean = (ctx_first + ctx_last) // 2
@@ -136,15 +137,25 @@ def main():
     prefill_flops = n_local * (2.0 * prompt * params + 2.0 * prompt * prompt * cfg["n_head"] * cfg["head_dim"])
     prefill_tflops = prefill_flops / (main_run["prefill_ms"] * 1e-3) / 1e12
 
-    # dominant kernel: the MLP up(+gate) projection GEMV, timed with HIP events inside the library
-    us, kbytes = part.time_kernel(2, 50)
-    roofline = {"bound": "hbm", "kernel": "k_gemv MLP up+gate projection", "achieved": kbytes / us / 1e3,
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kbytes / us / 1e3 / HBM_PEAK_GBS, "traffic": None,
-                "avg_launch_us": us, "bytes_per_launch": kbytes}
+    persistent = part.info(0) == 0
     kernels = {}
-    for which, name in ((1, "attn_out_proj"), (2, "mlp_up"), (3, "mlp_down")):
-        u_, b_ = part.time_kernel(which, 50)
-        kernels[name] = {"avg_us": u_, "GB/s": b_ / u_ / 1e3}
+    if persistent:
+        # the whole step is one kernel launch; its mean duration over the timed region (HIP events on the
+        # partition's stream, launches back to back) against the bytes a step must move
+        roofline = {"bound": "hbm", "kernel": "k_step (persistent decode step, all layers)",
+                    "achieved": main_run["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": main_run["gbs"] / HBM_PEAK_GBS, "traffic": None,
+                    "avg_launch_us": main_run["ms_per_step"] * 1e3, "bytes_per_launch": main_run["bytes_per_step"],
+                    "workgroups": part.info(1), "lds_bytes": part.info(2)}
+    else:
+        # dominant kernel: the MLP up(+gate) projection GEMV, timed with HIP events inside the library
+        us, kbytes = part.time_kernel(2, 50)
+        roofline = {"bound": "hbm", "kernel": "k_gemv MLP up+gate projection", "achieved": kbytes / us / 1e3,
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kbytes / us / 1e3 / HBM_PEAK_GBS, "traffic": None,
+                    "avg_launch_us": us, "bytes_per_launch": kbytes}
+        for which, name in ((1, "attn_out_proj"), (2, "mlp_up"), (3, "mlp_down")):
+            u_, b_ = part.time_kernel(which, 50)
+            kernels[name] = {"avg_us": u_, "GB/s": b_ / u_ / 1e3}
 
     sweep = None
     if args.ctx_sweep:
@@ -159,7 +170,8 @@ def main():
         "ms_per_step": main_run["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["dtype"] == S.DT_BF16 else "f32", "data": "synthetic",
         "config": {"workload": wl["name"], "layers": [lo, hi], "seqs_in_flight": n_seqs, "prompt": prompt,
-                   "context_during_timing": main_run["ctx"], "kv_page_tokens": 64},
+                   "context_during_timing": main_run["ctx"], "kv_page_tokens": 64,
+                   "decode_path": "persistent" if persistent else "per_op"},
         "step_bytes": main_run["bytes_per_step"], "step_GBps": main_run["gbs"],
         "step_frac_of_hbm_peak": main_run["gbs"] / HBM_PEAK_GBS,
         "roofline": roofline, "kernels": kernels,

@@ -84,6 +84,9 @@ typedef struct mdi_config {
   uint32_t has_bias;       /* linear layers carry biases (GPT-2 family)                 */
   uint32_t tie_embed;      /* vocabulary projection shares the embedding matrix          */
   uint32_t dtype;          /* MDI_F32 | MDI_BF16                                        */
+  uint32_t decode_path;    /* 0 = automatic: a decode step is one persistent kernel launch
+                              when the shape allows it, else one kernel per operation;
+                              1 = always one kernel per operation                        */
 } mdi_config;
 
 /*
@@ -171,6 +174,14 @@ MDI_API mdi_status mdi_decode_step(mdi_partition *part, uint32_t seq_id, const v
 MDI_API mdi_status mdi_sample_greedy(mdi_partition *part, uint32_t seq_id, const void *act_in,
                              int32_t *token_out, float *logits_out);
 
+/*
+ * Wait for everything enqueued on the partition's stream and report errors that
+ * only the device can detect: MDI_ERR_HIP if the stream failed or if a
+ * workgroup of a persistent decode kernel gave up waiting for the others (its
+ * waits are bounded; the step's outputs are then invalid).
+ */
+MDI_API mdi_status mdi_partition_sync(mdi_partition *part);
+
 /* Drop sample seq_id's cache (its pages return to the pool); it may be prefilled again. */
 MDI_API mdi_status mdi_seq_reset(mdi_partition *part, uint32_t seq_id);
 
@@ -198,6 +209,13 @@ MDI_API mdi_status mdi_step_bytes(const mdi_partition *part, uint32_t ctx, int h
  */
 MDI_API mdi_status mdi_time_kernel(mdi_partition *part, int which, uint32_t reps, float *avg_us,
                                    uint64_t *bytes_per_launch);
+
+/*
+ * Introspection.  what: 0 = decode path in use (0 persistent single launch,
+ * 1 one kernel per operation), 1 = workgroups of the persistent kernel,
+ * 2 = its LDS bytes per workgroup, 3 = arena bytes in use.  value: host pointer.
+ */
+MDI_API mdi_status mdi_partition_info(const mdi_partition *part, uint32_t what, uint64_t *value);
 
 /* Frees the host object; the arena stays with the caller. */
 MDI_API void mdi_partition_destroy(mdi_partition *part);

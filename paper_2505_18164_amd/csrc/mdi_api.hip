@@ -2,6 +2,7 @@
 // repacking, per-sample cache bookkeeping and the launch sequences of a first
 // visit (prefill) and a later visit (decode step) of a sample (Alg. 1, Alg. 2).
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -58,6 +59,15 @@ struct mdi_partition {
   std::vector<int32_t> host_tables;   // mirror of `tables`, source of the async page-table copies
   std::vector<int32_t> free_pages;
   size_t arena_bytes = 0;
+  // persistent single-launch decode step
+  bool use_step = false;
+  int nwg = 0, G = 1, n_hg = 0, part_floats = 0;
+  size_t step_lds = 0;
+  std::vector<StepLayer> h_step_layers;
+  StepLayer* d_step_layers = nullptr;
+  unsigned *bar_flags = nullptr, *tickets = nullptr;
+  int* err = nullptr;
+  unsigned epoch = 0;
 };
 
 namespace {
@@ -127,6 +137,10 @@ size_t carve(mdi_partition* p, void* arena) {
     p->o = (float*)cv.take(H * h * 4);
     p->u = (float*)cv.take(F * 4);
     p->part = (float*)cv.take(H * kMaxSplits * (h + 2) * 4);
+    p->d_step_layers = (StepLayer*)cv.take(p->n_local * sizeof(StepLayer));
+    p->bar_flags = (unsigned*)cv.take(1024 * 4);
+    p->tickets = (unsigned*)cv.take(H * 4);
+    p->err = (int*)cv.take(256);
     const size_t T = p->Tm;
     p->p_xres = (float*)cv.take(T * d * 4);
     p->p_xn = cv.take(T * d * B);
@@ -147,6 +161,48 @@ void init_geometry(mdi_partition* p, const mdi_config* cfg, uint32_t lo, uint32_
   p->pages_per_seq = ((int)cfg->max_ctx + p->pt - 1) / p->pt;
   p->n_pages = cfg->kv_pages ? (int)cfg->kv_pages : (int)cfg->max_seqs * p->pages_per_seq;
   p->Tm = cfg->max_prefill ? (int)cfg->max_prefill : (int)cfg->max_ctx;
+}
+
+// Decides whether a decode step runs as one persistent launch and sizes its LDS.
+void plan_step(mdi_partition* p, int n_cu) {
+  const mdi_config& c = p->cfg;
+  p->use_step = false;
+  if (c.decode_path != 0 || !p->n_local || n_cu <= 0) return;
+  const int H = c.n_head, K = c.n_kv_head, h = c.head_dim, d = c.d_model, F = c.d_ff;
+  const int group = H / K;
+  p->G = (group == 8 || group == 4 || group == 2) ? group : 1;
+  p->n_hg = H / p->G;
+  p->nwg = std::min(n_cu, 1024);
+  if (p->n_hg > p->nwg) return;
+  const int nup = c.mlp_kind == MDI_MLP_SWIGLU ? 2 * F : F;
+  const int max_rows = std::max(std::max((H + 2 * K) * h, nup), d);
+  const int max_pairs = ((max_rows + 1) / 2 + p->nwg - 1) / p->nwg + 1;
+  p->part_floats = (max_pairs * 2 * kStepWaves + 3) & ~3;
+  int xs = std::max(std::max(d, H * h), F);
+  xs = std::max(xs, kStepWaves * p->G * (h + 2));
+  xs = (xs + 3) & ~3;
+  p->step_lds = (size_t)(32 + p->part_floats + xs) * sizeof(float);
+  if (p->step_lds > 64 * 1024) return;
+  p->use_step = true;
+}
+
+// Persistent kernels of different partitions must not be co-scheduled (each wants every
+// compute unit for its barriers), so their launches are chained with an event per process.
+std::mutex g_step_mutex;
+hipEvent_t g_step_event = nullptr;
+hipStream_t g_step_stream = nullptr;
+
+mdi_status launch_step_serialised(mdi_partition* p, const StepArgs& a) {
+  std::lock_guard<std::mutex> lock(g_step_mutex);
+  if (!g_step_event) {
+    if (hipEventCreateWithFlags(&g_step_event, hipEventDisableTiming) != hipSuccess) return MDI_ERR_HIP;
+  } else if (g_step_stream != p->stream) {
+    if (hipStreamWaitEvent(p->stream, g_step_event, 0) != hipSuccess) return MDI_ERR_HIP;
+  }
+  launch_step(p->stream, p->cfg.dtype, p->G, p->nwg, p->step_lds, a);
+  if (hipEventRecord(g_step_event, p->stream) != hipSuccess) return MDI_ERR_HIP;
+  g_step_stream = p->stream;
+  return MDI_OK;
 }
 
 // device-to-device copy of a [rows, cols] matrix into rows r*mul + off of dst
@@ -248,6 +304,24 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
   launch_fill_u32(p->stream, p->counters, H + 1, 0u);
   if (p->rope) launch_rope_table(p->stream, p->rope, (int)c.max_ctx, (int)h, (double)c.rope_base);
 
+  if (p->n_local) {
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n_cu = 0;
+    plan_step(p, n_cu);
+    launch_fill_u32(p->stream, p->bar_flags, 1024, 0u);
+    launch_fill_u32(p->stream, p->tickets, H, 0u);
+    launch_fill_u32(p->stream, (uint32_t*)p->err, 64, 0u);
+    p->h_step_layers.resize(p->n_local);
+    for (int i = 0; i < p->n_local; ++i) {
+      const LayerPacked& L = p->layers[i];
+      p->h_step_layers[i] = StepLayer{L.wqkv, L.wo, L.wup, L.wdown, L.bqkv, L.bo, L.bup, L.bdown,
+                                      L.ln1_g, L.ln1_b, L.ln2_g, L.ln2_b, L.kv};
+    }
+    if (hipMemcpyAsync(p->d_step_layers, p->h_step_layers.data(), p->n_local * sizeof(StepLayer), hipMemcpyHostToDevice, p->stream) != hipSuccess) {
+      delete p;
+      return MDI_ERR_HIP;
+    }
+  }
   p->seq_len.assign(c.max_seqs, 0u);
   if (p->n_local) {
     p->host_tables.assign((size_t)c.max_seqs * p->pages_per_seq, 0);
@@ -331,10 +405,35 @@ mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, v
   const int d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff;
   const int ak = act_kind(c);
   const bool embed = p->flags & MDI_HAS_EMBED, swiglu = c.mlp_kind == MDI_MLP_SWIGLU;
+  const int ctx = len + 1;
+  if (p->use_step) {
+    StepArgs a{};
+    a.layers = p->d_step_layers; a.n_layer = p->n_local;
+    a.d = d; a.H = H; a.K = K; a.h = h; a.F = F; a.pt = p->pt; a.pt_h = (long)p->pt * h;
+    a.norm_kind = c.norm_kind; a.mlp_kind = c.mlp_kind; a.eps = c.norm_eps;
+    a.in = act_in; a.in_kind = embed ? IN_TOKEN : ak; a.wte = p->wte; a.wpe = p->wpe;
+    a.pos = len; a.ctx = ctx;
+    a.rope = p->rope ? p->rope + (size_t)len * (h / 2) : nullptr;
+    a.table = drow; a.table_entry = new_entry; a.new_page = page;
+    a.kv_tok_off = (long)page * K * 2 * a.pt_h + (long)slot * h;
+    a.xres = p->xres; a.q = p->q; a.o = p->o; a.u = p->u; a.part = p->part;
+    a.tickets = p->tickets; a.flags = p->bar_flags; a.epoch0 = p->epoch; a.err = p->err; a.spin_limit = 1 << 21;
+    a.n_hg = p->n_hg;
+    const int max_splits = std::max(1, std::min(kMaxSplits, p->nwg / p->n_hg));
+    int chunk = (ctx + max_splits - 1) / max_splits;
+    chunk = (chunk + 15) / 16 * 16;
+    a.chunk = chunk; a.n_splits = (ctx + chunk - 1) / chunk;
+    a.scale = 1.f / sqrtf((float)h);
+    a.act_out = act_out; a.act_kind = ak; a.part_floats = p->part_floats;
+    const mdi_status st = launch_step_serialised(p, a);
+    if (st != MDI_OK) return st;
+    p->epoch += 5u * (unsigned)p->n_local;
+    p->seq_len[seq] = (uint32_t)ctx;
+    return hip_status();
+  }
   InputArgs ia{act_in, embed ? IN_TOKEN : ak, p->wte, p->wpe, (int)c.dtype, len, d, p->xres, new_entry, page};
   launch_input(s, ia);
 
-  const int ctx = len + 1;
   // context split: enough workgroups to cover the chip, at least 64 tokens each
   int want = 512 / H * (H / K);   // splits so that (H/G) * splits is about 512 workgroups
   want = std::max(1, std::min(want, kMaxSplits));
@@ -395,6 +494,17 @@ mdi_status mdi_sample_greedy(mdi_partition* p, uint32_t seq, const void* act_in,
   a.out = logits_out; a.amax_val = p->amax_val; a.amax_idx = p->amax_idx;
   a.counter = p->counters + c.n_head; a.token_out = token_out;
   launch_gemv(p->stream, c.dtype, PRO_NORM, EPI_LOGITS, a);
+  return hip_status();
+}
+
+mdi_status mdi_partition_sync(mdi_partition* p) {
+  if (!p) return MDI_ERR_ARG;
+  if (hipStreamSynchronize(p->stream) != hipSuccess) return MDI_ERR_HIP;
+  if (p->err) {
+    int e = 0;
+    if (hipMemcpy(&e, p->err, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return MDI_ERR_HIP;
+    if (e) return MDI_ERR_HIP;
+  }
   return hip_status();
 }
 
@@ -469,6 +579,17 @@ mdi_status mdi_time_kernel(mdi_partition* p, int which, uint32_t reps, float* av
   const uint64_t B = p->esz;
   *bytes_per_launch = which == 1 ? (uint64_t)d * H * h * B : which == 2 ? (uint64_t)(swiglu ? 2 : 1) * F * d * B : (uint64_t)d * F * B;
   return hip_status();
+}
+
+mdi_status mdi_partition_info(const mdi_partition* p, uint32_t what, uint64_t* value) {
+  if (!p || !value) return MDI_ERR_ARG;
+  switch (what) {
+    case 0: *value = p->use_step ? 0 : 1; return MDI_OK;
+    case 1: *value = p->use_step ? (uint64_t)p->nwg : 0; return MDI_OK;
+    case 2: *value = p->use_step ? (uint64_t)p->step_lds : 0; return MDI_OK;
+    case 3: *value = p->arena_bytes; return MDI_OK;
+    default: return MDI_ERR_ARG;
+  }
 }
 
 void mdi_partition_destroy(mdi_partition* p) { delete p; }

@@ -115,6 +115,33 @@ struct RopeScatterArgs {
 };
 void launch_rope_scatter(hipStream_t s, const RopeScatterArgs& a);
 
+// ---- whole decode step as one persistent launch ------------------------------
+constexpr int kStepThreads = 512;    // one workgroup of 8 wavefronts per compute unit
+constexpr int kStepWaves = 8;
+
+struct StepLayer {                   // device-resident, one per local layer
+  const void *wqkv, *wo, *wup, *wdown;
+  const float *bqkv, *bo, *bup, *bdown, *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+  void* kv;                          // this layer's pages
+};
+
+struct StepArgs {
+  const StepLayer* layers; int n_layer;
+  int d, H, K, h, F, pt; long pt_h;
+  int norm_kind, mlp_kind; float eps;
+  const void* in; int in_kind; const void* wte; const void* wpe;
+  int pos, ctx;                      // position of the new token, context length including it
+  const float2* rope;                // (cos, sin)[h/2] of `pos`, or nullptr
+  const int32_t* table; int32_t* table_entry; int new_page;
+  long kv_tok_off;                   // element offset of K[kv head 0][slot] of the new token inside a layer's pool
+  float *xres, *q, *o, *u, *part;
+  unsigned *tickets, *flags; unsigned epoch0; int* err; int spin_limit;
+  int n_hg, n_splits, chunk; float scale;
+  void* act_out; int act_kind;
+  int part_floats;                   // LDS floats reserved for GEMV pair partials (multiple of 4)
+};
+void launch_step(hipStream_t s, int dtype, int G, int nwg, size_t lds_bytes, const StepArgs& a);
+
 // ---- set-up ---------------------------------------------------------------
 void launch_rope_table(hipStream_t s, float2* table, int max_ctx, int h, double base);
 // dst[r*dst_stride_rows + ...]: copy `rows` rows of `cols` elements, dst row = r*row_mul + row_off

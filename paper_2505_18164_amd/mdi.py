@@ -19,7 +19,7 @@ MDI_F32, MDI_BF16 = 0, 1
 MDI_HAS_EMBED, MDI_HAS_HEAD = 1, 2
 
 EXPORTS = ["mdi_partition_bytes", "mdi_partition_create", "mdi_prefill", "mdi_decode_step", "mdi_sample_greedy",
-           "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel", "mdi_partition_destroy", "mdi_strerror"]
+           "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel", "mdi_partition_info", "mdi_partition_destroy", "mdi_strerror"]
 
 
 class MdiConfig(C.Structure):
@@ -27,7 +27,7 @@ class MdiConfig(C.Structure):
                                           "d_ff", "vocab", "max_ctx", "max_seqs", "kv_page_tokens", "kv_pages",
                                           "max_prefill", "norm_kind")] + \
                [("norm_eps", C.c_float), ("mlp_kind", C.c_uint32), ("pos_kind", C.c_uint32), ("rope_base", C.c_float),
-                ("has_bias", C.c_uint32), ("tie_embed", C.c_uint32), ("dtype", C.c_uint32)]
+                ("has_bias", C.c_uint32), ("tie_embed", C.c_uint32), ("dtype", C.c_uint32), ("decode_path", C.c_uint32)]
 
 
 _LAYER_FIELDS = ("ln1_g", "ln1_b", "wq", "wk", "wv", "bq", "bk", "bv", "wo", "bo", "ln2_g", "ln2_b",
@@ -65,15 +65,17 @@ def lib():
         L.mdi_prefill.argtypes = [vp, u32, vp, u32, vp]
         L.mdi_decode_step.argtypes = [vp, u32, vp, vp]
         L.mdi_sample_greedy.argtypes = [vp, u32, vp, vp, vp]
+        L.mdi_partition_sync.argtypes = [vp]
         L.mdi_seq_reset.argtypes = [vp, u32]
         L.mdi_seq_len.argtypes = [vp, u32, C.POINTER(u32)]
         L.mdi_step_bytes.argtypes = [vp, u32, C.c_int, C.POINTER(C.c_uint64)]
         L.mdi_time_kernel.argtypes = [vp, C.c_int, u32, C.POINTER(C.c_float), C.POINTER(C.c_uint64)]
+        L.mdi_partition_info.argtypes = [vp, u32, C.POINTER(C.c_uint64)]
         L.mdi_partition_destroy.argtypes = [vp]
         L.mdi_partition_destroy.restype = None
         L.mdi_strerror.argtypes = [C.c_int]
         L.mdi_strerror.restype = C.c_char_p
-        for name in EXPORTS[:9]:
+        for name in EXPORTS[:11]:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -83,7 +85,7 @@ def strerror(status):
     return lib().mdi_strerror(int(status)).decode()
 
 
-def make_config(cfg, max_seqs, kv_page_tokens=0, kv_pages=0, max_prefill=0):
+def make_config(cfg, max_seqs, kv_page_tokens=0, kv_pages=0, max_prefill=0, decode_path=0):
     """cfg: the dict produced by synth.* shape presets (plain integers and floats)."""
     c = MdiConfig()
     c.abi_version = MDI_ABI_VERSION
@@ -93,6 +95,7 @@ def make_config(cfg, max_seqs, kv_page_tokens=0, kv_pages=0, max_prefill=0):
     c.norm_eps = float(cfg["norm_eps"])
     c.rope_base = float(cfg["rope_base"])
     c.max_seqs, c.kv_page_tokens, c.kv_pages, c.max_prefill = max_seqs, kv_page_tokens, kv_pages, max_prefill
+    c.decode_path = decode_path
     return c
 
 
@@ -122,7 +125,7 @@ class Partition:
     """One model chunk on the GPU (layers [lo, hi), optional embedding / output layers)."""
 
     def __init__(self, cfg, weights, lo, hi, has_embed=False, has_head=False, max_seqs=1, stream=None,
-                 kv_page_tokens=0, kv_pages=0, max_prefill=0, device="cuda:0"):
+                 kv_page_tokens=0, kv_pages=0, max_prefill=0, decode_path=0, device="cuda:0"):
         """weights: {"layers": {L: {name: array}}, "wte": ...} with numpy arrays (see synth.make_weights)
         or tensors already on the device in storage dtype (vectors fp32)."""
         self.cfg = dict(cfg)
@@ -130,7 +133,7 @@ class Partition:
         self.flags = (MDI_HAS_EMBED if has_embed else 0) | (MDI_HAS_HEAD if has_head else 0)
         self.device = torch.device(device)
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
-        self.c = make_config(cfg, max_seqs, kv_page_tokens, kv_pages, max_prefill)
+        self.c = make_config(cfg, max_seqs, kv_page_tokens, kv_pages, max_prefill, decode_path)
         self.dtype = int(cfg["dtype"])
         self.tdtype = torch_dtype(self.dtype)
         self.d, self.V = int(cfg["d_model"]), int(cfg["vocab"])
@@ -211,6 +214,11 @@ class Partition:
         return token_out
 
     # -- bookkeeping --------------------------------------------------------
+    def sync(self):
+        st = lib().mdi_partition_sync(self._h)
+        if st != MDI_OK:
+            raise MdiError(st, "mdi_partition_sync")
+
     def seq_reset(self, seq):
         st = lib().mdi_seq_reset(self._h, seq)
         if st != MDI_OK:
@@ -237,6 +245,13 @@ class Partition:
         if st != MDI_OK:
             raise MdiError(st, "mdi_time_kernel")
         return us.value, nb.value
+
+    def info(self, what):
+        v = C.c_uint64(0)
+        st = lib().mdi_partition_info(self._h, what, C.byref(v))
+        if st != MDI_OK:
+            raise MdiError(st, "mdi_partition_info")
+        return v.value
 
     def close(self):
         if self._h:

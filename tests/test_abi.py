@@ -34,8 +34,8 @@ def test_strerror(L):
 
 
 def test_config_struct_size_matches_header():
-    # 21 four-byte fields
-    assert C.sizeof(libmdi.MdiConfig) == 21 * 4
+    # 22 four-byte fields
+    assert C.sizeof(libmdi.MdiConfig) == 22 * 4
     assert C.sizeof(libmdi.MdiLayerWeights) == 17 * 8
     assert C.sizeof(libmdi.MdiWeights) == 6 * 8
 

@@ -21,14 +21,15 @@ VARIANTS = {
 }
 
 
+@pytest.mark.parametrize("path", [0, 1], ids=["persistent", "per_op"])
 @pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
 @pytest.mark.parametrize("name", list(VARIANTS))
-def test_full_model_teacher_forced(name, dtype):
+def test_full_model_teacher_forced(name, dtype, path):
     cfg = S.tiny(n_layer=3, dtype=dtype, max_ctx=48, **VARIANTS[name])
     # matrices scaled up so that every sub-layer moves the residual stream by O(1);
     # less so with bf16 storage, whose rounding noise three such layers amplify
     w = scale_matrices(S.make_weights(cfg, 31, exercise=True), 6.0 if dtype == S.DT_F32 else 3.0)
-    o, g = pair(cfg, w, 0, 3, embed=True, head=True, max_seqs=2, kv_page_tokens=8)
+    o, g = pair(cfg, w, 0, 3, embed=True, head=True, max_seqs=2, kv_page_tokens=8, decode_path=path)
     prompts = S.make_prompts(cfg, 31, 2, 13)
     prompts[1] = prompts[1][:5]
     rng = np.random.default_rng(5)
@@ -53,13 +54,15 @@ def test_full_model_teacher_forced(name, dtype):
             if gap > 10 * np.abs(host(lg) - wl).max():
                 assert int(gt.item()) == wt
     assert g.seq_len(0) == 13 + 22 and g.seq_len(1) == 5 + 22
+    g.sync()
 
 
+@pytest.mark.parametrize("path", [0, 1], ids=["persistent", "per_op"])
 @pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
-def test_mid_partition_activations_in_and_out(dtype):
+def test_mid_partition_activations_in_and_out(dtype, path):
     cfg = S.tiny(n_layer=4, dtype=dtype)
     w = scale_matrices(S.make_weights(cfg, 8, exercise=True), 6.0 if dtype == S.DT_F32 else 3.0)
-    o, g = pair(cfg, w, 1, 3, max_seqs=1)
+    o, g = pair(cfg, w, 1, 3, max_seqs=1, decode_path=path)
     a = S.make_activations(cfg, 8, 0, 19)
     check(g.prefill(0, dev_acts(a, cfg)), o.prefill(0, a), cfg, "prefill")
     for step in range(5):
@@ -109,4 +112,4 @@ def test_error_paths_and_page_pool():
     assert status(g.prefill, 0, big) == mdi.MDI_ERR_CTX
     again = host(g.prefill(0, ids))                                          # pages were returned and are reusable
     np.testing.assert_array_equal(again, first)
-    torch.cuda.synchronize()
+    g.sync()

@@ -217,6 +217,16 @@ MDI_API mdi_status mdi_time_kernel(mdi_partition *part, int which, uint32_t reps
  */
 MDI_API mdi_status mdi_partition_info(const mdi_partition *part, uint32_t what, uint64_t *value);
 
+/*
+ * Profiling aid for the persistent decode kernel: when trace is not NULL, every
+ * following decode step records, per workgroup, layer and phase (QKV, attention,
+ * output projection, MLP up, MLP down), four 100 MHz timestamps: phase entered,
+ * barrier passed, input vector staged, streaming done.  trace: device buffer of
+ * uint64 [workgroups][local layers][5][4] (mdi_partition_info gives the workgroup
+ * count), owned by the caller; NULL switches tracing off.
+ */
+MDI_API mdi_status mdi_partition_trace(mdi_partition *part, void *trace);
+
 /* Frees the host object; the arena stays with the caller. */
 MDI_API void mdi_partition_destroy(mdi_partition *part);
 

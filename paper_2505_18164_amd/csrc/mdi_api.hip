@@ -68,6 +68,7 @@ struct mdi_partition {
   unsigned *bar_flags = nullptr, *tickets = nullptr;
   int* err = nullptr;
   unsigned epoch = 0;
+  unsigned long long* trace = nullptr;
 };
 
 namespace {
@@ -181,7 +182,7 @@ void plan_step(mdi_partition* p, int n_cu) {
   int xs = std::max(std::max(d, H * h), F);
   xs = std::max(xs, kStepWaves * p->G * (h + 2));
   xs = (xs + 3) & ~3;
-  p->step_lds = (size_t)(32 + p->part_floats + xs) * sizeof(float);
+  p->step_lds = (size_t)(128 + p->part_floats + xs) * sizeof(float);
   if (p->step_lds > 64 * 1024) return;
   p->use_step = true;
 }
@@ -424,7 +425,7 @@ mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, v
     chunk = (chunk + 15) / 16 * 16;
     a.chunk = chunk; a.n_splits = (ctx + chunk - 1) / chunk;
     a.scale = 1.f / sqrtf((float)h);
-    a.act_out = act_out; a.act_kind = ak; a.part_floats = p->part_floats;
+    a.act_out = act_out; a.act_kind = ak; a.part_floats = p->part_floats; a.trace = p->trace;
     const mdi_status st = launch_step_serialised(p, a);
     if (st != MDI_OK) return st;
     p->epoch += 5u * (unsigned)p->n_local;
@@ -590,6 +591,12 @@ mdi_status mdi_partition_info(const mdi_partition* p, uint32_t what, uint64_t* v
     case 3: *value = p->arena_bytes; return MDI_OK;
     default: return MDI_ERR_ARG;
   }
+}
+
+mdi_status mdi_partition_trace(mdi_partition* p, void* trace) {
+  if (!p) return MDI_ERR_ARG;
+  p->trace = (unsigned long long*)trace;
+  return MDI_OK;
 }
 
 void mdi_partition_destroy(mdi_partition* p) { delete p; }

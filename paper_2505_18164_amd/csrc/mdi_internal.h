@@ -139,6 +139,7 @@ struct StepArgs {
   int n_hg, n_splits, chunk; float scale;
   void* act_out; int act_kind;
   int part_floats;                   // LDS floats reserved for GEMV pair partials (multiple of 4)
+  unsigned long long* trace;         // optional [workgroup][n_layer * 5 phases][4] timestamps (100 MHz ticks), or nullptr
 };
 void launch_step(hipStream_t s, int dtype, int G, int nwg, size_t lds_bytes, const StepArgs& a);
 

@@ -19,7 +19,7 @@ MDI_F32, MDI_BF16 = 0, 1
 MDI_HAS_EMBED, MDI_HAS_HEAD = 1, 2
 
 EXPORTS = ["mdi_partition_bytes", "mdi_partition_create", "mdi_prefill", "mdi_decode_step", "mdi_sample_greedy",
-           "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel", "mdi_partition_info", "mdi_partition_destroy", "mdi_strerror"]
+           "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel", "mdi_partition_info", "mdi_partition_trace", "mdi_partition_destroy", "mdi_strerror"]
 
 
 class MdiConfig(C.Structure):
@@ -71,11 +71,12 @@ def lib():
         L.mdi_step_bytes.argtypes = [vp, u32, C.c_int, C.POINTER(C.c_uint64)]
         L.mdi_time_kernel.argtypes = [vp, C.c_int, u32, C.POINTER(C.c_float), C.POINTER(C.c_uint64)]
         L.mdi_partition_info.argtypes = [vp, u32, C.POINTER(C.c_uint64)]
+        L.mdi_partition_trace.argtypes = [vp, vp]
         L.mdi_partition_destroy.argtypes = [vp]
         L.mdi_partition_destroy.restype = None
         L.mdi_strerror.argtypes = [C.c_int]
         L.mdi_strerror.restype = C.c_char_p
-        for name in EXPORTS[:11]:
+        for name in EXPORTS[:12]:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -245,6 +246,13 @@ class Partition:
         if st != MDI_OK:
             raise MdiError(st, "mdi_time_kernel")
         return us.value, nb.value
+
+    def trace(self, buf):
+        """buf: int64 device tensor [workgroups, layers, 5, 4] or None."""
+        st = lib().mdi_partition_trace(self._h, _ptr(buf))
+        if st != MDI_OK:
+            raise MdiError(st, "mdi_partition_trace")
+        self._trace = buf
 
     def info(self, what):
         v = C.c_uint64(0)

@@ -220,9 +220,11 @@ MDI_API mdi_status mdi_partition_info(const mdi_partition *part, uint32_t what, 
 /*
  * Profiling aid for the persistent decode kernel: when trace is not NULL, every
  * following decode step records, per workgroup, layer and phase (QKV, attention,
- * output projection, MLP up, MLP down), four 100 MHz timestamps: phase entered,
- * barrier passed, input vector staged, streaming done.  trace: device buffer of
- * uint64 [workgroups][local layers][5][4] (mdi_partition_info gives the workgroup
+ * output projection, MLP up, MLP down), up to eight 100 MHz timestamps: 0 phase
+ * entered (first tiles issued), 1 barrier passed, 2 input vector staged, 3 first
+ * wavefront done streaming, 4 all wavefronts done (GEMV phases), 5 results
+ * stored, 6 stores acknowledged; slot 7 is unused.  trace: device buffer of
+ * uint64 [workgroups][local layers][5][8] (mdi_partition_info gives the workgroup
  * count), owned by the caller; NULL switches tracing off.
  */
 MDI_API mdi_status mdi_partition_trace(mdi_partition *part, void *trace);

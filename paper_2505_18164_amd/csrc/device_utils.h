@@ -48,6 +48,42 @@ __device__ __forceinline__ void store_kind(void* p, int kind, long i, float v) {
   if (kind == IN_BF16) ((bf16_t*)p)[i] = f32_to_bf16(v); else ((float*)p)[i] = v;
 }
 
+// Cross-lane adds through the DPP data path (full VALU rate, no LDS crossbar round trip).
+// Lanes a control word does not write receive 0 and so add nothing.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false);
+  return v + __int_as_float(moved);
+}
+constexpr int kDppXor1 = 0xB1;          // quad_perm:[1,0,3,2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm:[2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // lane i <-> 7 - i inside groups of 8
+constexpr int kDppMirror = 0x140;       // lane i <-> 15 - i inside rows of 16
+constexpr int kDppBcast15 = 0x142;      // lane 15 of each row -> every lane of the next row
+constexpr int kDppBcast31 = 0x143;      // lane 31 -> every lane of rows 2 and 3
+
+// Sum over the 64 lanes; the total is valid in lane 63 only.
+__device__ __forceinline__ float wave_sum_to_lane63(float v) {
+  v = dpp_add<kDppXor1, 0xF>(v);
+  v = dpp_add<kDppXor2, 0xF>(v);
+  v = dpp_add<kDppHalfMirror, 0xF>(v);
+  v = dpp_add<kDppMirror, 0xF>(v);       // every lane of a row holds the row's sum
+  v = dpp_add<kDppBcast15, 0xA>(v);      // rows 1 and 3 add the sum of rows 0 and 2
+  v = dpp_add<kDppBcast31, 0xC>(v);      // rows 2 and 3 add lane 31 = rows 0 + 1
+  return v;
+}
+
+// Sum inside aligned groups of L lanes (L a power of two), result in every lane of the group.
+__device__ __forceinline__ float group_sum(float v, int L) {
+  if (L >= 2) v = dpp_add<kDppXor1, 0xF>(v);
+  if (L >= 4) v = dpp_add<kDppXor2, 0xF>(v);
+  if (L >= 8) v = dpp_add<kDppHalfMirror, 0xF>(v);
+  if (L >= 16) v = dpp_add<kDppMirror, 0xF>(v);
+  if (L >= 32) v += __shfl_xor(v, 16, 64);
+  if (L >= 64) v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);

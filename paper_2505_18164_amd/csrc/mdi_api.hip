@@ -409,7 +409,10 @@ mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, v
   const int ctx = len + 1;
   if (p->use_step) {
     StepArgs a{};
-    a.layers = p->d_step_layers; a.n_layer = p->n_local;
+    a.l0 = p->h_step_layers[0];
+    a.w_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].wqkv - (const char*)p->h_step_layers[0].wqkv : 0;
+    a.kv_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].kv - (const char*)p->h_step_layers[0].kv : 0;
+    a.n_layer = p->n_local;
     a.d = d; a.H = H; a.K = K; a.h = h; a.F = F; a.pt = p->pt; a.pt_h = (long)p->pt * h;
     a.norm_kind = c.norm_kind; a.mlp_kind = c.mlp_kind; a.eps = c.norm_eps;
     a.in = act_in; a.in_kind = embed ? IN_TOKEN : ak; a.wte = p->wte; a.wpe = p->wpe;

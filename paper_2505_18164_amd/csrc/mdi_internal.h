@@ -126,7 +126,9 @@ struct StepLayer {                   // device-resident, one per local layer
 };
 
 struct StepArgs {
-  const StepLayer* layers; int n_layer;
+  StepLayer l0;                      // first local layer; layer i's pointers are these advanced by i strides
+  long w_stride, kv_stride;          // bytes between consecutive layers' packed weights / page pools
+  int n_layer;
   int d, H, K, h, F, pt; long pt_h;
   int norm_kind, mlp_kind; float eps;
   const void* in; int in_kind; const void* wte; const void* wpe;

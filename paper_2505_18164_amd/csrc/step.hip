@@ -64,7 +64,14 @@ template <> struct Unpack<bf16_t> {
 
 enum StepPhase { PH_QKV = 0, PH_ATTN = 1, PH_OPROJ = 2, PH_UP = 3, PH_DOWN = 4 };
 
-// LDS map (floats): [0,16) reduction scratch, [16,20) flags, [20,52) phase geometry,
+// optional timeline for profiling: thread 0 of every workgroup records a 100 MHz timestamp
+__device__ __forceinline__ void stamp(const StepArgs& a, int layer, int ph, int k) {
+  if (a.trace && threadIdx.x == 0)
+    a.trace[(((long)blockIdx.x * a.n_layer + layer) * 5 + ph) * 8 + k] = wall_clock64();
+}
+
+
+// LDS map (floats): [0,16) reduction scratch, [16,20) flags, [20,56) phase geometry,
 // [128, 128+part_floats) pair partials, then the vector.
 constexpr int kLdsPart = 128;
 __device__ __forceinline__ float* lds_red() { extern __shared__ float smem[]; return smem; }
@@ -104,29 +111,6 @@ __device__ __forceinline__ float stage_coherent(const float* src, int n, float* 
   return ss;
 }
 
-// the step's own input (token embedding + learned position, or the previous stage's activation)
-template <typename WT>
-__device__ __forceinline__ void stage_input(const StepArgs& a, float* xs, int n_res_pairs) {
-  const int n = a.d;
-  if (a.in_kind == IN_TOKEN) {
-    const long tok = *(const int32_t*)a.in;
-    for (int i = threadIdx.x; i < n; i += kStepThreads) {
-      float v = Storage<WT>::get((const WT*)a.wte + tok * n + i);
-      if (a.wpe) v += Storage<WT>::get((const WT*)a.wpe + (long)a.pos * n + i);
-      xs[i] = v;
-    }
-  } else {
-    for (int i = threadIdx.x; i < n; i += kStepThreads) xs[i] = load_kind(a.in, a.in_kind, i);
-  }
-  __syncthreads();
-  // rows this workgroup owns in the residual phases get their starting value
-  for (int pl = threadIdx.x; pl < n_res_pairs; pl += kStepThreads) {
-    const int r = 2 * ((int)blockIdx.x + pl * (int)gridDim.x);
-    st_sc(a.xres + r, xs[r]);
-    if (r + 1 < n) st_sc(a.xres + r + 1, xs[r + 1]);
-  }
-}
-
 __device__ __forceinline__ void normalise(float* xs, int n, int norm_kind, float eps, const float* g, const float* b, float* red) {
   if (norm_kind == MDI_NORM_LAYERNORM) {
     float s = 0.f;
@@ -150,8 +134,9 @@ struct Geo {
   const void* W;
   int N, units, cpp;     // rows, 16-byte units per row, 64-lane chunks per row
   int rope_h;            // > 0: pair (i, i + h/2) inside heads of size h; 0: rows (2p, 2p + 1)
-  int p_lo, n_pl;        // this workgroup's pairs: p_lo, p_lo + nwg, p_lo + 2 nwg, ... (n_pl of them), so that at any
-                         // moment the whole grid reads one contiguous window of the matrix
+  int p_lo, n_pl;        // this workgroup owns n_pl pairs: blocks of 2^bshift consecutive pairs, block b of the
+  int bshift;            // matrix going to workgroup b % nwg (p_lo = workgroup index).  At any moment the grid
+                         // reads one contiguous window of the matrix, and a workgroup stays >= 64 KiB in place.
   int n_k;               // this wavefront's items: item k is flat index wave + 8k, flat = pair * cpp + chunk
   int dq, dr;            // 8 / cpp and 8 % cpp: how (pair, chunk) moves from one item to the next
 };
@@ -163,7 +148,14 @@ __device__ __forceinline__ Geo make_geo(const void* W, int N, int Kd, int rope_h
   g.W = W; g.N = N; g.units = Kd / V; g.cpp = (g.units + 63) >> 6; g.rope_h = rope_h;
   const int pairs = (N + 1) >> 1;
   g.p_lo = wg;
-  g.n_pl = pairs > wg ? (pairs - wg + nwg - 1) / nwg : 0;
+  g.bshift = 0;
+  const long pair_bytes = 2L * Kd * (long)sizeof(WT);
+  // larger blocks only while they still divide evenly among the workgroups (balance comes first)
+  while (g.bshift < 3 && (pair_bytes << g.bshift) < 65536 && pairs % (nwg << (g.bshift + 1)) == 0) ++g.bshift;
+  const int B = 1 << g.bshift, nblk = (pairs + B - 1) >> g.bshift;
+  const int own = nblk > wg ? (nblk - wg + nwg - 1) / nwg : 0;
+  g.n_pl = own * B;
+  if (own > 0 && wg + (own - 1) * nwg == nblk - 1) g.n_pl -= nblk * B - pairs;   // the matrix's last block may be short
   const int flat = g.n_pl * g.cpp;
   g.n_k = flat > wave ? (flat - wave + kStepWaves - 1) / kStepWaves : 0;
   g.dq = kStepWaves / g.cpp; g.dr = kStepWaves - g.dq * g.cpp;
@@ -172,6 +164,9 @@ __device__ __forceinline__ Geo make_geo(const void* W, int N, int Kd, int rope_h
 __device__ __forceinline__ void geo_next(const Geo& g, int& pl, int& c) {
   c += g.dr; pl += g.dq;
   if (c >= g.cpp) { c -= g.cpp; ++pl; }
+}
+__device__ __forceinline__ int geo_pair(const Geo& g, int pl) {     // local pair index -> pair index in the matrix
+  return ((((pl >> g.bshift) * (int)gridDim.x) + g.p_lo) << g.bshift) + (pl & ((1 << g.bshift) - 1));
 }
 __device__ __forceinline__ int geo_row(const Geo& g, int p, int j) {
   if (g.rope_h) {                                   // head sizes are powers of two
@@ -182,22 +177,48 @@ __device__ __forceinline__ int geo_row(const Geo& g, int p, int j) {
   return 2 * p + j;
 }
 
+// the step's own input (token embedding + learned position, or the previous stage's activation)
+template <typename WT>
+__device__ __forceinline__ void stage_input(const StepArgs& a, float* xs, const Geo& gres) {
+  const int n = a.d;
+  if (a.in_kind == IN_TOKEN) {
+    const long tok = *(const int32_t*)a.in;
+    for (int i = threadIdx.x; i < n; i += kStepThreads) {
+      float v = Storage<WT>::get((const WT*)a.wte + tok * n + i);
+      if (a.wpe) v += Storage<WT>::get((const WT*)a.wpe + (long)a.pos * n + i);
+      xs[i] = v;
+    }
+  } else {
+    for (int i = threadIdx.x; i < n; i += kStepThreads) xs[i] = load_kind(a.in, a.in_kind, i);
+  }
+  __syncthreads();
+  // rows this workgroup owns in the residual phases get their starting value
+  for (int pl = threadIdx.x; pl < gres.n_pl; pl += kStepThreads) {
+    const int r = 2 * geo_pair(gres, pl);
+    st_sc(a.xres + r, xs[r]);
+    if (r + 1 < n) st_sc(a.xres + r + 1, xs[r + 1]);
+  }
+}
+
+// Every call issues exactly 2 * kTile loads, whatever the geometry: items past the end of the
+// wavefront's share (and lanes past the end of a row) read the first bytes of the matrix instead
+// and are ignored by gemv_compute.  A fixed number of loads per tile is what lets the compiler
+// wait for one tile while the next stays in flight (its counters cannot follow conditional loads).
 __device__ __forceinline__ void gemv_issue(Tile& t, const Geo& g, int ti, int wave, int lane) {
   const MDI_GLOBAL u32x4* W = (const MDI_GLOBAL u32x4*)g.W;
   const int i0 = wave + kStepWaves * kTile * ti;
   int pl = i0 / g.cpp, c = i0 - pl * g.cpp;
 #pragma unroll
   for (int s = 0; s < kTile; ++s) {
-    if (ti * kTile + s < g.n_k) {                           // uniform
-      const int p = g.p_lo + pl * (int)gridDim.x;
-      const int r0 = min(geo_row(g, p, 0), g.N - 1), r1 = min(geo_row(g, p, 1), g.N - 1);
-      const MDI_GLOBAL u32x4* b0 = W + (long)r0 * g.units + c * 64;
-      const MDI_GLOBAL u32x4* b1 = W + (long)r1 * g.units + c * 64;
-      const bool ok = c * 64 + lane < g.units;
-      const u32x4 z = {0u, 0u, 0u, 0u};
-      t.r[2 * s] = ok ? b0[lane] : z;
-      t.r[2 * s + 1] = ok ? b1[lane] : z;
-    }
+    const bool item = ti * kTile + s < g.n_k;                 // uniform
+    const int p = geo_pair(g, item ? pl : 0);
+    const int r0 = item ? min(geo_row(g, p, 0), g.N - 1) : 0, r1 = item ? min(geo_row(g, p, 1), g.N - 1) : 0;
+    const int cc = item ? c : 0;
+    const MDI_GLOBAL u32x4* b0 = W + (long)r0 * g.units + cc * 64;
+    const MDI_GLOBAL u32x4* b1 = W + (long)r1 * g.units + cc * 64;
+    const int off = cc * 64 + lane < g.units ? lane : 0;      // unit 0 of the chunk always exists
+    t.r[2 * s] = b0[off];
+    t.r[2 * s + 1] = b1[off];
     geo_next(g, pl, c);
   }
 }
@@ -228,8 +249,8 @@ __device__ __forceinline__ void gemv_compute(const Tile& t, const Geo& g, int ti
         for (int e = 0; e < V; ++e) { acc0 = fmaf(w0[e], xv[e], acc0); acc1 = fmaf(w1[e], xv[e], acc1); }
       }
       if (npl != pl || k == g.n_k - 1) {                     // this wavefront's share of the pair is complete
-        const float r0 = wave_sum(acc0), r1 = wave_sum(acc1);
-        if (lane == 0) { part[(pl * 2) * kStepWaves + wave] = r0; part[(pl * 2 + 1) * kStepWaves + wave] = r1; }
+        const float r0 = wave_sum_to_lane63(acc0), r1 = wave_sum_to_lane63(acc1);
+        if (lane == 63) { part[(pl * 2) * kStepWaves + wave] = r0; part[(pl * 2 + 1) * kStepWaves + wave] = r1; }
         acc0 = 0.f; acc1 = 0.f;
       }
     }
@@ -243,12 +264,13 @@ __device__ __forceinline__ void gemv_finish(int ph, const Geo& g, const StepLaye
                                             float row_scale, float x0_pre, float x1_pre) {
   const StepLayer& L = *Lp;
   __syncthreads();                                           // all wavefronts' partials are in LDS
+  stamp(a, layer, ph, 4);
   for (int pl = threadIdx.x; pl < g.n_pl; pl += kStepThreads) {
     float v0 = 0.f, v1 = 0.f;
 #pragma unroll
     for (int w = 0; w < kStepWaves; ++w) { v0 += part[(pl * 2) * kStepWaves + w]; v1 += part[(pl * 2 + 1) * kStepWaves + w]; }
     v0 *= row_scale; v1 *= row_scale;
-    const int p = g.p_lo + pl * (int)gridDim.x;
+    const int p = geo_pair(g, pl);
     const int r0 = geo_row(g, p, 0), r1 = geo_row(g, p, 1);
     if (ph == PH_QKV) {
       if (L.bqkv) { v0 += L.bqkv[r0]; v1 += L.bqkv[r1]; }
@@ -320,6 +342,7 @@ __device__ __forceinline__ AttnGeo make_attn_geo(const StepArgs& a, int wg, int 
   return g;
 }
 
+// Issues exactly 2 * kTile loads (see gemv_issue); slots without a token re-read token 0.
 template <typename WT>
 __device__ __forceinline__ void attn_issue(Tile& t, const AttnGeo& g, const StepArgs& a, const void* pool_, int ti, int wave) {
   const MDI_GLOBAL WT* pool = (const MDI_GLOBAL WT*)pool_;
@@ -327,18 +350,12 @@ __device__ __forceinline__ void attn_issue(Tile& t, const AttnGeo& g, const Step
 #pragma unroll
   for (int s = 0; s < kTile; ++s) {
     const int k = ti * kTile + s;
-    if (k < g.n_k) {                                           // uniform
-      const int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
-      const u32x4 z = {0u, 0u, 0u, 0u};
-      u32x4 kq = z, vq = z;
-      if (tok < g.s1p) {
-        const int page = table[tok / a.pt];
-        const MDI_GLOBAL WT* kp = pool + ((long)page * a.K + g.kvh) * 2 * a.pt_h + (long)(tok % a.pt) * a.h + g.hoff;
-        kq = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp);
-        vq = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp + a.pt_h);
-      }
-      t.r[2 * s] = kq; t.r[2 * s + 1] = vq;
-    }
+    int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
+    if (!(k < g.n_k && tok < g.s1p)) tok = 0;
+    const int page = table[tok / a.pt];
+    const MDI_GLOBAL WT* kp = pool + ((long)page * a.K + g.kvh) * 2 * a.pt_h + (long)(tok % a.pt) * a.h + g.hoff;
+    t.r[2 * s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp);
+    t.r[2 * s + 1] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp + a.pt_h);
   }
 }
 
@@ -362,7 +379,7 @@ __device__ __forceinline__ void attn_update(AttnState<WT, G>& st, const AttnGeo&
       const float4 q4 = *reinterpret_cast<const float4*>(qs + gi * h + g.hoff + e);
       s = fmaf(q4.x, kf[e], s); s = fmaf(q4.y, kf[e + 1], s); s = fmaf(q4.z, kf[e + 2], s); s = fmaf(q4.w, kf[e + 3], s);
     }
-    for (int off = 1; off < g.L; off <<= 1) s += __shfl_xor(s, off, 64);
+    s = group_sum(s, g.L);
     if (valid) {
       const float mn = fmaxf(st.m[gi], s);
       const float alpha = __expf(st.m[gi] - mn), p = __expf(s - mn);
@@ -482,13 +499,26 @@ __device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a,
     const int gi = idx / h, e = idx - gi * h;
     const int head = g.hg * G + gi;
     const float* pr = a.part + (long)head * kMaxSplits * rec;
-    float m = -1e30f;
-    for (int sp = 0; sp < a.n_splits; ++sp) m = fmaxf(m, ld_sc(pr + sp * rec + h));
-    float l = 0.f, o = 0.f;
-    for (int sp = 0; sp < a.n_splits; ++sp) {
-      const float* r = pr + sp * rec;
-      const float sc = __expf(ld_sc(r + h) - m);
-      l += ld_sc(r + h + 1) * sc; o += ld_sc(r + e) * sc;
+    // splits are folded in split order, eight at a time so that their loads are in flight together
+    float m = -1e30f, l = 0.f, o = 0.f;
+    for (int sp0 = 0; sp0 < a.n_splits; sp0 += 8) {
+      float2 ml[8];
+      float oo[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const bool ok = sp0 + k < a.n_splits;
+        const float* r = pr + (sp0 + k) * rec;
+        ml[k] = ok ? ld_sc2(r + h) : make_float2(-1e30f, 0.f);
+        oo[k] = ok ? ld_sc(r + e) : 0.f;
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float mn = fmaxf(m, ml[k].x);
+        const float sa = __expf(m - mn), sb = __expf(ml[k].x - mn);
+        l = l * sa + ml[k].y * sb;
+        o = o * sa + oo[k] * sb;
+        m = mn;
+      }
     }
     st_sc(a.o + (long)head * h + e, o / l);
   }
@@ -496,21 +526,17 @@ __device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a,
 }
 
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void stamp(const StepArgs& a, int layer, int ph, int k) {
-  if (a.trace && threadIdx.x == 0)
-    a.trace[(((long)blockIdx.x * a.n_layer + layer) * 5 + ph) * 4 + k] = wall_clock64();
-}
 
 // Geometry of the four GEMV phases lives in LDS as plain integers (it depends on the workgroup
 // only); a phase reloads what it needs, so only two geometries are ever live in registers.
-constexpr int kGeoInts = 8;
+constexpr int kGeoInts = 9;
 __device__ __forceinline__ int* lds_geo() { extern __shared__ float smem[]; return (int*)(smem + 16) + 4; }   // 32 ints after the flags
 
 template <typename WT>
 __device__ __forceinline__ void store_geo(int j, int N, int Kd, int rope_h, int wg, int nwg) {
   const Geo g = make_geo<WT>(nullptr, N, Kd, rope_h, wg, nwg, 0);
   int* o = lds_geo() + j * kGeoInts;
-  o[0] = g.N; o[1] = g.units; o[2] = g.cpp; o[3] = g.rope_h; o[4] = g.p_lo; o[5] = g.n_pl; o[6] = g.dq; o[7] = g.dr;
+  o[0] = g.N; o[1] = g.units; o[2] = g.cpp; o[3] = g.rope_h; o[4] = g.p_lo; o[5] = g.n_pl; o[6] = g.dq; o[7] = g.dr; o[8] = g.bshift;
 }
 __device__ __forceinline__ Geo load_geo(int j, const void* W, int wave) {
   const int* o = lds_geo() + j * kGeoInts;
@@ -520,13 +546,29 @@ __device__ __forceinline__ Geo load_geo(int j, const void* W, int wave) {
   g.cpp = __builtin_amdgcn_readfirstlane(o[2]); g.rope_h = __builtin_amdgcn_readfirstlane(o[3]);
   g.p_lo = __builtin_amdgcn_readfirstlane(o[4]); g.n_pl = __builtin_amdgcn_readfirstlane(o[5]);
   g.dq = __builtin_amdgcn_readfirstlane(o[6]); g.dr = __builtin_amdgcn_readfirstlane(o[7]);
+  g.bshift = __builtin_amdgcn_readfirstlane(o[8]);
   const int flat = g.n_pl * g.cpp;
   g.n_k = flat > wave ? (flat - wave + kStepWaves - 1) / kStepWaves : 0;
   return g;
 }
 // GEMV phases in order: 0 = QKV, 1 = output projection, 2 = MLP up, 3 = MLP down
 __device__ __forceinline__ int gemv_index(int ph) { return ph == PH_QKV ? 0 : ph - 1; }
-__device__ __forceinline__ const void* layer_matrix(const StepLayer* L, int j) { return ((const void* const*)L)[j]; }
+// Every layer occupies an identically laid out block of the arena, so layer i's pointers are
+// the first layer's advanced by i strides: no pointer has to be fetched from memory.
+template <typename T> __device__ __forceinline__ T* advance(T* p, long bytes) { return p ? (T*)((char*)p + bytes) : p; }
+__device__ __forceinline__ const void* advance(const void* p, long bytes) { return p ? (const void*)((const char*)p + bytes) : p; }
+__device__ __forceinline__ StepLayer layer_at(const StepArgs& a, int layer) {
+  const long w = a.w_stride * layer, kv = a.kv_stride * layer;
+  StepLayer L;
+  L.wqkv = advance(a.l0.wqkv, w); L.wo = advance(a.l0.wo, w); L.wup = advance(a.l0.wup, w); L.wdown = advance(a.l0.wdown, w);
+  L.bqkv = advance(a.l0.bqkv, w); L.bo = advance(a.l0.bo, w); L.bup = advance(a.l0.bup, w); L.bdown = advance(a.l0.bdown, w);
+  L.ln1_g = advance(a.l0.ln1_g, w); L.ln1_b = advance(a.l0.ln1_b, w); L.ln2_g = advance(a.l0.ln2_g, w); L.ln2_b = advance(a.l0.ln2_b, w);
+  L.kv = advance(a.l0.kv, kv);
+  return L;
+}
+__device__ __forceinline__ const void* layer_matrix(const StepLayer& L, int j) {
+  return j == 0 ? L.wqkv : j == 1 ? L.wo : j == 2 ? L.wup : L.wdown;
+}
 
 template <typename WT, int G>
 __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
@@ -552,17 +594,20 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
   float acc0 = 0.f, acc1 = 0.f;
   AttnState<WT, G> st;
   Tile A, B;
-  {
-    const Geo g0 = load_geo(0, a.layers[0].wqkv, wave);
-    gemv_issue(A, g0, 0, wave, lane);
-    gemv_issue(B, g0, 1, wave, lane);
-  }
 
 #pragma nounroll
   for (int layer = 0; layer < a.n_layer; ++layer) {
-    const StepLayer* L = a.layers + layer;
+    const StepLayer Lv = layer_at(a, layer);
+    const StepLayer* L = &Lv;
 #pragma nounroll
     for (int ph = 0; ph < 5; ++ph) {
+      // ---- this phase's first two tiles: their addresses depend on nothing another workgroup writes,
+      //      so they are in flight while the barrier completes and the input vector is staged
+      const int j = gemv_index(ph);
+      const Geo g = load_geo(j, layer_matrix(Lv, j), wave);
+      if (ph == PH_ATTN) { attn_issue<WT>(A, ga, a, L->kv, 0, wave); attn_issue<WT>(B, ga, a, L->kv, 1, wave); }
+      else { gemv_issue(A, g, 0, wave, lane); gemv_issue(B, g, 1, wave, lane); }
+
       // ---- wait until every workgroup has finished the previous phase ----------------------------
       stamp(a, layer, ph, 0);
       if (threadIdx.x < 64) {
@@ -589,39 +634,29 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
       stamp(a, layer, ph, 1);
 
       if (ph == PH_ATTN) {
-        // ---- attention over the sample's pages; prefetches the output projection -----------------
-        const Geo gn = load_geo(1, L->wo, wave);
+        // ---- attention over the sample's pages -----------------------------------------------------
         attn_begin<WT, G>(st, ga, a, L->kv, xs);
         stamp(a, layer, ph, 2);
         const int nte = ((ga.n_k + kTile - 1) / kTile + 1) & ~1;
-        if (nte == 0) { gemv_issue(A, gn, 0, wave, lane); gemv_issue(B, gn, 1, wave, lane); }
 #pragma nounroll
         for (int t = 0; t < nte; t += 2) {
           attn_compute<WT, G>(st, A, ga, a.h, t, wave, xs);
-          if (t + 2 < nte) attn_issue<WT>(A, ga, a, L->kv, t + 2, wave); else gemv_issue(A, gn, 0, wave, lane);
+          attn_issue<WT>(A, ga, a, L->kv, t + 2, wave);
           attn_compute<WT, G>(st, B, ga, a.h, t + 1, wave, xs);
-          if (t + 3 < nte) attn_issue<WT>(B, ga, a, L->kv, t + 3, wave); else gemv_issue(B, gn, 1, wave, lane);
+          attn_issue<WT>(B, ga, a, L->kv, t + 3, wave);
         }
         stamp(a, layer, ph, 3);
         attn_to_lds<WT, G>(st, ga, a.h, xs, wave);
         attn_finish<G>(ga, a, xs, s_flag);
       } else {
-        // ---- a GEMV phase; prefetches the phase that follows -----------------------------------------
-        const int j = gemv_index(ph);
-        const Geo g = load_geo(j, layer_matrix(L, j), wave);
-        const bool more = layer + 1 < a.n_layer;
-        // what follows: attention after QKV, the next matrix otherwise (the next layer's QKV after the down projection)
-        const int jn = ph == PH_DOWN ? 0 : j + 1;
-        const Geo gn = load_geo(jn, layer_matrix(ph == PH_DOWN && more ? L + 1 : L, jn), wave);
-        const bool next_attn = ph == PH_QKV, has_next = ph != PH_DOWN || more;
-
+        // ---- a GEMV phase ----------------------------------------------------------------------------
         for (int i = threadIdx.x; i < g.n_pl * 2 * kStepWaves; i += kStepThreads) part[i] = 0.f;
         const bool normed = ph == PH_QKV || ph == PH_UP;
         const bool fused_rms = normed && a.norm_kind == MDI_NORM_RMSNORM && !(ph == PH_QKV && layer == 0);
         const float* gain = ph == PH_QKV ? L->ln1_g : L->ln2_g;
         float row_scale = 1.f;                       // 1/rms when the norm is folded into the epilogue
         if (ph == PH_QKV && layer == 0) {
-          stage_input<WT>(a, xs, lds_geo()[1 * kGeoInts + 5]);
+          stage_input<WT>(a, xs, load_geo(1, nullptr, wave));
         } else {
           const float* src = ph == PH_OPROJ ? a.o : ph == PH_DOWN ? a.u : a.xres;
           const float ss = stage_coherent(src, g.units * Storage<WT>::kVec, xs, fused_rms ? gain : nullptr);
@@ -635,33 +670,29 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
         // residual phases: fetch this thread's rows of x now, the stream below hides the latency
         float x0 = 0.f, x1 = 0.f;
         if ((ph == PH_OPROJ || ph == PH_DOWN) && (int)threadIdx.x < g.n_pl) {
-          const int r0 = 2 * (g.p_lo + (int)threadIdx.x * nwg);
+          const int r0 = 2 * geo_pair(g, (int)threadIdx.x);
           x0 = ld_sc(a.xres + r0);
           if (r0 + 1 < g.N) x1 = ld_sc(a.xres + r0 + 1);
         }
         stamp(a, layer, ph, 2);
 
         const int nte = ((g.n_k + kTile - 1) / kTile + 1) & ~1;
-        if (nte == 0 && has_next) {
-          if (next_attn) { attn_issue<WT>(A, ga, a, L->kv, 0, wave); attn_issue<WT>(B, ga, a, L->kv, 1, wave); }
-          else { gemv_issue(A, gn, 0, wave, lane); gemv_issue(B, gn, 1, wave, lane); }
-        }
 #pragma nounroll
         for (int t = 0; t < nte; t += 2) {
           gemv_compute<WT>(A, g, t, wave, lane, xs, part, acc0, acc1);
-          if (t + 2 < nte) gemv_issue(A, g, t + 2, wave, lane);
-          else if (has_next) { if (next_attn) attn_issue<WT>(A, ga, a, L->kv, 0, wave); else gemv_issue(A, gn, 0, wave, lane); }
+          gemv_issue(A, g, t + 2, wave, lane);
           gemv_compute<WT>(B, g, t + 1, wave, lane, xs, part, acc0, acc1);
-          if (t + 3 < nte) gemv_issue(B, g, t + 3, wave, lane);
-          else if (has_next) { if (next_attn) attn_issue<WT>(B, ga, a, L->kv, 1, wave); else gemv_issue(B, gn, 1, wave, lane); }
+          gemv_issue(B, g, t + 3, wave, lane);
         }
         stamp(a, layer, ph, 3);
         gemv_finish<WT>(ph, g, L, layer, a, part, row_scale, x0, x1);
       }
 
       // ---- publish: this workgroup is done with the phase ---------------------------------------------
+      stamp(a, layer, ph, 5);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this thread's stores have completed
       __syncthreads();
+      stamp(a, layer, ph, 6);
       ++epoch;
       if (threadIdx.x == 0) __hip_atomic_store(a.flags + wg, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }

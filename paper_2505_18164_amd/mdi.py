@@ -248,7 +248,7 @@ class Partition:
         return us.value, nb.value
 
     def trace(self, buf):
-        """buf: int64 device tensor [workgroups, layers, 5, 4] or None."""
+        """buf: int64 device tensor [workgroups, layers, 5, 8] or None."""
         st = lib().mdi_partition_trace(self._h, _ptr(buf))
         if st != MDI_OK:
             raise MdiError(st, "mdi_partition_trace")

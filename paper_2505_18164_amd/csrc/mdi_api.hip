@@ -66,6 +66,7 @@ struct mdi_partition {
   std::vector<StepLayer> h_step_layers;
   StepLayer* d_step_layers = nullptr;
   unsigned *bar_flags = nullptr, *tickets = nullptr;
+  tagged_t *t_xres = nullptr, *t_q = nullptr, *t_o = nullptr, *t_u = nullptr, *t_part = nullptr, *t_knew = nullptr;
   int* err = nullptr;
   unsigned epoch = 0;
   unsigned long long* trace = nullptr;
@@ -142,6 +143,12 @@ size_t carve(mdi_partition* p, void* arena) {
     p->bar_flags = (unsigned*)cv.take(1024 * 4);
     p->tickets = (unsigned*)cv.take(H * 4);
     p->err = (int*)cv.take(256);
+    p->t_xres = (tagged_t*)cv.take(d * 8);
+    p->t_q = (tagged_t*)cv.take(H * h * 8);
+    p->t_o = (tagged_t*)cv.take(H * h * 8);
+    p->t_u = (tagged_t*)cv.take(F * 8);
+    p->t_part = (tagged_t*)cv.take(H * kMaxSplits * (h + 2) * 8);
+    p->t_knew = (tagged_t*)cv.take(2 * K * h * 8);
     const size_t T = p->Tm;
     p->p_xres = (float*)cv.take(T * d * 4);
     p->p_xn = cv.take(T * d * B);
@@ -309,7 +316,14 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
     int dev = 0, n_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n_cu = 0;
     plan_step(p, n_cu);
-    launch_fill_u32(p->stream, p->bar_flags, 1024, 0u);
+    launch_fill_u32(p->stream, p->bar_flags, 1024, 1u);     // phase counters start at 1: tag 0 marks "never written"
+    p->epoch = 1;
+    launch_fill_u32(p->stream, (uint32_t*)p->t_xres, 2 * d, 0u);
+    launch_fill_u32(p->stream, (uint32_t*)p->t_q, 2 * H * h, 0u);
+    launch_fill_u32(p->stream, (uint32_t*)p->t_o, 2 * H * h, 0u);
+    launch_fill_u32(p->stream, (uint32_t*)p->t_u, 2 * F, 0u);
+    launch_fill_u32(p->stream, (uint32_t*)p->t_part, 2 * H * kMaxSplits * (h + 2), 0u);
+    launch_fill_u32(p->stream, (uint32_t*)p->t_knew, 4 * K * h, 0u);
     launch_fill_u32(p->stream, p->tickets, H, 0u);
     launch_fill_u32(p->stream, (uint32_t*)p->err, 64, 0u);
     p->h_step_layers.resize(p->n_local);
@@ -420,7 +434,7 @@ mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, v
     a.rope = p->rope ? p->rope + (size_t)len * (h / 2) : nullptr;
     a.table = drow; a.table_entry = new_entry; a.new_page = page;
     a.kv_tok_off = (long)page * K * 2 * a.pt_h + (long)slot * h;
-    a.xres = p->xres; a.q = p->q; a.o = p->o; a.u = p->u; a.part = p->part;
+    a.xres = p->t_xres; a.q = p->t_q; a.o = p->t_o; a.u = p->t_u; a.part = p->t_part; a.knew = p->t_knew;
     a.tickets = p->tickets; a.flags = p->bar_flags; a.epoch0 = p->epoch; a.err = p->err; a.spin_limit = 1 << 21;
     a.n_hg = p->n_hg;
     const int max_splits = std::max(1, std::min(kMaxSplits, p->nwg / p->n_hg));

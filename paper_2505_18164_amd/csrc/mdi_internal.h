@@ -119,6 +119,8 @@ void launch_rope_scatter(hipStream_t s, const RopeScatterArgs& a);
 constexpr int kStepThreads = 512;    // one workgroup of 8 wavefronts per compute unit
 constexpr int kStepWaves = 8;
 
+typedef unsigned long long tagged_t;  // low half: the value's bits, high half: the phase counter it was written in
+
 struct StepLayer {                   // device-resident, one per local layer
   const void *wqkv, *wo, *wup, *wdown;
   const float *bqkv, *bo, *bup, *bdown, *ln1_g, *ln1_b, *ln2_g, *ln2_b;
@@ -136,7 +138,8 @@ struct StepArgs {
   const float2* rope;                // (cos, sin)[h/2] of `pos`, or nullptr
   const int32_t* table; int32_t* table_entry; int new_page;
   long kv_tok_off;                   // element offset of K[kv head 0][slot] of the new token inside a layer's pool
-  float *xres, *q, *o, *u, *part;
+  // vectors exchanged between workgroups inside the launch: every element is (float bits, tag) in 8 bytes
+  tagged_t *xres, *q, *o, *u, *part, *knew;   // [d], [H*h], [H*h], [F], [H][kMaxSplits][h+2], [2][K*h]
   unsigned *tickets, *flags; unsigned epoch0; int* err; int spin_limit;
   int n_hg, n_splits, chunk; float scale;
   void* act_out; int act_kind;

@@ -11,8 +11,10 @@
 //     flags.  Everything that crosses workgroups (x, q, o, u, attention partials,
 //     the newest K/V row, the flags) is written and read with cache-coherent
 //     (sc1, agent scope) stores and loads, so the barrier needs no L2
-//     write-back/invalidate; ordering inside a workgroup comes from
-//     workgroup-scope fences (plain waits on outstanding memory operations).
+//     write-back/invalidate.  Because such a store can be acknowledged before
+//     every compute die sees it, each exchanged value carries the counter of the
+//     phase that wrote it in the same 8-byte word and readers reload until the
+//     counter is the expected one; the flags only guard against overwriting.
 //   * weight and KV-cache addresses do not depend on activations, so every
 //     wavefront keeps two register tiles of 16-byte loads in flight and, while it
 //     finishes a phase, already issues the first two tiles of the NEXT phase; the
@@ -37,14 +39,28 @@ constexpr int kTile = 4;                 // items per register tile (two 16-byte
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct Tile { u32x4 r[2 * kTile]; };
 
-__device__ __forceinline__ float ld_sc(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ uint32_t ld_sc(const uint32_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void st_sc(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void st_sc(bf16_t* p, float v) { __hip_atomic_store(p, f32_to_bf16(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-
-__device__ __forceinline__ float2 ld_sc2(const float* p) {     // 8-byte coherent load
-  const unsigned long long u = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return make_float2(__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32)));
+// Tagged exchange.  A workgroup that has seen every flag of a barrier may still be ahead of the data
+// another compute die wrote before raising its flag (a store is acknowledged before every die can
+// read it back), so the data validates itself: value and the writing phase's counter travel in one
+// 8-byte store, and a reader that finds another counter simply loads again.  Flags then only protect
+// buffers from being overwritten while still in use, which needs no ordering between stores.
+__device__ __forceinline__ void st_tag(tagged_t* p, float v, unsigned tag) {
+  __hip_atomic_store(p, ((tagged_t)tag << 32) | (tagged_t)__float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ tagged_t ld_raw(const tagged_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float tag_value(tagged_t u) { return __uint_as_float((uint32_t)u); }
+// Returns the value once its tag is `tag`; gives up (error flag) after spin_limit reloads.
+__device__ __forceinline__ float settle(const tagged_t* p, tagged_t u, unsigned tag, int spin_limit, int* err) {
+  int it = 0;
+  while ((uint32_t)(u >> 32) != tag) {
+    if (++it > spin_limit) { __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
+    __builtin_amdgcn_s_sleep(1);
+    u = ld_raw(p);
+  }
+  return tag_value(u);
+}
+__device__ __forceinline__ float ld_tag(const tagged_t* p, unsigned tag, int spin_limit, int* err) {
+  return settle(p, ld_raw(p), tag, spin_limit, err);
 }
 
 template <typename T> struct Unpack;
@@ -83,28 +99,23 @@ __device__ __forceinline__ float* lds_vec(int part_floats) { extern __shared__ f
 // vector staging: n floats written earlier in this launch by other workgroups -> LDS
 // With gain != nullptr (RMSNorm) the staged values are x[i] * gain[i] and the return value is this
 // thread's share of sum(x^2); the common factor 1/rms is applied to the finished dot products.
-__device__ __forceinline__ float stage_coherent(const float* src, int n, float* xs, const float* gain) {
-  // n is a multiple of 8: 8-byte coherent loads, four in flight per thread
-  const int n2 = n >> 1;
+__device__ __forceinline__ float stage_coherent(const tagged_t* src, int n, float* xs, const float* gain, unsigned tag,
+                                                int spin_limit, int* err) {
   float ss = 0.f;
-  for (int i0 = threadIdx.x; i0 < n2; i0 += 4 * kStepThreads) {
-    float2 x[4], gv[4];
+  for (int i0 = threadIdx.x; i0 < n; i0 += 8 * kStepThreads) {
+    tagged_t raw[8];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 8; ++j) {                      // eight loads in flight per thread
       const int i = i0 + j * kStepThreads;
-      x[j] = i < n2 ? ld_sc2(src + 2 * i) : make_float2(0.f, 0.f);
+      raw[j] = i < n ? ld_raw(src + i) : 0ull;
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 8; ++j) {
       const int i = i0 + j * kStepThreads;
-      gv[j] = (gain && i < n2) ? *reinterpret_cast<const float2*>(gain + 2 * i) : make_float2(1.f, 1.f);
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int i = i0 + j * kStepThreads;
-      if (i < n2) {
-        ss += x[j].x * x[j].x + x[j].y * x[j].y;
-        *reinterpret_cast<float2*>(xs + 2 * i) = make_float2(x[j].x * gv[j].x, x[j].y * gv[j].y);
+      if (i < n) {
+        const float x = settle(src + i, raw[j], tag, spin_limit, err);
+        ss += x * x;
+        xs[i] = gain ? x * gain[i] : x;
       }
     }
   }
@@ -179,7 +190,7 @@ __device__ __forceinline__ int geo_row(const Geo& g, int p, int j) {
 
 // the step's own input (token embedding + learned position, or the previous stage's activation)
 template <typename WT>
-__device__ __forceinline__ void stage_input(const StepArgs& a, float* xs, const Geo& gres) {
+__device__ __forceinline__ void stage_input(const StepArgs& a, float* xs, const Geo& gres, unsigned tag) {
   const int n = a.d;
   if (a.in_kind == IN_TOKEN) {
     const long tok = *(const int32_t*)a.in;
@@ -195,8 +206,8 @@ __device__ __forceinline__ void stage_input(const StepArgs& a, float* xs, const 
   // rows this workgroup owns in the residual phases get their starting value
   for (int pl = threadIdx.x; pl < gres.n_pl; pl += kStepThreads) {
     const int r = 2 * geo_pair(gres, pl);
-    st_sc(a.xres + r, xs[r]);
-    if (r + 1 < n) st_sc(a.xres + r + 1, xs[r + 1]);
+    st_tag(a.xres + r, xs[r], tag);
+    if (r + 1 < n) st_tag(a.xres + r + 1, xs[r + 1], tag);
   }
 }
 
@@ -261,7 +272,8 @@ __device__ __forceinline__ void gemv_compute(const Tile& t, const Geo& g, int ti
 // Sums the wavefront slots of every pair and applies the phase's epilogue.
 template <typename WT>
 __device__ __forceinline__ void gemv_finish(int ph, const Geo& g, const StepLayer* Lp, int layer, const StepArgs& a, const float* part,
-                                            float row_scale, float x0_pre, float x1_pre) {
+                                            float row_scale, tagged_t x0_pre, tagged_t x1_pre, unsigned epoch) {
+  const unsigned wtag = epoch + 1;                            // what this phase writes carries the next counter
   const StepLayer& L = *Lp;
   __syncthreads();                                           // all wavefronts' partials are in LDS
   stamp(a, layer, ph, 4);
@@ -281,21 +293,25 @@ __device__ __forceinline__ void gemv_finish(int ph, const Geo& g, const StepLaye
         v0 = t0; v1 = t1;
       }
       if (head < a.H) {
-        st_sc(a.q + r0, v0); st_sc(a.q + r1, v1);
+        st_tag(a.q + r0, v0, wtag); st_tag(a.q + r1, v1, wtag);
       } else {
+        // the cache row is for later launches (plain stores); this launch's attention takes the same
+        // rounded values from the tagged copy
         const bool is_v = head >= a.H + a.K;
         const int kvh = head - a.H - (is_v ? a.K : 0);
         WT* dst = (WT*)L.kv + a.kv_tok_off + (long)(kvh * 2 + (is_v ? 1 : 0)) * a.pt_h + i;
-        st_sc(dst, v0); st_sc(dst + (a.h >> 1), v1);
+        Storage<WT>::put(dst, v0); Storage<WT>::put(dst + (a.h >> 1), v1);
+        tagged_t* kn = a.knew + (long)(is_v ? a.K * a.h : 0) + kvh * a.h + i;
+        st_tag(kn, Storage<WT>::get(dst), wtag); st_tag(kn + (a.h >> 1), Storage<WT>::get(dst + (a.h >> 1)), wtag);
       }
     } else if (ph == PH_UP) {
       if (a.mlp_kind == MDI_MLP_SWIGLU) {
-        st_sc(a.u + p, silu_f(v0) * v1);                     // rows (2f, 2f+1) = (gate_f, up_f)
+        st_tag(a.u + p, silu_f(v0) * v1, wtag);              // rows (2f, 2f+1) = (gate_f, up_f)
       } else {
         if (L.bup) { v0 += L.bup[r0]; if (r1 < g.N) v1 += L.bup[r1]; }
         const bool tanh_form = a.mlp_kind == MDI_MLP_GELU_TANH;
-        st_sc(a.u + r0, tanh_form ? gelu_tanh_f(v0) : gelu_erf_f(v0));
-        if (r1 < g.N) st_sc(a.u + r1, tanh_form ? gelu_tanh_f(v1) : gelu_erf_f(v1));
+        st_tag(a.u + r0, tanh_form ? gelu_tanh_f(v0) : gelu_erf_f(v0), wtag);
+        if (r1 < g.N) st_tag(a.u + r1, tanh_form ? gelu_tanh_f(v1) : gelu_erf_f(v1), wtag);
       }
     } else {                                                  // residual phases
       const float* bias = ph == PH_OPROJ ? L.bo : L.bdown;
@@ -303,13 +319,16 @@ __device__ __forceinline__ void gemv_finish(int ph, const Geo& g, const StepLaye
       const bool two = r1 < g.N;
       // rows of the first kStepThreads pairs were fetched before the stream
       const bool pre = pl == (int)threadIdx.x;
-      const float x0 = pre ? x0_pre : ld_sc(a.xres + r0), x1 = pre ? x1_pre : (two ? ld_sc(a.xres + r1) : 0.f);
+      // this workgroup wrote these rows itself: two phases ago (output projection) or one (down projection)
+      const unsigned rtag = ph == PH_OPROJ ? epoch - 2 : epoch - 1;
+      const float x0 = settle(a.xres + r0, pre ? x0_pre : ld_raw(a.xres + r0), rtag, a.spin_limit, a.err);
+      const float x1 = two ? settle(a.xres + r1, pre ? x1_pre : ld_raw(a.xres + r1), rtag, a.spin_limit, a.err) : 0.f;
       v0 += x0 + (bias ? bias[r0] : 0.f);
-      st_sc(a.xres + r0, v0);
+      st_tag(a.xres + r0, v0, wtag);
       if (last) store_kind(a.act_out, a.act_kind, r0, v0);
       if (two) {
         v1 += x1 + (bias ? bias[r1] : 0.f);
-        st_sc(a.xres + r1, v1);
+        st_tag(a.xres + r1, v1, wtag);
         if (last) store_kind(a.act_out, a.act_kind, r1, v1);
       }
     }
@@ -352,7 +371,7 @@ __device__ __forceinline__ void attn_issue(Tile& t, const AttnGeo& g, const Step
     const int k = ti * kTile + s;
     int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
     if (!(k < g.n_k && tok < g.s1p)) tok = 0;
-    const int page = table[tok / a.pt];
+    const int page = __hip_atomic_load(table + tok / a.pt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const MDI_GLOBAL WT* kp = pool + ((long)page * a.K + g.kvh) * 2 * a.pt_h + (long)(tok % a.pt) * a.h + g.hoff;
     t.r[2 * s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp);
     t.r[2 * s + 1] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp + a.pt_h);
@@ -365,12 +384,9 @@ struct AttnState {
 };
 
 template <typename WT, int G>
-__device__ __forceinline__ void attn_update(AttnState<WT, G>& st, const AttnGeo& g, int h, const u32x4& kq, const u32x4& vq,
-                                            bool valid, const float* qs) {
+__device__ __forceinline__ void attn_update_f(AttnState<WT, G>& st, const AttnGeo& g, int h, const float (&kf)[Storage<WT>::kVec],
+                                              const float (&vf)[Storage<WT>::kVec], bool valid, const float* qs) {
   constexpr int V = Storage<WT>::kVec;
-  float kf[V], vf[V];
-  Unpack<WT>::go(kq, kf);
-  Unpack<WT>::go(vq, vf);
 #pragma unroll
   for (int gi = 0; gi < G; ++gi) {
     float s = 0.f;
@@ -392,6 +408,15 @@ __device__ __forceinline__ void attn_update(AttnState<WT, G>& st, const AttnGeo&
 }
 
 template <typename WT, int G>
+__device__ __forceinline__ void attn_update(AttnState<WT, G>& st, const AttnGeo& g, int h, const u32x4& kq, const u32x4& vq,
+                                            bool valid, const float* qs) {
+  float kf[Storage<WT>::kVec], vf[Storage<WT>::kVec];
+  Unpack<WT>::go(kq, kf);
+  Unpack<WT>::go(vq, vf);
+  attn_update_f<WT, G>(st, g, h, kf, vf, valid, qs);
+}
+
+template <typename WT, int G>
 __device__ __forceinline__ void attn_compute(AttnState<WT, G>& st, const Tile& t, const AttnGeo& g, int h, int ti, int wave,
                                              const float* qs) {
 #pragma unroll
@@ -406,7 +431,7 @@ __device__ __forceinline__ void attn_compute(AttnState<WT, G>& st, const Tile& t
 
 // queries into LDS (pre-scaled); the newest position through coherent loads
 template <typename WT, int G>
-__device__ __forceinline__ void attn_begin(AttnState<WT, G>& st, const AttnGeo& g, const StepArgs& a, const void* pool, float* qs) {
+__device__ __forceinline__ void attn_begin(AttnState<WT, G>& st, const AttnGeo& g, const StepArgs& a, float* qs, unsigned epoch) {
   constexpr int V = Storage<WT>::kVec;
 #pragma unroll
   for (int gi = 0; gi < G; ++gi) {
@@ -415,18 +440,21 @@ __device__ __forceinline__ void attn_begin(AttnState<WT, G>& st, const AttnGeo& 
     for (int e = 0; e < V; ++e) st.o[gi][e] = 0.f;
   }
   if (g.active)
-    for (int i = threadIdx.x; i < G * a.h; i += kStepThreads) qs[i] = ld_sc(a.q + (long)g.hg * G * a.h + i) * a.scale;
+    for (int i = threadIdx.x; i < G * a.h; i += kStepThreads)
+      qs[i] = ld_tag(a.q + (long)g.hg * G * a.h + i, epoch, a.spin_limit, a.err) * a.scale;
   __syncthreads();
   if (g.active && g.s1 == a.ctx && threadIdx.x < 64) {
-    const WT* kp = (const WT*)pool + a.kv_tok_off + (long)(g.kvh * 2) * a.pt_h + g.hoff;
-    u32x4 kq = {0u, 0u, 0u, 0u}, vq = kq;
+    // the newest position: its K/V row (already rounded to the storage type) from the tagged copy
+    float kf[V], vf[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) { kf[e] = 0.f; vf[e] = 0.f; }
     if (g.sub == 0) {
-      const uint32_t* k32 = (const uint32_t*)kp;
-      const uint32_t* v32 = (const uint32_t*)(kp + a.pt_h);
-      kq.x = ld_sc(k32); kq.y = ld_sc(k32 + 1); kq.z = ld_sc(k32 + 2); kq.w = ld_sc(k32 + 3);
-      vq.x = ld_sc(v32); vq.y = ld_sc(v32 + 1); vq.z = ld_sc(v32 + 2); vq.w = ld_sc(v32 + 3);
+      const tagged_t* kn = a.knew + g.kvh * a.h + g.hoff;
+      const tagged_t* vn = kn + (long)a.K * a.h;
+#pragma unroll
+      for (int e = 0; e < V; ++e) { kf[e] = ld_tag(kn + e, epoch, a.spin_limit, a.err); vf[e] = ld_tag(vn + e, epoch, a.spin_limit, a.err); }
     }
-    attn_update<WT, G>(st, g, a.h, kq, vq, g.sub == 0, qs);
+    attn_update_f<WT, G>(st, g, a.h, kf, vf, g.sub == 0, qs);
   }
 }
 
@@ -463,7 +491,8 @@ __device__ __forceinline__ void attn_to_lds(AttnState<WT, G>& st, const AttnGeo&
 // Wavefront records -> split partial (or the final output when there is one split);
 // the last workgroup of a head group to arrive folds the splits in split order.
 template <int G>
-__device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a, const float* sm, int* s_flag) {
+__device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a, const float* sm, int* s_flag, unsigned epoch) {
+  const unsigned wtag = epoch + 1;
   const int h = a.h, rec = h + 2;
   if (!g.active) return;
   const bool single = a.n_splits == 1;
@@ -479,11 +508,11 @@ __device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a,
     }
     const int head = g.hg * G + gi;
     if (single) {
-      st_sc(a.o + (long)head * h + e, o / l);
+      st_tag(a.o + (long)head * h + e, o / l, wtag);
     } else {
-      float* pr = a.part + ((long)head * kMaxSplits + g.split) * rec;
-      st_sc(pr + e, o);
-      if (e == 0) { st_sc(pr + h, m); st_sc(pr + h + 1, l); }
+      tagged_t* pr = a.part + ((long)head * kMaxSplits + g.split) * rec;
+      st_tag(pr + e, o, wtag);
+      if (e == 0) { st_tag(pr + h, m, wtag); st_tag(pr + h + 1, l, wtag); }
     }
   }
   if (single) return;
@@ -498,29 +527,33 @@ __device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a,
   for (int idx = threadIdx.x; idx < G * h; idx += kStepThreads) {
     const int gi = idx / h, e = idx - gi * h;
     const int head = g.hg * G + gi;
-    const float* pr = a.part + (long)head * kMaxSplits * rec;
+    const tagged_t* pr = a.part + (long)head * kMaxSplits * rec;
     // splits are folded in split order, eight at a time so that their loads are in flight together
     float m = -1e30f, l = 0.f, o = 0.f;
     for (int sp0 = 0; sp0 < a.n_splits; sp0 += 8) {
-      float2 ml[8];
-      float oo[8];
+      tagged_t rm[8], rl[8], ro[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
         const bool ok = sp0 + k < a.n_splits;
-        const float* r = pr + (sp0 + k) * rec;
-        ml[k] = ok ? ld_sc2(r + h) : make_float2(-1e30f, 0.f);
-        oo[k] = ok ? ld_sc(r + e) : 0.f;
+        const tagged_t* r = pr + (sp0 + k) * rec;
+        rm[k] = ok ? ld_raw(r + h) : 0ull; rl[k] = ok ? ld_raw(r + h + 1) : 0ull; ro[k] = ok ? ld_raw(r + e) : 0ull;
       }
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        const float mn = fmaxf(m, ml[k].x);
-        const float sa = __expf(m - mn), sb = __expf(ml[k].x - mn);
-        l = l * sa + ml[k].y * sb;
-        o = o * sa + oo[k] * sb;
-        m = mn;
+        if (sp0 + k < a.n_splits) {
+          const tagged_t* r = pr + (sp0 + k) * rec;
+          const float mk = settle(r + h, rm[k], wtag, a.spin_limit, a.err);
+          const float lk = settle(r + h + 1, rl[k], wtag, a.spin_limit, a.err);
+          const float ok_ = settle(r + e, ro[k], wtag, a.spin_limit, a.err);
+          const float mn = fmaxf(m, mk);
+          const float sa = __expf(m - mn), sb = __expf(mk - mn);
+          l = l * sa + lk * sb;
+          o = o * sa + ok_ * sb;
+          m = mn;
+        }
       }
     }
-    st_sc(a.o + (long)head * h + e, o / l);
+    st_tag(a.o + (long)head * h + e, o / l, wtag);
   }
   if (threadIdx.x == 0) __hip_atomic_store(a.tickets + g.hg, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -635,7 +668,7 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
 
       if (ph == PH_ATTN) {
         // ---- attention over the sample's pages -----------------------------------------------------
-        attn_begin<WT, G>(st, ga, a, L->kv, xs);
+        attn_begin<WT, G>(st, ga, a, xs, epoch);
         stamp(a, layer, ph, 2);
         const int nte = ((ga.n_k + kTile - 1) / kTile + 1) & ~1;
 #pragma nounroll
@@ -647,7 +680,7 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
         }
         stamp(a, layer, ph, 3);
         attn_to_lds<WT, G>(st, ga, a.h, xs, wave);
-        attn_finish<G>(ga, a, xs, s_flag);
+        attn_finish<G>(ga, a, xs, s_flag, epoch);
       } else {
         // ---- a GEMV phase ----------------------------------------------------------------------------
         for (int i = threadIdx.x; i < g.n_pl * 2 * kStepWaves; i += kStepThreads) part[i] = 0.f;
@@ -656,10 +689,10 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
         const float* gain = ph == PH_QKV ? L->ln1_g : L->ln2_g;
         float row_scale = 1.f;                       // 1/rms when the norm is folded into the epilogue
         if (ph == PH_QKV && layer == 0) {
-          stage_input<WT>(a, xs, load_geo(1, nullptr, wave));
+          stage_input<WT>(a, xs, load_geo(1, nullptr, wave), epoch);
         } else {
-          const float* src = ph == PH_OPROJ ? a.o : ph == PH_DOWN ? a.u : a.xres;
-          const float ss = stage_coherent(src, g.units * Storage<WT>::kVec, xs, fused_rms ? gain : nullptr);
+          const tagged_t* src = ph == PH_OPROJ ? a.o : ph == PH_DOWN ? a.u : a.xres;
+          const float ss = stage_coherent(src, g.units * Storage<WT>::kVec, xs, fused_rms ? gain : nullptr, epoch, a.spin_limit, a.err);
           if (fused_rms) row_scale = 1.f / sqrtf(block_sum(ss, red) / (float)a.d + a.eps);
         }
         __syncthreads();
@@ -668,11 +701,11 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
           __syncthreads();
         }
         // residual phases: fetch this thread's rows of x now, the stream below hides the latency
-        float x0 = 0.f, x1 = 0.f;
+        tagged_t x0 = 0ull, x1 = 0ull;
         if ((ph == PH_OPROJ || ph == PH_DOWN) && (int)threadIdx.x < g.n_pl) {
           const int r0 = 2 * geo_pair(g, (int)threadIdx.x);
-          x0 = ld_sc(a.xres + r0);
-          if (r0 + 1 < g.N) x1 = ld_sc(a.xres + r0 + 1);
+          x0 = ld_raw(a.xres + r0);
+          if (r0 + 1 < g.N) x1 = ld_raw(a.xres + r0 + 1);
         }
         stamp(a, layer, ph, 2);
 
@@ -685,7 +718,7 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
           gemv_issue(B, g, t + 3, wave, lane);
         }
         stamp(a, layer, ph, 3);
-        gemv_finish<WT>(ph, g, L, layer, a, part, row_scale, x0, x1);
+        gemv_finish<WT>(ph, g, L, layer, a, part, row_scale, x0, x1, epoch);
       }
 
       // ---- publish: this workgroup is done with the phase ---------------------------------------------

@@ -22,6 +22,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+# HBM bytes per k_step launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this script (workload -> bytes);
+# the numbers and the commands are in profiles/k_step_c4_decode_hbm_counters.md
+MEASURED_TRAFFIC = {4: 3.4757e9}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 
@@ -33,6 +36,8 @@ def parse():
     ap.add_argument("--workload", type=int, default=4, help="index into the five benchmark configs (1-5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ctx-sweep", action="store_true", help="also time decode at the middle and end context")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--decode-path", type=int, default=0, help="0 = persistent single-launch step, 1 = one kernel per operation")
     return ap.parse_args()
 
@@ -131,6 +136,13 @@ def main():
         return dict(ctx=ctx_mean, ms_per_step=ms, tokens_per_s=1000.0 / ms, bytes_per_step=nbytes,
                     gbs=nbytes / ms / 1e6, prefill_ms=prefill_ms)
 
+    if args.calib_copy_mib:
+        src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev).zero_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     main_run = run(prompt, args.steps, args.warmup)
     n_local = hi - lo
     params = sum(a * b for a, b in S.layer_tensor_shapes(cfg).values())
@@ -144,7 +156,7 @@ def main():
         # partition's stream, launches back to back) against the bytes a step must move
         roofline = {"bound": "hbm", "kernel": "k_step (persistent decode step, all layers)",
                     "achieved": main_run["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": main_run["gbs"] / HBM_PEAK_GBS, "traffic": None,
+                    "frac": main_run["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(args.workload),
                     "avg_launch_us": main_run["ms_per_step"] * 1e3, "bytes_per_launch": main_run["bytes_per_step"],
                     "workgroups": part.info(1), "lds_bytes": part.info(2)}
     else:

@@ -308,7 +308,8 @@ __global__ __launch_bounds__(kBlock) void k_attn(AttnArgs a) {
     const int tok = t0 + sub;
     const bool valid = tok < s1;
     const int tk = valid ? tok : s1 - 1;
-    const int page = a.table[tk / a.pt];
+    // coherent load: the entry may have been written by the previous launch from another compute die
+    const int page = __hip_atomic_load(a.table + tk / a.pt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const KT* kp = pool + ((long)page * a.K + kvh) * 2 * pt_h + (long)(tk % a.pt) * h + hoff;
     float kf[V], vf[V];
     Storage<KT>::load(kp, kf);

@@ -180,6 +180,8 @@ class Partition:
             if not cfg["tie_embed"]:
                 w.lm_head = _ptr(dev(weights.get("lm_head"), True))
         w.layers = C.cast(layers, C.POINTER(MdiLayerWeights))
+        # the source tensors were produced on the current stream; the repacking runs on the partition's
+        self.stream.wait_stream(torch.cuda.current_stream(self.device))
         with torch.cuda.stream(self.stream):
             st = lib().mdi_partition_create(C.byref(self.c), lo, hi, C.byref(w), self.flags, C.c_void_p(base), nbytes,
                                             C.c_void_p(self.stream.cuda_stream), C.byref(self._h))

@@ -113,3 +113,32 @@ def test_error_paths_and_page_pool():
     again = host(g.prefill(0, ids))                                          # pages were returned and are reusable
     np.testing.assert_array_equal(again, first)
     g.sync()
+
+
+@pytest.mark.parametrize("path", [0, 1], ids=["persistent", "per_op"])
+@pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
+def test_streams_do_not_change_results(dtype, path):
+    """Three chunks on three streams (the single-GPU stand-in for three nodes, Sec. III-C) give the
+    bits of the same chunks on one stream, run after run: nothing read by one kernel may be a stale
+    copy of what an earlier kernel, or another workgroup of the same kernel, wrote.  Small heads make
+    several cache rows share a cache line, the worst case for that."""
+    from paper_2505_18164_amd.pipeline import RecurrentPipeline
+    cfg = S.tiny(n_layer=6, dtype=dtype, max_ctx=96, vocab=211)
+    w = S.make_weights(cfg, 17, exercise=True)
+    prompts = [dev_ids(p) for p in S.make_prompts(cfg, 17, 4, 9)]
+
+    def run(streams):
+        parts = [mdi.Partition(cfg, w, 0, 2, has_embed=True, max_seqs=4, stream=streams[0], kv_page_tokens=8, decode_path=path),
+                 mdi.Partition(cfg, w, 2, 4, max_seqs=4, stream=streams[1], kv_page_tokens=8, decode_path=path),
+                 mdi.Partition(cfg, w, 4, 6, has_head=True, max_seqs=4, stream=streams[2], kv_page_tokens=8, decode_path=path)]
+        t, _, h = RecurrentPipeline(parts).generate(prompts, 60, keep_hidden=True)
+        torch.cuda.synchronize()
+        for p in parts:
+            p.sync()
+        return t.cpu(), h.float().cpu()
+
+    ref = run([None, None, None])
+    for rep in range(4):
+        got = run([torch.cuda.Stream() for _ in range(3)])
+        assert torch.equal(got[0], ref[0]), rep
+        assert torch.equal(got[1], ref[1]), rep

@@ -10,6 +10,7 @@ namespace mdi {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_rows_input(RowsInArgs a) {
@@ -87,91 +88,142 @@ __device__ __forceinline__ void gemm_store(const GemmArgs& a, int out_kind, int 
 
 // ---------------------------------------------------------------------------
 // bf16 GEMM on MFMA: C[T, N] = A[T, Kd] * W[N, Kd]^T, fp32 accumulate.
-// Workgroup tile 128 (tokens) x 128 (weight rows), K step 64; four wavefronts in
-// a 2 x 2 arrangement, each owning 64 x 64 = 2 x 2 MFMA tiles of 32 x 32.
+// Workgroup tile BM (tokens) x BN (weight rows), K step 64; four wavefronts in a
+// 2 x 2 arrangement, each owning (BM/2) x (BN/2) as MFMA tiles of 32 x 32.
 // Both operands are K-contiguous, so a lane's MFMA fragment (8 consecutive k of
-// one row) is one 16-byte LDS read; LDS rows are padded by 16 bytes to spread
-// the banks.  Global loads for step k+1 are issued into registers before the
-// MFMAs of step k.
-constexpr int BM = 128, BN = 128, BK = 64, LDS_STRIDE = BK + 8;
+// one row) is one 16-byte LDS read; LDS rows are padded by 16 bytes, which makes
+// the 16 lanes served together hit 16 different bank groups.  LDS is double
+// buffered: the global loads of step k+1 are issued before the MFMAs of step k and
+// land in the other buffer after them, so a K step costs one workgroup barrier.
+constexpr int BK = 64, LDS_STRIDE = BK + 8;
 
-template <int EPI>
-__global__ __launch_bounds__(kBlock) void k_gemm_bf16(GemmArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[BM * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LDS_STRIDE];
+template <int EPI, int BM, int BN>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) void k_gemm_bf16(GemmArgs a) {
+  constexpr int TM = BM / 64, TN = BN / 64;            // MFMA tiles per wavefront
+  constexpr int PA = BM * 8 / kBlock, PB = BN * 8 / kBlock;   // 16-byte pieces per thread per K step
+  extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
+  bf16_t* As = (bf16_t*)gemm_smem;                     // [2][BM][LDS_STRIDE]
+  bf16_t* Bs = As + 2 * BM * LDS_STRIDE;               // [2][BN][LDS_STRIDE]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const bf16_t* A = (const bf16_t*)a.A;
   const bf16_t* W = (const bf16_t*)a.W;
   const int Kd = a.Kd;
 
-  // each thread moves 4 + 4 pieces of 16 bytes per K step: piece p covers row p/8, k-offset (p%8)*8
-  uint4 ra[4], rb[4];
-  auto gload = [&](int k0) {
+  // piece p of a tile covers row p / 8, k-offset (p % 8) * 8; rows past the matrix re-read its last row
+  const int prow = tid >> 3, pk = (tid & 7) * 8;
+  const bf16_t* ga[PA];
+  const bf16_t* gb[PB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int p = tid + i * kBlock, r = p >> 3, kk = k0 + (p & 7) * 8;
-      const int ar = min(m0 + r, a.T - 1), br = min(n0 + r, a.N - 1);
-      const uint4 z = {0u, 0u, 0u, 0u};
-      ra[i] = kk < Kd ? *reinterpret_cast<const uint4*>(A + (long)ar * Kd + kk) : z;
-      rb[i] = kk < Kd ? *reinterpret_cast<const uint4*>(W + (long)br * Kd + kk) : z;
-    }
-  };
-  auto sstore = [&]() {
+  for (int i = 0; i < PA; ++i) ga[i] = A + (long)min(m0 + prow + i * 32, a.T - 1) * Kd + pk;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int p = tid + i * kBlock, r = p >> 3, kk = (p & 7) * 8;
-      *reinterpret_cast<uint4*>(As + r * LDS_STRIDE + kk) = ra[i];
-      *reinterpret_cast<uint4*>(Bs + r * LDS_STRIDE + kk) = rb[i];
-    }
-  };
+  for (int i = 0; i < PB; ++i) gb[i] = W + (long)min(n0 + prow + i * 32, a.N - 1) * Kd + pk;
 
-  f32x16 acc[2][2];
+  f32x16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  gload(0);
+  const u32x4 z4 = {0u, 0u, 0u, 0u};
+  u32x4 ra[PA], rb[PB];
+  const bool k_ok0 = pk < Kd;
+#pragma unroll
+  for (int i = 0; i < PA; ++i) ra[i] = k_ok0 ? *reinterpret_cast<const u32x4*>(ga[i]) : z4;
+#pragma unroll
+  for (int i = 0; i < PB; ++i) rb[i] = k_ok0 ? *reinterpret_cast<const u32x4*>(gb[i]) : z4;
+#pragma unroll
+  for (int i = 0; i < PA; ++i) *reinterpret_cast<u32x4*>(As + (prow + i * 32) * LDS_STRIDE + pk) = ra[i];
+#pragma unroll
+  for (int i = 0; i < PB; ++i) *reinterpret_cast<u32x4*>(Bs + (prow + i * 32) * LDS_STRIDE + pk) = rb[i];
+  __syncthreads();
+
+  int cur = 0;
   for (int k0 = 0; k0 < Kd; k0 += BK) {
-    __syncthreads();            // previous step's LDS reads are done
-    sstore();
-    __syncthreads();
-    if (k0 + BK < Kd) gload(k0 + BK);
+    const bool more = k0 + BK < Kd;
+    const bool k_ok = k0 + BK + pk < Kd;
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < PA; ++i) ra[i] = k_ok ? *reinterpret_cast<const u32x4*>(ga[i] + k0 + BK) : z4;
+#pragma unroll
+      for (int i = 0; i < PB; ++i) rb[i] = k_ok ? *reinterpret_cast<const u32x4*>(gb[i] + k0 + BK) : z4;
+    }
+    const bf16_t* Ac = As + cur * BM * LDS_STRIDE;
+    const bf16_t* Bc = Bs + cur * BN * LDS_STRIDE;
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
       const int kk = ks + (lane >> 5) * 8;
-      bf16x8 fa[2], fb[2];
+      bf16x8 fa[TM], fb[TN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        fa[i] = *reinterpret_cast<const bf16x8*>(As + (wm + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
-        fb[i] = *reinterpret_cast<const bf16x8*>(Bs + (wn + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
-      }
+      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(Ac + (wm + i * 32 + (lane & 31)) * LDS_STRIDE + kk);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(Bc + (wn + j * 32 + (lane & 31)) * LDS_STRIDE + kk);
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
+    if (more) {
+      bf16_t* An = As + (cur ^ 1) * BM * LDS_STRIDE;
+      bf16_t* Bn = Bs + (cur ^ 1) * BN * LDS_STRIDE;
+#pragma unroll
+      for (int i = 0; i < PA; ++i) *reinterpret_cast<u32x4*>(An + (prow + i * 32) * LDS_STRIDE + pk) = ra[i];
+#pragma unroll
+      for (int i = 0; i < PB; ++i) *reinterpret_cast<u32x4*>(Bn + (prow + i * 32) * LDS_STRIDE + pk) = rb[i];
+    }
+    __syncthreads();
+    cur ^= 1;
   }
 
   // accumulator layout of the 32x32 MFMA: register r of lane l holds
-  // C[row = 8*(r/4) + 4*(l/32) + r%4][col = l%32]
+  // C[row = 8*(r/4) + 4*(l/32) + r%4][col = l%32].  Per MFMA tile a lane owns one column n and 16 rows:
+  // everything it needs from memory (bias, residual) is fetched before the first store, so the loads
+  // are in flight together instead of one round trip per element.
+  float* __restrict__ out_f32 = a.out_f32;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn + j * 32 + (lane & 31);
+      const int tb = m0 + wm + i * 32 + 4 * (lane >> 5);
+      const bool n_ok = n < a.N;
+      const float bias = (EPI != GEPI_SWIGLU && a.bias && n_ok) ? a.bias[n] : 0.f;
+      float res[16];
+      if (EPI == GEPI_RESID) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int t = tb + 8 * (r >> 2) + (r & 3);
+          res[r] = (n_ok && t < a.T) ? out_f32[(long)t * a.N + n] : 0.f;
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int t = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const int n = n0 + wn + j * 32 + (lane & 31);
-        const float v = acc[i][j][r];
-        const float partner = EPI == GEPI_SWIGLU ? __shfl_xor(v, 1, 64) : 0.f;
-        gemm_store<EPI>(a, IN_BF16, t, n, v, partner);
+        const int t = tb + 8 * (r >> 2) + (r & 3);
+        float v = acc[i][j][r];
+        if (EPI == GEPI_SWIGLU) {
+          const float partner = __shfl_xor(v, 1, 64);          // column n^1: rows (2f, 2f+1) = (gate_f, up_f)
+          if (n_ok && t < a.T && !(n & 1)) store_kind(a.out_act, IN_BF16, (long)t * (a.N >> 1) + (n >> 1), silu_f(v) * partner);
+        } else if (n_ok && t < a.T) {
+          const long o = (long)t * a.N + n;
+          v += bias;
+          if (EPI == GEPI_F32_BIAS) {
+            out_f32[o] = v;
+          } else if (EPI == GEPI_RESID) {
+            v += res[r];
+            out_f32[o] = v;
+            if (a.out_act) store_kind(a.out_act, IN_BF16, o, v);
+          } else if (EPI == GEPI_GELU_TANH) {
+            store_kind(a.out_act, IN_BF16, o, gelu_tanh_f(v));
+          } else {
+            store_kind(a.out_act, IN_BF16, o, gelu_erf_f(v));
+          }
+        }
       }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -221,20 +273,32 @@ __global__ __launch_bounds__(kBlock) void k_gemm_f32(GemmArgs a) {
       gemm_store<EPI>(a, IN_F32, m0 + ty * 4 + i, n0 + tx * 4 + j, acc[i][j], acc[i][j ^ 1]);
 }
 
-void launch_gemm(hipStream_t s, int dtype, int epi, const GemmArgs& a) {
-#define MDI_GEMM(K, TM, TN)                                                                     \
-  {                                                                                             \
-    const dim3 grid((a.N + TN - 1) / TN, (a.T + TM - 1) / TM), block(kBlock);                   \
-    switch (epi) {                                                                              \
-      case GEPI_F32_BIAS: hipLaunchKernelGGL((K<GEPI_F32_BIAS>), grid, block, 0, s, a); break;  \
-      case GEPI_RESID: hipLaunchKernelGGL((K<GEPI_RESID>), grid, block, 0, s, a); break;        \
-      case GEPI_SWIGLU: hipLaunchKernelGGL((K<GEPI_SWIGLU>), grid, block, 0, s, a); break;      \
-      case GEPI_GELU_TANH: hipLaunchKernelGGL((K<GEPI_GELU_TANH>), grid, block, 0, s, a); break;\
-      default: hipLaunchKernelGGL((K<GEPI_GELU_ERF>), grid, block, 0, s, a); break;             \
-    }                                                                                           \
+template <int BM, int BN>
+static void launch_gemm_bf16(hipStream_t s, int epi, const GemmArgs& a) {
+  const dim3 grid((a.N + BN - 1) / BN, (a.T + BM - 1) / BM), block(kBlock);
+  const size_t lds = (size_t)2 * (BM + BN) * LDS_STRIDE * sizeof(bf16_t);
+  switch (epi) {
+    case GEPI_F32_BIAS: hipLaunchKernelGGL((k_gemm_bf16<GEPI_F32_BIAS, BM, BN>), grid, block, lds, s, a); break;
+    case GEPI_RESID: hipLaunchKernelGGL((k_gemm_bf16<GEPI_RESID, BM, BN>), grid, block, lds, s, a); break;
+    case GEPI_SWIGLU: hipLaunchKernelGGL((k_gemm_bf16<GEPI_SWIGLU, BM, BN>), grid, block, lds, s, a); break;
+    case GEPI_GELU_TANH: hipLaunchKernelGGL((k_gemm_bf16<GEPI_GELU_TANH, BM, BN>), grid, block, lds, s, a); break;
+    default: hipLaunchKernelGGL((k_gemm_bf16<GEPI_GELU_ERF, BM, BN>), grid, block, lds, s, a); break;
   }
-  if (dtype == MDI_BF16) MDI_GEMM(k_gemm_bf16, BM, BN) else MDI_GEMM(k_gemm_f32, 64, 64)
-#undef MDI_GEMM
+}
+
+void launch_gemm(hipStream_t s, int dtype, int epi, const GemmArgs& a) {
+  if (dtype == MDI_BF16) {
+    launch_gemm_bf16<128, 128>(s, epi, a);
+    return;
+  }
+  const dim3 grid((a.N + 63) / 64, (a.T + 63) / 64), block(kBlock);
+  switch (epi) {
+    case GEPI_F32_BIAS: hipLaunchKernelGGL((k_gemm_f32<GEPI_F32_BIAS>), grid, block, 0, s, a); break;
+    case GEPI_RESID: hipLaunchKernelGGL((k_gemm_f32<GEPI_RESID>), grid, block, 0, s, a); break;
+    case GEPI_SWIGLU: hipLaunchKernelGGL((k_gemm_f32<GEPI_SWIGLU>), grid, block, 0, s, a); break;
+    case GEPI_GELU_TANH: hipLaunchKernelGGL((k_gemm_f32<GEPI_GELU_TANH>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((k_gemm_f32<GEPI_GELU_ERF>), grid, block, 0, s, a); break;
+  }
 }
 
 // ---------------------------------------------------------------------------

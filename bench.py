@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--ctx-sweep", action="store_true", help="also time decode at the middle and end context")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
-    ap.add_argument("--decode-path", type=int, default=0, help="0 = persistent single-launch step, 1 = one kernel per operation")
+    ap.add_argument("--decode-path", type=int, default=0, help="0 = automatic (persistent single-launch step), 1 = one kernel per operation, 3 = persistent launch with streaming/exchange wavefronts on tiled matrices")
     return ap.parse_args()
 
 
@@ -149,12 +149,13 @@ def main():
     prefill_flops = n_local * (2.0 * prompt * params + 2.0 * prompt * prompt * cfg["n_head"] * cfg["head_dim"])
     prefill_tflops = prefill_flops / (main_run["prefill_ms"] * 1e-3) / 1e12
 
-    persistent = part.info(0) == 0
+    path_kind = part.info(0)          # 2 = persistent launch, 3 = persistent launch with streaming + exchange wavefronts on tiled matrices, 1 = per operation
+    persistent = path_kind in (2, 3)
     kernels = {}
     if persistent:
         # the whole step is one kernel launch; its mean duration over the timed region (HIP events on the
         # partition's stream, launches back to back) against the bytes a step must move
-        roofline = {"bound": "hbm", "kernel": "k_step (persistent decode step, all layers)",
+        roofline = {"bound": "hbm", "kernel": ("k_step2" if path_kind == 3 else "k_step") + " (persistent decode step, all layers)",
                     "achieved": main_run["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": main_run["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(args.workload),
                     "avg_launch_us": main_run["ms_per_step"] * 1e3, "bytes_per_launch": main_run["bytes_per_step"],
@@ -183,7 +184,7 @@ def main():
         "dtype": "bf16" if cfg["dtype"] == S.DT_BF16 else "f32", "data": "synthetic",
         "config": {"workload": wl["name"], "layers": [lo, hi], "seqs_in_flight": n_seqs, "prompt": prompt,
                    "context_during_timing": main_run["ctx"], "kv_page_tokens": 64,
-                   "decode_path": "persistent" if persistent else "per_op"},
+                   "decode_path": {3: "persistent_tiles", 2: "persistent", 1: "per_op"}[path_kind]},
         "step_bytes": main_run["bytes_per_step"], "step_GBps": main_run["gbs"],
         "step_frac_of_hbm_peak": main_run["gbs"] / HBM_PEAK_GBS,
         "roofline": roofline, "kernels": kernels,

@@ -84,9 +84,11 @@ typedef struct mdi_config {
   uint32_t has_bias;       /* linear layers carry biases (GPT-2 family)                 */
   uint32_t tie_embed;      /* vocabulary projection shares the embedding matrix          */
   uint32_t dtype;          /* MDI_F32 | MDI_BF16                                        */
-  uint32_t decode_path;    /* 0 = automatic: a decode step is one persistent kernel launch
-                              when the shape allows it, else one kernel per operation;
-                              1 = always one kernel per operation                        */
+  uint32_t decode_path;    /* how a decode step is launched.  0 = automatic: one persistent kernel launch
+                              when the shape allows it, else one kernel per operation; 1 = always one
+                              kernel per operation; 2 = same as 0; 3 = the persistent launch with
+                              streaming and exchange wavefronts on matrix-core tiles (keeps a second,
+                              tiled copy of the layer matrices in the arena; currently the slower one) */
 } mdi_config;
 
 /*

@@ -2,6 +2,7 @@
 // repacking, per-sample cache bookkeeping and the launch sequences of a first
 // visit (prefill) and a later visit (decode step) of a sample (Alg. 1, Alg. 2).
 #include <algorithm>
+#include <cstdlib>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -15,6 +16,7 @@ namespace {
 struct LayerPacked {
   const float *ln1_g = nullptr, *ln1_b = nullptr, *ln2_g = nullptr, *ln2_b = nullptr;
   const void *wqkv = nullptr, *wo = nullptr, *wup = nullptr, *wdown = nullptr;
+  const void *wqkv_t = nullptr, *wo_t = nullptr, *wup_t = nullptr, *wdown_t = nullptr;   // the same in 16-row tiles (decode)
   const float *bqkv = nullptr, *bo = nullptr, *bup = nullptr, *bdown = nullptr;
   char* kv = nullptr;  // this layer's pages: [page][K][2][pt][h]
 };
@@ -70,6 +72,13 @@ struct mdi_partition {
   int* err = nullptr;
   unsigned epoch = 0;
   unsigned long long* trace = nullptr;
+  // persistent decode step with specialised wavefronts
+  bool use_step2 = false;
+  bool tiled = false;                  // the arena holds tiled copies of the layer matrices
+  StepLayer s2_l0{};                   // first layer's pointers for step2.hip (tiled matrices)
+  int s2_S = 0, s2_E = 0;
+  size_t s2_lds = 0;
+  int s2_tab = 0, s2_own = 0, s2_part = 0, s2_xs = 0, s2_xraw = 0, s2_rec = 0, s2_gain = 0, s2_part_floats = 0;
 };
 
 namespace {
@@ -117,6 +126,12 @@ size_t carve(mdi_partition* p, void* arena) {
     if (c.has_bias && !swiglu) L.bup = (float*)cv.take(F * 4);
     L.wdown = cv.take(d * F * B);
     if (c.has_bias && !swiglu) L.bdown = (float*)cv.take(d * 4);
+    if (p->tiled) {
+      L.wqkv_t = cv.take(tiled_bytes(c.dtype, nqkv, d));
+      L.wo_t = cv.take(tiled_bytes(c.dtype, d, H * h));
+      L.wup_t = cv.take(tiled_bytes(c.dtype, nup, d));
+      L.wdown_t = cv.take(tiled_bytes(c.dtype, d, F));
+    }
   }
   const bool embed = p->flags & MDI_HAS_EMBED, head = p->flags & MDI_HAS_HEAD;
   if (embed || (head && c.tie_embed)) p->wte = cv.take(V * d * B);
@@ -169,13 +184,14 @@ void init_geometry(mdi_partition* p, const mdi_config* cfg, uint32_t lo, uint32_
   p->pages_per_seq = ((int)cfg->max_ctx + p->pt - 1) / p->pt;
   p->n_pages = cfg->kv_pages ? (int)cfg->kv_pages : (int)cfg->max_seqs * p->pages_per_seq;
   p->Tm = cfg->max_prefill ? (int)cfg->max_prefill : (int)cfg->max_ctx;
+  p->tiled = p->n_local > 0 && cfg->decode_path == 3;
 }
 
 // Decides whether a decode step runs as one persistent launch and sizes its LDS.
 void plan_step(mdi_partition* p, int n_cu) {
   const mdi_config& c = p->cfg;
   p->use_step = false;
-  if (c.decode_path != 0 || !p->n_local || n_cu <= 0) return;
+  if (c.decode_path == 1 || !p->n_local || n_cu <= 0) return;
   const int H = c.n_head, K = c.n_kv_head, h = c.head_dim, d = c.d_model, F = c.d_ff;
   const int group = H / K;
   p->G = (group == 8 || group == 4 || group == 2) ? group : 1;
@@ -194,20 +210,61 @@ void plan_step(mdi_partition* p, int n_cu) {
   p->use_step = true;
 }
 
+// Same decision for the kernel with streaming and exchange wavefronts (step2.hip); lays out its LDS.
+void plan_step2(mdi_partition* p, int n_cu) {
+  const mdi_config& c = p->cfg;
+  p->use_step2 = false;
+  if (!p->tiled || n_cu <= 0) return;
+  const int H = c.n_head, K = c.n_kv_head, h = c.head_dim, d = c.d_model, F = c.d_ff;
+  const int group = H / K;
+  p->G = group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;      // query heads that share one pass over their kv head's cache
+  step2_shape(p->G, &p->s2_S, &p->s2_E);
+  const int S = p->s2_S;
+  p->n_hg = H / p->G;
+  p->nwg = std::min(n_cu, 1024);
+  if (p->n_hg > p->nwg) return;
+  const int nup = c.mlp_kind == MDI_MLP_SWIGLU ? 2 * F : F;
+  const long rows[4] = {(long)(H + 2 * K) * h, d, nup, d};
+  const long cols[4] = {d, (long)H * h, d, F};
+  const int KT = c.dtype == MDI_BF16 ? 32 : 16;                      // columns per tile
+  long nb_max = 0, kpad_max = 0;
+  for (int j = 0; j < 4; ++j) {
+    const long nblk = (rows[j] + 15) / 16;
+    nb_max = std::max(nb_max, (nblk + p->nwg - 1) / p->nwg);
+    kpad_max = std::max(kpad_max, (cols[j] + KT - 1) / KT * KT);
+  }
+  const long nb_d = ((d + 15) / 16 + p->nwg - 1) / p->nwg;
+  auto up4 = [](long v) { return (int)((v + 3) & ~3L); };
+  p->s2_tab = kStep2HeaderWords;
+  p->s2_own = up4(p->s2_tab + p->pages_per_seq);
+  p->s2_part = up4(p->s2_own + 16 * nb_d);
+  p->s2_part_floats = up4(nb_max * S * 16);
+  p->s2_xs = p->s2_part + p->s2_part_floats;
+  const int xs_words = up4(std::max<long>(kpad_max * p->esz / 4, (long)p->G * h + 2 * h));
+  p->s2_xraw = p->s2_xs + xs_words;
+  p->s2_rec = p->s2_xraw + up4(d);
+  p->s2_gain = p->s2_rec + up4((long)(S + 1) * p->G * (h + 2));
+  p->s2_lds = (size_t)(p->s2_gain + up4(d) * (c.norm_kind == MDI_NORM_LAYERNORM ? 2 : 1)) * sizeof(float);
+  if (p->s2_lds > 160 * 1024) return;
+  if (p->s2_lds > 64 * 1024 && !step2_allow_lds(c.dtype, p->G, p->s2_lds)) return;
+  p->use_step2 = true;
+}
+
 // Persistent kernels of different partitions must not be co-scheduled (each wants every
 // compute unit for its barriers), so their launches are chained with an event per process.
 std::mutex g_step_mutex;
 hipEvent_t g_step_event = nullptr;
 hipStream_t g_step_stream = nullptr;
 
-mdi_status launch_step_serialised(mdi_partition* p, const StepArgs& a) {
+template <typename Launch>
+mdi_status launch_step_serialised(mdi_partition* p, Launch&& launch) {
   std::lock_guard<std::mutex> lock(g_step_mutex);
   if (!g_step_event) {
     if (hipEventCreateWithFlags(&g_step_event, hipEventDisableTiming) != hipSuccess) return MDI_ERR_HIP;
   } else if (g_step_stream != p->stream) {
     if (hipStreamWaitEvent(p->stream, g_step_event, 0) != hipSuccess) return MDI_ERR_HIP;
   }
-  launch_step(p->stream, p->cfg.dtype, p->G, p->nwg, p->step_lds, a);
+  launch();
   if (hipEventRecord(g_step_event, p->stream) != hipSuccess) return MDI_ERR_HIP;
   g_step_stream = p->stream;
   return MDI_OK;
@@ -286,6 +343,12 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
       put_rows(p, s.w_up, L.wup, F, d, B);
     }
     put_rows(p, s.w_down, L.wdown, d, F, B);
+    if (p->tiled) {
+      launch_pack_tiles(p->stream, c.dtype, L.wqkv, const_cast<void*>(L.wqkv_t), (int)((H + 2 * K) * h), (int)d, (int)h);
+      launch_pack_tiles(p->stream, c.dtype, L.wo, const_cast<void*>(L.wo_t), (int)d, (int)(H * h), 0);
+      launch_pack_tiles(p->stream, c.dtype, L.wup, const_cast<void*>(L.wup_t), (int)(swiglu ? 2 * F : F), (int)d, 0);
+      launch_pack_tiles(p->stream, c.dtype, L.wdown, const_cast<void*>(L.wdown_t), (int)d, (int)F, 0);
+    }
     if (c.has_bias) {
       float* bq = (float*)L.bqkv;
       launch_fill_f32(p->stream, bq, (H + 2 * K) * h, 0.f);
@@ -315,7 +378,8 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
   if (p->n_local) {
     int dev = 0, n_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n_cu = 0;
-    plan_step(p, n_cu);
+    plan_step2(p, n_cu);
+    if (!p->use_step2) plan_step(p, n_cu);
     launch_fill_u32(p->stream, p->bar_flags, 1024, 1u);     // phase counters start at 1: tag 0 marks "never written"
     p->epoch = 1;
     launch_fill_u32(p->stream, (uint32_t*)p->t_xres, 2 * d, 0u);
@@ -331,6 +395,10 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
       const LayerPacked& L = p->layers[i];
       p->h_step_layers[i] = StepLayer{L.wqkv, L.wo, L.wup, L.wdown, L.bqkv, L.bo, L.bup, L.bdown,
                                       L.ln1_g, L.ln1_b, L.ln2_g, L.ln2_b, L.kv};
+    }
+    {
+      const LayerPacked& L = p->layers[0];
+      p->s2_l0 = StepLayer{L.wqkv_t, L.wo_t, L.wup_t, L.wdown_t, L.bqkv, L.bo, L.bup, L.bdown, L.ln1_g, L.ln1_b, L.ln2_g, L.ln2_b, L.kv};
     }
     if (hipMemcpyAsync(p->d_step_layers, p->h_step_layers.data(), p->n_local * sizeof(StepLayer), hipMemcpyHostToDevice, p->stream) != hipSuccess) {
       delete p;
@@ -421,6 +489,36 @@ mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, v
   const int ak = act_kind(c);
   const bool embed = p->flags & MDI_HAS_EMBED, swiglu = c.mlp_kind == MDI_MLP_SWIGLU;
   const int ctx = len + 1;
+  if (p->use_step2) {
+    Step2Args a{};
+    a.l0 = p->s2_l0;
+    a.w_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].wqkv - (const char*)p->h_step_layers[0].wqkv : 0;
+    a.kv_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].kv - (const char*)p->h_step_layers[0].kv : 0;
+    a.n_layer = p->n_local;
+    a.d = d; a.H = H; a.K = K; a.h = h; a.F = F; a.pt = p->pt; a.pt_h = (long)p->pt * h;
+    a.norm_kind = c.norm_kind; a.mlp_kind = c.mlp_kind; a.eps = c.norm_eps;
+    a.in = act_in; a.in_kind = embed ? IN_TOKEN : ak; a.wte = p->wte; a.wpe = p->wpe;
+    a.pos = len; a.ctx = ctx;
+    a.rope = p->rope ? p->rope + (size_t)len * (h / 2) : nullptr;
+    a.table = drow; a.n_tab = (len + p->pt - 1) / p->pt; a.table_entry = new_entry; a.new_page = page;
+    a.kv_tok_off = (long)page * K * 2 * a.pt_h + (long)slot * h;
+    a.xres = p->t_xres; a.q = p->t_q; a.o = p->t_o; a.u = p->t_u; a.part = p->t_part; a.knew = p->t_knew;
+    a.tickets = p->tickets; a.flags = p->bar_flags; a.epoch0 = p->epoch; a.err = p->err; a.spin_limit = 1 << 21;
+    a.n_hg = p->n_hg;
+    const int max_splits = std::max(1, std::min(kMaxSplits, p->nwg / p->n_hg));
+    int chunk = (ctx + max_splits - 1) / max_splits;
+    chunk = (chunk + 15) / 16 * 16;
+    a.chunk = chunk; a.n_splits = (ctx + chunk - 1) / chunk;
+    a.scale = 1.f / sqrtf((float)h);
+    a.act_out = act_out; a.act_kind = ak;
+    a.lds_tab = p->s2_tab; a.lds_own = p->s2_own; a.lds_part = p->s2_part; a.lds_xs = p->s2_xs; a.lds_xraw = p->s2_xraw;
+    a.lds_rec = p->s2_rec; a.lds_gain = p->s2_gain; a.part_floats = p->s2_part_floats; a.trace = p->trace;
+    const mdi_status st = launch_step_serialised(p, [&]() { launch_step2(p->stream, p->cfg.dtype, p->G, p->nwg, p->s2_lds, a); });
+    if (st != MDI_OK) return st;
+    p->epoch += 5u * (unsigned)p->n_local;
+    p->seq_len[seq] = (uint32_t)ctx;
+    return hip_status();
+  }
   if (p->use_step) {
     StepArgs a{};
     a.l0 = p->h_step_layers[0];
@@ -443,7 +541,7 @@ mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, v
     a.chunk = chunk; a.n_splits = (ctx + chunk - 1) / chunk;
     a.scale = 1.f / sqrtf((float)h);
     a.act_out = act_out; a.act_kind = ak; a.part_floats = p->part_floats; a.trace = p->trace;
-    const mdi_status st = launch_step_serialised(p, a);
+    const mdi_status st = launch_step_serialised(p, [&]() { launch_step(p->stream, p->cfg.dtype, p->G, p->nwg, p->step_lds, a); });
     if (st != MDI_OK) return st;
     p->epoch += 5u * (unsigned)p->n_local;
     p->seq_len[seq] = (uint32_t)ctx;
@@ -602,9 +700,9 @@ mdi_status mdi_time_kernel(mdi_partition* p, int which, uint32_t reps, float* av
 mdi_status mdi_partition_info(const mdi_partition* p, uint32_t what, uint64_t* value) {
   if (!p || !value) return MDI_ERR_ARG;
   switch (what) {
-    case 0: *value = p->use_step ? 0 : 1; return MDI_OK;
-    case 1: *value = p->use_step ? (uint64_t)p->nwg : 0; return MDI_OK;
-    case 2: *value = p->use_step ? (uint64_t)p->step_lds : 0; return MDI_OK;
+    case 0: *value = p->use_step2 ? 3 : p->use_step ? 2 : 1; return MDI_OK;
+    case 1: *value = p->use_step2 || p->use_step ? (uint64_t)p->nwg : 0; return MDI_OK;
+    case 2: *value = p->use_step2 ? (uint64_t)p->s2_lds : p->use_step ? (uint64_t)p->step_lds : 0; return MDI_OK;
     case 3: *value = p->arena_bytes; return MDI_OK;
     default: return MDI_ERR_ARG;
   }

@@ -21,7 +21,7 @@ VARIANTS = {
 }
 
 
-@pytest.mark.parametrize("path", [0, 1], ids=["persistent", "per_op"])
+@pytest.mark.parametrize("path", [0, 1, 3], ids=["persistent", "per_op", "persistent_tiles"])
 @pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
 @pytest.mark.parametrize("name", list(VARIANTS))
 def test_full_model_teacher_forced(name, dtype, path):
@@ -57,7 +57,7 @@ def test_full_model_teacher_forced(name, dtype, path):
     g.sync()
 
 
-@pytest.mark.parametrize("path", [0, 1], ids=["persistent", "per_op"])
+@pytest.mark.parametrize("path", [0, 1, 3], ids=["persistent", "per_op", "persistent_tiles"])
 @pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
 def test_mid_partition_activations_in_and_out(dtype, path):
     cfg = S.tiny(n_layer=4, dtype=dtype)
@@ -115,7 +115,7 @@ def test_error_paths_and_page_pool():
     g.sync()
 
 
-@pytest.mark.parametrize("path", [0, 1], ids=["persistent", "per_op"])
+@pytest.mark.parametrize("path", [0, 1, 3], ids=["persistent", "per_op", "persistent_tiles"])
 @pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
 def test_streams_do_not_change_results(dtype, path):
     """Three chunks on three streams (the single-GPU stand-in for three nodes, Sec. III-C) give the

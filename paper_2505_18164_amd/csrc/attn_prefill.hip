@@ -1,0 +1,197 @@
+// Causal attention of a first visit (all T prompt positions of a sample at once; Alg. 1 round 0,
+// Alg. 2 "first iteration") on the matrix cores: bf16 operands, fp32 scores, softmax and output
+// accumulation.
+//
+// Everything is computed transposed, S^T = K Q^T and O^T = V^T P^T, because of where the matrix
+// core leaves its results: with v_mfma_f32_32x32x16_bf16, register r of lane l is element
+// (row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32).  In the transposed products a column is a
+// query, so each lane owns one query: its running maximum, its sum and the rescaling of its output
+// are plain per-lane scalars (lanes l and l + 32 share a query and exchange two numbers per block of
+// keys), and P^T leaves the first product in exactly the register layout the second one wants as
+// its B operand, without any data movement.  The price is that the values are needed with the key
+// index contiguous (A operand of V^T P^T), so a small kernel writes V transposed beforehand.
+#include "device_utils.h"
+
+namespace mdi {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int BQ = 128;       // queries per workgroup (32 per wavefront)
+constexpr int BK = 64;        // keys per step
+
+// values of the first visit: fp32 rows of the fused QKV product -> bf16 [kv head][h][Tp] (zero beyond T)
+__global__ __launch_bounds__(256) void k_v_transpose(const float* qkv, int T, int Tp, int n_rows, int v_off, int h, bf16_t* vt) {
+  __shared__ bf16_t tile[64][64 + 2];
+  const int t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;          // 64 positions x 64 channels of the K*h value channels
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int tt = i >> 6, c = i & 63;
+    const int t = t0 + tt;
+    tile[tt][c] = t < T ? f32_to_bf16(qkv[(long)t * n_rows + v_off + c0 + c]) : (bf16_t)0;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int c = i >> 6, tt = i & 63;
+    vt[(long)(c0 + c) * Tp + t0 + tt] = tile[tt][c];          // channel c0 + c = kv head * h + element
+  }
+}
+
+template <int HD>
+__global__ __launch_bounds__(256) void k_flash_prefill(FlashArgs a) {
+  constexpr int KS = HD + 8;            // LDS row stride of a key (elements): 16 bytes of padding spread the rows over the banks
+  constexpr int VS = BK + 4;            // LDS row stride of a value channel: an odd number of 8-byte units
+  constexpr int HT = HD / 32;           // 32-channel tiles of the output
+  constexpr int KP = BK * HD / 8 / 256; // 16-byte pieces of a key block per thread
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[BK * KS];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[HD * VS];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int qb = gridDim.x - 1 - blockIdx.x;                     // the longest rows first
+  const int head = blockIdx.y, kvh = head / (a.H / a.K);
+  const int q0 = qb * BQ, qw0 = q0 + 32 * wave;
+  const int col = lane & 31, half = lane >> 5;
+  const int query = qw0 + col;
+  const long HH = (long)a.H * HD;
+
+  // this lane's query as B operand of K Q^T: elements [16 ks + 8 half, + 8) for every step ks
+  bf16x8 qf[HD / 16];
+  {
+    const bf16_t* qp = a.q + (long)min(query, a.T - 1) * HH + (long)head * HD + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < HD / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+  }
+
+  f32x16 o[HT];
+#pragma unroll
+  for (int i = 0; i < HT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+  float m = -1e30f, l = 0.f;
+
+  const bf16_t* kbase = a.k + (long)kvh * a.Tp * HD;
+  const bf16_t* vbase = a.vt + (long)kvh * HD * a.Tp;
+  const int n_kb = min((q0 + BQ + BK - 1) / BK, a.Tp / BK);      // key blocks any query of this workgroup may see
+
+  // staging registers: the next block's keys and values travel global -> registers during the arithmetic
+  u32x4 kreg[KP], vreg[KP];
+  auto fetch = [&](int kb) {
+#pragma unroll
+    for (int i = 0; i < KP; ++i) {
+      const int p = tid + i * 256;                               // piece p: key p / (HD/8), elements 8 (p % (HD/8))
+      kreg[i] = *reinterpret_cast<const u32x4*>(kbase + ((long)kb * BK + p / (HD / 8)) * HD + 8 * (p % (HD / 8)));
+      const int c = p / (BK / 8), j = p % (BK / 8);              // channel c, keys [8 j, 8 j + 8) of the block
+      vreg[i] = *reinterpret_cast<const u32x4*>(vbase + (long)c * a.Tp + (long)kb * BK + 8 * j);
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int i = 0; i < KP; ++i) {
+      const int p = tid + i * 256;
+      *reinterpret_cast<u32x4*>(Ks + (p / (HD / 8)) * KS + 8 * (p % (HD / 8))) = kreg[i];
+      const int c = p / (BK / 8), j = p % (BK / 8);
+      u32x2* d = reinterpret_cast<u32x2*>(Vs + c * VS + 8 * j);  // 8-byte aligned: VS * 2 is a multiple of 8
+      d[0] = u32x2{vreg[i].x, vreg[i].y};
+      d[1] = u32x2{vreg[i].z, vreg[i].w};
+    }
+  };
+
+  fetch(0);
+  for (int kb = 0; kb < n_kb; ++kb) {
+    __syncthreads();                                             // everybody is done with the previous block
+    stash();
+    __syncthreads();
+    if (kb + 1 < n_kb) fetch(kb + 1);
+    const int k0 = kb * BK;
+    if (k0 > qw0 + 31) continue;                                 // this wavefront's queries see none of these keys
+
+    // ---- S^T = K Q^T: two tiles of 32 keys x 32 queries
+    f32x16 s[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
+      const bf16_t* kr = Ks + (32 * t + col) * KS + 8 * half;
+#pragma unroll
+      for (int ks = 0; ks < HD / 16; ++ks)
+        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(kr + 16 * ks), qf[ks], s[t], 0, 0, 0);
+    }
+    // ---- causal mask and the lane's share of the row statistics (row of S = column here = this lane's query)
+    float mloc = -1e30f;
+    const bool diag = k0 + BK - 1 > qw0;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = k0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (diag && key > query) s[t][r] = -1e30f;
+        mloc = fmaxf(mloc, s[t][r]);
+      }
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    const float mn = fmaxf(m, mloc);
+    const float alpha = __expf(m - mn);
+    m = mn;
+    float lsum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { const float p = __expf(s[t][r] - mn); s[t][r] = p; lsum += p; }
+    l = l * alpha + lsum;                                        // the two lanes of a query keep separate sums until the end
+#pragma unroll
+    for (int i = 0; i < HT; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+
+    // ---- O^T += V^T P^T.  Step (t, pp) contracts keys [32 t + 16 pp, + 16); inside a step this half of the
+    // wavefront supplies keys {0..3, 8..11} + 4 half, which is what registers 8 pp .. 8 pp + 7 of tile t hold
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int pp = 0; pp < 2; ++pp) {
+        bf16x8 pf;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) pf[j] = (__bf16)s[t][8 * pp + j];
+        const bf16_t* vr = Vs + col * VS + 32 * t + 16 * pp + 4 * half;
+#pragma unroll
+        for (int i = 0; i < HT; ++i) {
+          const u32x2 lo = *reinterpret_cast<const u32x2*>(vr + 32 * i * VS);
+          const u32x2 hi = *reinterpret_cast<const u32x2*>(vr + 32 * i * VS + 8);
+          const u32x4 vf = {lo.x, lo.y, hi.x, hi.y};
+          o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf), pf, o[i], 0, 0, 0);
+        }
+      }
+  }
+
+  l += __shfl_xor(l, 32, 64);
+  if (query < a.T) {
+    const float inv = 1.f / l;
+    bf16_t* op = a.out + (long)query * HH + (long)head * HD;
+#pragma unroll
+    for (int i = 0; i < HT; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {                              // four consecutive channels: 32 i + 8 g + 4 half + 0..3
+        const uint32_t w0 = (uint32_t)f32_to_bf16(o[i][4 * g] * inv) | ((uint32_t)f32_to_bf16(o[i][4 * g + 1] * inv) << 16);
+        const uint32_t w1 = (uint32_t)f32_to_bf16(o[i][4 * g + 2] * inv) | ((uint32_t)f32_to_bf16(o[i][4 * g + 3] * inv) << 16);
+        *reinterpret_cast<u32x2*>(op + 32 * i + 8 * g + 4 * half) = u32x2{w0, w1};
+      }
+  }
+}
+
+}  // namespace
+
+bool flash_supported(int dtype, int h) { return dtype == MDI_BF16 && (h == 64 || h == 128); }
+
+void launch_v_transpose(hipStream_t s, const float* qkv, int T, int Tp, int H, int K, int h, bf16_t* vt) {
+  const dim3 grid(Tp / 64, K * h / 64);
+  hipLaunchKernelGGL(k_v_transpose, grid, dim3(256), 0, s, qkv, T, Tp, (H + 2 * K) * h, (H + K) * h, h, vt);
+}
+
+void launch_flash_prefill(hipStream_t s, const FlashArgs& a) {
+  const dim3 grid(a.Tp / BQ, a.H);
+  if (a.h == 128) hipLaunchKernelGGL(k_flash_prefill<128>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(k_flash_prefill<64>, grid, dim3(256), 0, s, a);
+}
+
+}  // namespace mdi

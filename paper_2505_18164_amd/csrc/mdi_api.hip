@@ -56,6 +56,8 @@ struct mdi_partition {
   // prefill scratch
   float *p_xres = nullptr, *p_qkv = nullptr, *p_q = nullptr;
   void *p_xn = nullptr, *p_o = nullptr, *p_u = nullptr;
+  bf16_t *p_qb = nullptr, *p_kc = nullptr, *p_vt = nullptr;   // operands of the matrix-core attention of a first visit
+  int Tp = 0;                                                 // longest first visit rounded up to whole query blocks
   // host bookkeeping
   std::vector<uint32_t> seq_len;
   std::vector<int32_t> host_tables;   // mirror of `tables`, source of the async page-table copies
@@ -171,6 +173,12 @@ size_t carve(mdi_partition* p, void* arena) {
     p->p_q = (float*)cv.take(T * H * h * 4);
     p->p_o = cv.take(T * H * h * B);
     p->p_u = cv.take(T * F * B);
+    if (flash_supported(c.dtype, (int)h)) {
+      p->Tp = (int)((T + 127) / 128 * 128);
+      p->p_qb = (bf16_t*)cv.take(T * H * h * 2);
+      p->p_kc = (bf16_t*)cv.take((size_t)K * p->Tp * h * 2);
+      p->p_vt = (bf16_t*)cv.take((size_t)K * h * p->Tp * 2);
+    }
   }
   return (cv.off + 255) & ~(size_t)255;
 }
@@ -444,14 +452,24 @@ mdi_status mdi_prefill(mdi_partition* p, uint32_t seq, const void* acts_in, uint
     launch_norm_rows(s, n1);
     GemmArgs g1{p->p_xn, L.wqkv, L.bqkv, (int)T, (H + 2 * K) * h, d, p->p_qkv, nullptr};
     launch_gemm(s, c.dtype, GEPI_F32_BIAS, g1);
-    RopeScatterArgs rs{p->p_qkv, (int)T, H, K, h, p->pt, p->rope, p->p_q, L.kv, drow, (int)c.dtype};
+    const bool flash = p->p_qb != nullptr;
+    const int Tp = ((int)T + 127) / 128 * 128;
+    const float scale = 1.f / sqrtf((float)h);
+    RopeScatterArgs rs{p->p_qkv, (int)T, H, K, h, p->pt, p->rope, flash ? nullptr : p->p_q, L.kv, drow, (int)c.dtype,
+                       flash ? p->p_qb : nullptr, flash ? p->p_kc : nullptr, Tp, scale};
     launch_rope_scatter(s, rs);
-    AttnArgs at{};
-    at.q = p->p_q; at.q_stride = (long)H * h; at.pool = L.kv; at.table = drow;
-    at.ctx0 = 1; at.n_q = (int)T; at.H = H; at.K = K; at.h = h; at.pt = p->pt;
-    at.chunk = (int)c.max_ctx; at.n_splits = 1; at.scale = 1.f / sqrtf((float)h);
-    at.part = p->part; at.counters = p->counters; at.out = p->p_o; at.out_stride = (long)H * h; at.out_kind = ak;
-    launch_attn(s, c.dtype, at);
+    if (flash) {
+      launch_v_transpose(s, p->p_qkv, (int)T, Tp, H, K, h, p->p_vt);
+      FlashArgs fa{p->p_qb, p->p_kc, p->p_vt, (bf16_t*)p->p_o, (int)T, Tp, H, K, h};
+      launch_flash_prefill(s, fa);
+    } else {
+      AttnArgs at{};
+      at.q = p->p_q; at.q_stride = (long)H * h; at.pool = L.kv; at.table = drow;
+      at.ctx0 = 1; at.n_q = (int)T; at.H = H; at.K = K; at.h = h; at.pt = p->pt;
+      at.chunk = (int)c.max_ctx; at.n_splits = 1; at.scale = scale;
+      at.part = p->part; at.counters = p->counters; at.out = p->p_o; at.out_stride = (long)H * h; at.out_kind = ak;
+      launch_attn(s, c.dtype, at);
+    }
     GemmArgs g2{p->p_o, L.wo, L.bo, (int)T, d, H * h, p->p_xres, nullptr};
     launch_gemm(s, c.dtype, GEPI_RESID, g2);
     NormRowsArgs n2{p->p_xres, (int)T, d, (int)c.norm_kind, L.ln2_g, L.ln2_b, c.norm_eps, p->p_xn, ak};

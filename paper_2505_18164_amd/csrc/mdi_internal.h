@@ -108,12 +108,28 @@ struct RopeScatterArgs {
   const float* qkv;  // [T, (H+2K)h] fp32
   int T, H, K, h, pt;
   const float2* rope;     // [max_ctx][h/2] or nullptr
-  float* q_out;           // [T, H*h] fp32
+  float* q_out;           // [T, H*h] fp32, or nullptr
   void* pool;             // this layer's pages
   const int32_t* table;
   int dtype;
+  // operands of the matrix-core attention of the first visit (bf16), or nullptr
+  bf16_t* q_bf;           // [T][H*h], rotated and scaled by `scale`
+  bf16_t* k_bf;           // [K][Tp][h], rotated; rows T..Tp-1 are zero-filled
+  int Tp; float scale;
 };
 void launch_rope_scatter(hipStream_t s, const RopeScatterArgs& a);
+
+// Causal attention of a first visit on the matrix cores (bf16 operands, fp32 accumulation and softmax).
+struct FlashArgs {
+  const bf16_t* q;        // [T][H*h] rotated, scaled
+  const bf16_t* k;        // [K][Tp][h]
+  const bf16_t* vt;       // [K][h][Tp]: values transposed, so that the contraction index (position) is contiguous
+  bf16_t* out;            // [T][H*h]
+  int T, Tp, H, K, h;
+};
+bool flash_supported(int dtype, int h);
+void launch_v_transpose(hipStream_t s, const float* qkv, int T, int Tp, int H, int K, int h, bf16_t* vt);
+void launch_flash_prefill(hipStream_t s, const FlashArgs& a);
 
 // ---- whole decode step as one persistent launch ------------------------------
 constexpr int kStepThreads = 512;    // one workgroup of 8 wavefronts per compute unit

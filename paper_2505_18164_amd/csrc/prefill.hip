@@ -309,6 +309,10 @@ void launch_gemm(hipStream_t s, int dtype, int epi, const GemmArgs& a) {
 __global__ __launch_bounds__(kBlock) void k_rope_scatter(RopeScatterArgs a) {
   const int t = blockIdx.x, h = a.h, half = h >> 1;
   const int n_heads = a.H + 2 * a.K;
+  if (t >= a.T) {                                   // padding rows of the attention operand: keys nobody may see, but finite
+    for (int i = threadIdx.x; i < a.K * h; i += kBlock) a.k_bf[((long)(i / h) * a.Tp + t) * h + i % h] = 0;
+    return;
+  }
   const float* row = a.qkv + (long)t * n_heads * h;
   const int page = a.table[t / a.pt], slot = t % a.pt;
   const long pt_h = (long)a.pt * h;
@@ -322,19 +326,29 @@ __global__ __launch_bounds__(kBlock) void k_rope_scatter(RopeScatterArgs a) {
       v0 = t0; v1 = t1;
     }
     if (head < a.H) {
-      float* q = a.q_out + (long)t * a.H * h + head * h + i;
-      q[0] = v0; q[half] = v1;
+      if (a.q_out) {
+        float* q = a.q_out + (long)t * a.H * h + head * h + i;
+        q[0] = v0; q[half] = v1;
+      }
+      if (a.q_bf) {
+        bf16_t* q = a.q_bf + (long)t * a.H * h + head * h + i;
+        q[0] = f32_to_bf16(v0 * a.scale); q[half] = f32_to_bf16(v1 * a.scale);
+      }
     } else {
       const bool is_v = head >= a.H + a.K;
       const int kvh = head - a.H - (is_v ? a.K : 0);
       const long o = (((long)page * a.K + kvh) * 2 + (is_v ? 1 : 0)) * pt_h + (long)slot * h + i;
       store_kind(a.pool, kind, o, v0);
       store_kind(a.pool, kind, o + half, v1);
+      if (a.k_bf && !is_v) {
+        bf16_t* k = a.k_bf + ((long)kvh * a.Tp + t) * h + i;
+        k[0] = f32_to_bf16(v0); k[half] = f32_to_bf16(v1);
+      }
     }
   }
 }
 void launch_rope_scatter(hipStream_t s, const RopeScatterArgs& a) {
-  hipLaunchKernelGGL(k_rope_scatter, dim3(a.T), dim3(kBlock), 0, s, a);
+  hipLaunchKernelGGL(k_rope_scatter, dim3(a.k_bf ? a.Tp : a.T), dim3(kBlock), 0, s, a);
 }
 
 // ---------------------------------------------------------------------------

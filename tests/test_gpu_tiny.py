@@ -142,3 +142,24 @@ def test_streams_do_not_change_results(dtype, path):
         got = run([torch.cuda.Stream() for _ in range(3)])
         assert torch.equal(got[0], ref[0]), rep
         assert torch.equal(got[1], ref[1]), rep
+
+
+@pytest.mark.parametrize("shape", [dict(head_dim=64, n_head=4, n_kv_head=2, d_model=256, d_ff=384),
+                                   dict(head_dim=128, n_head=2, n_kv_head=2, d_model=256, d_ff=384),
+                                   dict(head_dim=64, n_head=4, n_kv_head=4, d_model=128, d_ff=256, norm_kind=S.NORM_LAYERNORM,
+                                        mlp_kind=S.MLP_GELU_TANH, pos_kind=S.POS_LEARNED, has_bias=1)],
+                         ids=["gqa_h64", "mha_h128", "gpt2_h64"])
+@pytest.mark.parametrize("T", [1, 63, 64, 129, 200, 333])
+def test_first_visit_attention_on_matrix_cores(shape, T):
+    """bf16 first visits with 64- and 128-wide heads run their causal attention on the matrix cores
+    (transposed products, one query per lane).  Prompt lengths around the 64-key and 128-query block
+    edges, then decode steps that read the cache the first visit wrote."""
+    cfg = S.tiny(n_layer=2, dtype=S.DT_BF16, max_ctx=352, vocab=97, **shape)
+    w = scale_matrices(S.make_weights(cfg, 77, exercise=True), 2.0)
+    o, g = pair(cfg, w, 0, 2, embed=True, max_seqs=1, kv_page_tokens=16)
+    ids = S.make_prompts(cfg, 77, 1, T)[0]
+    check(g.prefill(0, dev_ids(ids)), o.prefill(0, ids), cfg, ("prefill", T))
+    for step in range(3):
+        t = (7 * step + 3) % cfg["vocab"]
+        check(g.decode_step(0, dev_ids([t])), o.decode_step(0, t), cfg, ("decode", step))
+    g.sync()

@@ -290,7 +290,10 @@ static void launch_gemm_bf16(hipStream_t s, int epi, const GemmArgs& a) {
 
 void launch_gemm(hipStream_t s, int dtype, int epi, const GemmArgs& a) {
   if (dtype == MDI_BF16) {
-    launch_gemm_bf16<128, 128>(s, epi, a);
+    // a grid of 128 x 128 tiles that cannot give every compute unit two workgroups gets narrower tiles
+    const long tiles = (long)((a.N + 127) / 128) * ((a.T + 127) / 128);
+    if (tiles <= 256) launch_gemm_bf16<128, 64>(s, epi, a);
+    else launch_gemm_bf16<128, 128>(s, epi, a);
     return;
   }
   const dim3 grid((a.N + 63) / 64, (a.T + 63) / 64), block(kBlock);

@@ -95,8 +95,8 @@ __device__ __forceinline__ void gemm_store(const GemmArgs& a, int out_kind, int 
 // Both operands are K-contiguous, so a lane's MFMA fragment (8 consecutive k of
 // one row) is one 16-byte LDS read; LDS rows are padded by 16 bytes, which makes
 // the 16 lanes served together hit 16 different bank groups.  LDS is double
-// buffered: the global loads of step k+1 are issued before the MFMAs of step k and
-// land in the other buffer after them, so a K step costs one workgroup barrier.
+// buffered and fed from two register stages, so a K step costs one workgroup barrier and a
+// global load has two K steps to arrive.
 constexpr int BK = 64, LDS_STRIDE = BK + 8;
 
 template <int EPI, int BM, int BN>
@@ -131,30 +131,36 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) 
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const u32x4 z4 = {0u, 0u, 0u, 0u};
-  u32x4 ra[PA], rb[PB];
-  const bool k_ok0 = pk < Kd;
+  // Two register stages: while step k is multiplied out of LDS, the operands of step k + 1 wait in one stage to be
+  // written to the other LDS buffer and those of step k + 2 are still on their way into the second stage, so a
+  // global load has two K steps of arithmetic to arrive (one is not enough, a third stage costs more registers
+  // than it gains).
+  u32x4 ra0[PA], rb0[PB], ra1[PA], rb1[PB];
+  const int nk = (Kd + BK - 1) / BK;
+  auto fetch_full = [&](u32x4 (&ra)[PA], u32x4 (&rb)[PB], int step) __attribute__((always_inline)) {
 #pragma unroll
-  for (int i = 0; i < PA; ++i) ra[i] = k_ok0 ? *reinterpret_cast<const u32x4*>(ga[i]) : z4;
+    for (int i = 0; i < PA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(ga[i] + step * BK);
 #pragma unroll
-  for (int i = 0; i < PB; ++i) rb[i] = k_ok0 ? *reinterpret_cast<const u32x4*>(gb[i]) : z4;
+    for (int i = 0; i < PB; ++i) rb[i] = *reinterpret_cast<const u32x4*>(gb[i] + step * BK);
+  };
+  auto fetch_guarded = [&](u32x4 (&ra)[PA], u32x4 (&rb)[PB], int step) __attribute__((always_inline)) {
+    const bool ok = step * BK + pk < Kd;              // steps past the matrix, and its last columns when Kd % 64 != 0, are zero
 #pragma unroll
-  for (int i = 0; i < PA; ++i) *reinterpret_cast<u32x4*>(As + (prow + i * 32) * LDS_STRIDE + pk) = ra[i];
+    for (int i = 0; i < PA; ++i) ra[i] = ok ? *reinterpret_cast<const u32x4*>(ga[i] + step * BK) : z4;
 #pragma unroll
-  for (int i = 0; i < PB; ++i) *reinterpret_cast<u32x4*>(Bs + (prow + i * 32) * LDS_STRIDE + pk) = rb[i];
-  __syncthreads();
-
-  int cur = 0;
-  for (int k0 = 0; k0 < Kd; k0 += BK) {
-    const bool more = k0 + BK < Kd;
-    const bool k_ok = k0 + BK + pk < Kd;
-    if (more) {
+    for (int i = 0; i < PB; ++i) rb[i] = ok ? *reinterpret_cast<const u32x4*>(gb[i] + step * BK) : z4;
+  };
+  auto stash = [&](const u32x4 (&ra)[PA], const u32x4 (&rb)[PB], int buf) __attribute__((always_inline)) {
+    bf16_t* An = As + buf * BM * LDS_STRIDE;
+    bf16_t* Bn = Bs + buf * BN * LDS_STRIDE;
 #pragma unroll
-      for (int i = 0; i < PA; ++i) ra[i] = k_ok ? *reinterpret_cast<const u32x4*>(ga[i] + k0 + BK) : z4;
+    for (int i = 0; i < PA; ++i) *reinterpret_cast<u32x4*>(An + (prow + i * 32) * LDS_STRIDE + pk) = ra[i];
 #pragma unroll
-      for (int i = 0; i < PB; ++i) rb[i] = k_ok ? *reinterpret_cast<const u32x4*>(gb[i] + k0 + BK) : z4;
-    }
-    const bf16_t* Ac = As + cur * BM * LDS_STRIDE;
-    const bf16_t* Bc = Bs + cur * BN * LDS_STRIDE;
+    for (int i = 0; i < PB; ++i) *reinterpret_cast<u32x4*>(Bn + (prow + i * 32) * LDS_STRIDE + pk) = rb[i];
+  };
+  auto multiply = [&](int buf) __attribute__((always_inline)) {
+    const bf16_t* Ac = As + buf * BM * LDS_STRIDE;
+    const bf16_t* Bc = Bs + buf * BN * LDS_STRIDE;
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
       const int kk = ks + (lane >> 5) * 8;
@@ -169,16 +175,41 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) 
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (more) {
-      bf16_t* An = As + (cur ^ 1) * BM * LDS_STRIDE;
-      bf16_t* Bn = Bs + (cur ^ 1) * BN * LDS_STRIDE;
-#pragma unroll
-      for (int i = 0; i < PA; ++i) *reinterpret_cast<u32x4*>(An + (prow + i * 32) * LDS_STRIDE + pk) = ra[i];
-#pragma unroll
-      for (int i = 0; i < PB; ++i) *reinterpret_cast<u32x4*>(Bn + (prow + i * 32) * LDS_STRIDE + pk) = rb[i];
+  };
+
+  fetch_guarded(ra0, rb0, 0);
+  stash(ra0, rb0, 0);
+  fetch_guarded(ra0, rb0, 1);
+  fetch_guarded(ra1, rb1, 2);
+  __syncthreads();
+
+  // invariant at an even step k: LDS buffer 0 holds step k, stage 0 step k + 1, stage 1 step k + 2
+  int k = 0;
+  for (; (k + 5) * BK <= Kd; k += 2) {              // every fetch below is of a whole step inside the matrix
+    multiply(0);
+    stash(ra0, rb0, 1);
+    fetch_full(ra0, rb0, k + 3);
+    __syncthreads();
+    multiply(1);
+    stash(ra1, rb1, 0);
+    fetch_full(ra1, rb1, k + 4);
+    __syncthreads();
+  }
+  for (; k < nk; k += 2) {
+    multiply(0);
+    if (k + 1 < nk) {
+      stash(ra0, rb0, 1);
+      fetch_guarded(ra0, rb0, k + 3);
     }
     __syncthreads();
-    cur ^= 1;
+    if (k + 1 < nk) {
+      multiply(1);
+      if (k + 2 < nk) {
+        stash(ra1, rb1, 0);
+        fetch_guarded(ra1, rb1, k + 4);
+      }
+      __syncthreads();
+    }
   }
 
   // accumulator layout of the 32x32 MFMA: register r of lane l holds

@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--decode-path", type=int, default=0, help="0 = automatic (persistent single-launch step), 1 = one kernel per operation, 3 = persistent launch with streaming/exchange wavefronts on tiled matrices")
+    ap.add_argument("--queue", type=int, default=1,
+                    help="messages of different samples handed to the partition per call (1 = mdi_decode_step, "
+                         "more = mdi_decode_steps); must divide the number of samples in flight")
     return ap.parse_args()
 
 
@@ -119,14 +122,23 @@ def main():
         torch.cuda.synchronize()
         prefill_ms = e0.elapsed_time(e1) / n_seqs
         xs = step_inputs()
-        out = torch.empty((d,), dtype=tdt, device=dev)
-        for k in range(warmup):
-            part.decode_step(k % n_seqs, xs[k % n_seqs], out)
+        q = args.queue
+        douts = [torch.empty((d,), dtype=tdt, device=dev) for _ in range(q)]
+
+        def visit(k):                      # messages k .. k + q - 1 of the round-robin order
+            if q == 1:
+                part.decode_step(k % n_seqs, xs[k % n_seqs], douts[0])
+            else:
+                ids = [(k + i) % n_seqs for i in range(q)]
+                part.decode_steps(ids, [xs[i] for i in ids], douts)
+
+        for k in range(0, warmup, q):
+            visit(k)
         torch.cuda.synchronize()
         ctx_first = part.seq_len(0) + 1
         e0.record()
-        for k in range(steps):
-            part.decode_step((warmup + k) % n_seqs, xs[k % n_seqs], out)
+        for k in range(0, steps, q):
+            visit(warmup + k)
         e1.record()
         part.sync()
         ms = e0.elapsed_time(e1) / steps
@@ -143,6 +155,9 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.queue < 1 or n_seqs % args.queue or args.steps % args.queue or args.warmup % args.queue:
+        print("bench.py: --queue must divide the samples in flight, --steps and --warmup", file=sys.stderr)
+        sys.exit(2)
     main_run = run(prompt, args.steps, args.warmup)
     n_local = hi - lo
     params = sum(a * b for a, b in S.layer_tensor_shapes(cfg).values())

@@ -167,6 +167,24 @@ MDI_API mdi_status mdi_decode_step(mdi_partition *part, uint32_t seq_id, const v
                            void *act_out);
 
 /*
+ * Later visits of n different samples whose messages wait in the node's input
+ * queue (Sec. III-A: arriving messages are queued and taken out in order;
+ * Sec. III-C: several samples are in flight at once).  The result is exactly that of
+ * n mdi_decode_step calls in the order given - every message is still forwarded
+ * on its own, reading the layer weights itself - but on the persistent decode
+ * path messages are taken two per launch with their phases alternating, so
+ * that the exchange between workgroups that ends one message's phase is
+ * covered by the other message's weight streaming.
+ * seq_ids: host uint32[n], pairwise different.  acts_in / acts_out: host arrays
+ * of n device pointers, each as act_in / act_out of mdi_decode_step.
+ * Errors: as mdi_decode_step, checked for all n messages before the first is
+ * taken (on an error no sequence has advanced); MDI_ERR_ARG also when n == 0 or
+ * a sample id occurs twice.
+ */
+MDI_API mdi_status mdi_decode_steps(mdi_partition *part, uint32_t n, const uint32_t *seq_ids,
+                            const void *const *acts_in, void *const *acts_out);
+
+/*
  * Output layers (Alg. 1 "process output layers ... get token", with greedy
  * argmax in place of sampling): final norm, vocabulary projection, argmax
  * (lowest index on exact ties).  Needs MDI_HAS_HEAD; touches no KV state.
@@ -226,8 +244,9 @@ MDI_API mdi_status mdi_partition_info(const mdi_partition *part, uint32_t what, 
  * entered (first tiles issued), 1 barrier passed, 2 input vector staged, 3 first
  * wavefront done streaming, 4 all wavefronts done (GEMV phases), 5 results
  * stored, 6 stores acknowledged; slot 7 is unused.  trace: device buffer of
- * uint64 [workgroups][local layers][5][8] (mdi_partition_info gives the workgroup
- * count), owned by the caller; NULL switches tracing off.
+ * uint64 [2][workgroups][local layers][5][8] (mdi_partition_info gives the workgroup
+ * count; the second half is written for the second message of a launch that
+ * carries two, see mdi_decode_steps), owned by the caller; NULL switches tracing off.
  */
 MDI_API mdi_status mdi_partition_trace(mdi_partition *part, void *trace);
 

@@ -13,7 +13,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmdi.so")
-SOURCES = ["mdi_api.hip", "decode.hip", "prefill.hip", "step.hip", "step2.hip", "attn_prefill.hip"]
+SOURCES = ["mdi_api.hip", "decode.hip", "prefill.hip", "step_w4.hip", "step_w8.hip", "step2.hip", "attn_prefill.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]

@@ -74,6 +74,13 @@ struct mdi_partition {
   int* err = nullptr;
   unsigned epoch = 0;
   unsigned long long* trace = nullptr;
+  // exchange buffers, flags and phase counter of each message a launch can carry (set 0 aliases the members above)
+  struct StepScratch {
+    tagged_t *xres = nullptr, *q = nullptr, *o = nullptr, *u = nullptr, *part = nullptr, *knew = nullptr;
+    unsigned *flags = nullptr, *tickets = nullptr;
+    unsigned epoch = 0;
+  } sc[kMaxSlots];
+  int n_cu = 0;
   // persistent decode step with specialised wavefronts
   bool use_step2 = false;
   bool tiled = false;                  // the arena holds tiled copies of the layer matrices
@@ -166,6 +173,19 @@ size_t carve(mdi_partition* p, void* arena) {
     p->t_u = (tagged_t*)cv.take(F * 8);
     p->t_part = (tagged_t*)cv.take(H * kMaxSplits * (h + 2) * 8);
     p->t_knew = (tagged_t*)cv.take(2 * K * h * 8);
+    p->sc[0].xres = p->t_xres; p->sc[0].q = p->t_q; p->sc[0].o = p->t_o; p->sc[0].u = p->t_u;
+    p->sc[0].part = p->t_part; p->sc[0].knew = p->t_knew; p->sc[0].flags = p->bar_flags; p->sc[0].tickets = p->tickets;
+    for (int m = 1; m < kMaxSlots; ++m) {
+      auto& sc = p->sc[m];
+      sc.flags = (unsigned*)cv.take(1024 * 4);
+      sc.tickets = (unsigned*)cv.take(H * 4);
+      sc.xres = (tagged_t*)cv.take(d * 8);
+      sc.q = (tagged_t*)cv.take(H * h * 8);
+      sc.o = (tagged_t*)cv.take(H * h * 8);
+      sc.u = (tagged_t*)cv.take(F * 8);
+      sc.part = (tagged_t*)cv.take(H * kMaxSplits * (h + 2) * 8);
+      sc.knew = (tagged_t*)cv.take(2 * K * h * 8);
+    }
     const size_t T = p->Tm;
     p->p_xres = (float*)cv.take(T * d * 4);
     p->p_xn = cv.take(T * d * B);
@@ -209,9 +229,9 @@ void plan_step(mdi_partition* p, int n_cu) {
   const int nup = c.mlp_kind == MDI_MLP_SWIGLU ? 2 * F : F;
   const int max_rows = std::max(std::max((H + 2 * K) * h, nup), d);
   const int max_pairs = ((max_rows + 1) / 2 + p->nwg - 1) / p->nwg + 1;
-  p->part_floats = (max_pairs * 2 * kStepWaves + 3) & ~3;
+  p->part_floats = (max_pairs * 2 * kStepWavesMax + 3) & ~3;
   int xs = std::max(std::max(d, H * h), F);
-  xs = std::max(xs, kStepWaves * p->G * (h + 2));
+  xs = std::max(xs, kStepWavesMax * p->G * (h + 2));
   xs = (xs + 3) & ~3;
   p->step_lds = (size_t)(128 + p->part_floats + xs) * sizeof(float);
   if (p->step_lds > 64 * 1024) return;
@@ -386,6 +406,7 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
   if (p->n_local) {
     int dev = 0, n_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n_cu = 0;
+    p->n_cu = n_cu;
     plan_step2(p, n_cu);
     if (!p->use_step2) plan_step(p, n_cu);
     launch_fill_u32(p->stream, p->bar_flags, 1024, 1u);     // phase counters start at 1: tag 0 marks "never written"
@@ -397,6 +418,18 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
     launch_fill_u32(p->stream, (uint32_t*)p->t_part, 2 * H * kMaxSplits * (h + 2), 0u);
     launch_fill_u32(p->stream, (uint32_t*)p->t_knew, 4 * K * h, 0u);
     launch_fill_u32(p->stream, p->tickets, H, 0u);
+    for (int m = 1; m < kMaxSlots; ++m) {
+      auto& sc = p->sc[m];
+      launch_fill_u32(p->stream, sc.flags, 1024, 1u);
+      sc.epoch = 1;
+      launch_fill_u32(p->stream, (uint32_t*)sc.xres, 2 * d, 0u);
+      launch_fill_u32(p->stream, (uint32_t*)sc.q, 2 * H * h, 0u);
+      launch_fill_u32(p->stream, (uint32_t*)sc.o, 2 * H * h, 0u);
+      launch_fill_u32(p->stream, (uint32_t*)sc.u, 2 * F, 0u);
+      launch_fill_u32(p->stream, (uint32_t*)sc.part, 2 * H * kMaxSplits * (h + 2), 0u);
+      launch_fill_u32(p->stream, (uint32_t*)sc.knew, 4 * K * h, 0u);
+      launch_fill_u32(p->stream, sc.tickets, H, 0u);
+    }
     launch_fill_u32(p->stream, (uint32_t*)p->err, 64, 0u);
     p->h_step_layers.resize(p->n_local);
     for (int i = 0; i < p->n_local; ++i) {
@@ -483,30 +516,122 @@ mdi_status mdi_prefill(mdi_partition* p, uint32_t seq, const void* acts_in, uint
   return hip_status();
 }
 
-mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, void* act_out) {
-  if (!p || !act_in || !act_out || !p->n_local) return MDI_ERR_ARG;
+namespace {
+
+// Host bookkeeping of one decode message: the page and slot of the new position.
+struct MessagePlan {
+  int len, ctx, page, slot;
+  int32_t* drow;        // the sequence's page table on the device
+  int32_t* new_entry;   // table entry the launch has to fill (a page starts), or nullptr
+};
+
+mdi_status check_message(const mdi_partition* p, uint32_t seq) {
   const mdi_config& c = p->cfg;
   if (seq >= c.max_seqs) return MDI_ERR_ARG;
-  const int len = (int)p->seq_len[seq];
+  const uint32_t len = p->seq_len[seq];
   if (!len) return MDI_ERR_STATE;
-  if ((uint32_t)len + 1 > c.max_ctx) return MDI_ERR_CTX;
+  if (len + 1 > c.max_ctx) return MDI_ERR_CTX;
+  return MDI_OK;
+}
+
+mdi_status plan_message(mdi_partition* p, uint32_t seq, MessagePlan* m) {
+  const mdi_status st = check_message(p, seq);
+  if (st != MDI_OK) return st;
+  m->len = (int)p->seq_len[seq];
+  m->ctx = m->len + 1;
   int32_t* row = p->host_tables.data() + (size_t)seq * p->pages_per_seq;
-  int32_t* drow = p->tables + (size_t)seq * p->pages_per_seq;
-  const int pidx = len / p->pt, slot = len % p->pt;
-  int32_t* new_entry = nullptr;
-  if (slot == 0) {
+  m->drow = p->tables + (size_t)seq * p->pages_per_seq;
+  const int pidx = m->len / p->pt;
+  m->slot = m->len % p->pt;
+  m->new_entry = nullptr;
+  if (m->slot == 0) {
     if (p->free_pages.empty()) return MDI_ERR_NOMEM;
     row[pidx] = p->free_pages.back();
     p->free_pages.pop_back();
-    new_entry = drow + pidx;
+    m->new_entry = m->drow + pidx;
   }
-  const int page = row[pidx];
+  m->page = row[pidx];
+  return MDI_OK;
+}
+
+// Arguments of the persistent step kernel that do not depend on the message.
+void fill_step_shared(const mdi_partition* p, StepArgs* a) {
+  const mdi_config& c = p->cfg;
+  a->l0 = p->h_step_layers[0];
+  a->w_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].wqkv - (const char*)p->h_step_layers[0].wqkv : 0;
+  a->kv_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].kv - (const char*)p->h_step_layers[0].kv : 0;
+  a->n_layer = p->n_local;
+  a->d = c.d_model; a->H = c.n_head; a->K = c.n_kv_head; a->h = c.head_dim; a->F = c.d_ff; a->pt = p->pt;
+  a->pt_h = (long)p->pt * c.head_dim;
+  a->norm_kind = c.norm_kind; a->mlp_kind = c.mlp_kind; a->eps = c.norm_eps;
+  a->wte = p->wte; a->wpe = p->wpe;
+  a->err = p->err; a->spin_limit = 1 << 21;
+  a->n_hg = p->n_hg;
+  a->scale = 1.f / sqrtf((float)c.head_dim);
+  a->act_kind = act_kind(c);
+  a->part_floats = p->part_floats;
+}
+
+// One message's part of the arguments: message m of a launch whose sets have nwg workgroups each.
+void fill_step_slot(const mdi_partition* p, int m, int nwg, const MessagePlan& mp, const void* act_in, void* act_out, StepSlot* s) {
+  const mdi_config& c = p->cfg;
+  const int h = c.head_dim, K = c.n_kv_head;
+  const long pt_h = (long)p->pt * h;
+  s->in = act_in; s->in_kind = (p->flags & MDI_HAS_EMBED) ? IN_TOKEN : act_kind(c);
+  s->pos = mp.len; s->ctx = mp.ctx;
+  s->rope = p->rope ? p->rope + (size_t)mp.len * (h / 2) : nullptr;
+  s->table = mp.drow; s->table_entry = mp.new_entry; s->new_page = mp.page;
+  s->kv_tok_off = (long)mp.page * K * 2 * pt_h + (long)mp.slot * h;
+  const auto& sc = p->sc[m];
+  s->xres = sc.xres; s->q = sc.q; s->o = sc.o; s->u = sc.u; s->part = sc.part; s->knew = sc.knew;
+  s->tickets = sc.tickets; s->flags = sc.flags; s->epoch0 = m == 0 ? p->epoch : sc.epoch;
+  const int max_splits = std::max(1, std::min(kMaxSplits, nwg / p->n_hg));
+  int chunk = (mp.ctx + max_splits - 1) / max_splits;
+  chunk = (chunk + 15) / 16 * 16;
+  s->chunk = chunk; s->n_splits = (mp.ctx + chunk - 1) / chunk;
+  s->act_out = act_out;
+  s->trace = (p->trace && m < 2) ? p->trace + (size_t)m * nwg * p->n_local * 40 : nullptr;
+}
+
+// Launches the persistent kernel for n <= kMaxSlots planned messages.
+mdi_status launch_messages(mdi_partition* p, int n, const uint32_t* seqs, const MessagePlan* mp, const void* const* ins, void* const* outs) {
+  static const int env_sets = getenv("MDI_SETS") ? atoi(getenv("MDI_SETS")) : 2;
+  static const int env_one = getenv("MDI_ONE") ? atoi(getenv("MDI_ONE")) : 1;
+  StepArgs a{};
+  fill_step_shared(p, &a);
+  a.n_slots = n;
+  a.n_sets = n >= 2 ? std::max(1, std::min(env_sets, 2)) : 1;
+  a.nwg = p->nwg;
+  if (n == 1 && env_one == 2 && 2 * p->nwg <= 1024) a.nwg = 2 * p->nwg;   // one message: both workgroups of a compute unit on it
+  a.set_lo[0] = 0; a.set_lo[1] = a.n_sets == 2 ? (n + 1) / 2 : n; a.set_lo[2] = n;
+  for (int m = 0; m < n; ++m) fill_step_slot(p, m, a.nwg, mp[m], ins[m], outs[m], &a.s[m]);
+  const mdi_status st = launch_step_serialised(p, [&]() {
+    if (n == 1 && env_one == 1) launch_step_w8(p->stream, p->cfg.dtype, p->G, a.nwg, p->step_lds, a);
+    else launch_step_w4(p->stream, p->cfg.dtype, p->G, a.nwg, p->step_lds, a);
+  });
+  if (st != MDI_OK) return st;
+  p->epoch += 5u * (unsigned)p->n_local;
+  for (int m = 1; m < n; ++m) p->sc[m].epoch += 5u * (unsigned)p->n_local;
+  for (int m = 0; m < n; ++m) p->seq_len[seqs[m]] = (uint32_t)mp[m].ctx;
+  return MDI_OK;
+}
+
+}  // namespace
+
+mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, void* act_out) {
+  if (!p || !act_in || !act_out || !p->n_local) return MDI_ERR_ARG;
+  const mdi_config& c = p->cfg;
+  MessagePlan mp;
+  const mdi_status pst = plan_message(p, seq, &mp);
+  if (pst != MDI_OK) return pst;
+  const int len = mp.len, ctx = mp.ctx, page = mp.page, slot = mp.slot;
+  int32_t* drow = mp.drow;
+  int32_t* new_entry = mp.new_entry;
 
   hipStream_t s = p->stream;
   const int d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff;
   const int ak = act_kind(c);
   const bool embed = p->flags & MDI_HAS_EMBED, swiglu = c.mlp_kind == MDI_MLP_SWIGLU;
-  const int ctx = len + 1;
   if (p->use_step2) {
     Step2Args a{};
     a.l0 = p->s2_l0;
@@ -538,32 +663,8 @@ mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, v
     return hip_status();
   }
   if (p->use_step) {
-    StepArgs a{};
-    a.l0 = p->h_step_layers[0];
-    a.w_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].wqkv - (const char*)p->h_step_layers[0].wqkv : 0;
-    a.kv_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].kv - (const char*)p->h_step_layers[0].kv : 0;
-    a.n_layer = p->n_local;
-    a.d = d; a.H = H; a.K = K; a.h = h; a.F = F; a.pt = p->pt; a.pt_h = (long)p->pt * h;
-    a.norm_kind = c.norm_kind; a.mlp_kind = c.mlp_kind; a.eps = c.norm_eps;
-    a.in = act_in; a.in_kind = embed ? IN_TOKEN : ak; a.wte = p->wte; a.wpe = p->wpe;
-    a.pos = len; a.ctx = ctx;
-    a.rope = p->rope ? p->rope + (size_t)len * (h / 2) : nullptr;
-    a.table = drow; a.table_entry = new_entry; a.new_page = page;
-    a.kv_tok_off = (long)page * K * 2 * a.pt_h + (long)slot * h;
-    a.xres = p->t_xres; a.q = p->t_q; a.o = p->t_o; a.u = p->t_u; a.part = p->t_part; a.knew = p->t_knew;
-    a.tickets = p->tickets; a.flags = p->bar_flags; a.epoch0 = p->epoch; a.err = p->err; a.spin_limit = 1 << 21;
-    a.n_hg = p->n_hg;
-    const int max_splits = std::max(1, std::min(kMaxSplits, p->nwg / p->n_hg));
-    int chunk = (ctx + max_splits - 1) / max_splits;
-    chunk = (chunk + 15) / 16 * 16;
-    a.chunk = chunk; a.n_splits = (ctx + chunk - 1) / chunk;
-    a.scale = 1.f / sqrtf((float)h);
-    a.act_out = act_out; a.act_kind = ak; a.part_floats = p->part_floats; a.trace = p->trace;
-    const mdi_status st = launch_step_serialised(p, [&]() { launch_step(p->stream, p->cfg.dtype, p->G, p->nwg, p->step_lds, a); });
-    if (st != MDI_OK) return st;
-    p->epoch += 5u * (unsigned)p->n_local;
-    p->seq_len[seq] = (uint32_t)ctx;
-    return hip_status();
+    const mdi_status st = launch_messages(p, 1, &seq, &mp, &act_in, &act_out);
+    return st != MDI_OK ? st : hip_status();
   }
   InputArgs ia{act_in, embed ? IN_TOKEN : ak, p->wte, p->wpe, (int)c.dtype, len, d, p->xres, new_entry, page};
   launch_input(s, ia);
@@ -614,6 +715,43 @@ mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, v
     launch_gemv(s, c.dtype, PRO_COPY, EPI_RESID, da);
   }
   p->seq_len[seq] = (uint32_t)ctx;
+  return hip_status();
+}
+
+mdi_status mdi_decode_steps(mdi_partition* p, uint32_t n, const uint32_t* seqs, const void* const* acts_in, void* const* acts_out) {
+  if (!p || !n || !seqs || !acts_in || !acts_out || !p->n_local) return MDI_ERR_ARG;
+  // everything that can be refused is checked before the first message is taken, so a refusal leaves no message half done
+  size_t new_pages = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (!acts_in[i] || !acts_out[i]) return MDI_ERR_ARG;
+    const mdi_status st = check_message(p, seqs[i]);
+    if (st != MDI_OK) return st;
+    for (uint32_t k = 0; k < i; ++k)
+      if (seqs[k] == seqs[i]) return MDI_ERR_ARG;            // a sequence has one message in flight
+    if (p->seq_len[seqs[i]] % (uint32_t)p->pt == 0) ++new_pages;
+  }
+  if (new_pages > p->free_pages.size()) return MDI_ERR_NOMEM;
+  uint32_t i = 0;
+  if (p->use_step) {
+    static const int env_launch = getenv("MDI_LAUNCH") ? atoi(getenv("MDI_LAUNCH")) : kMaxSlots;
+    const uint32_t per_launch = (uint32_t)std::max(1, std::min(env_launch, kMaxSlots));
+    while (n - i >= 2) {
+      const uint32_t m = std::min(per_launch, n - i);
+      if (m < 2) break;
+      MessagePlan mp[kMaxSlots];
+      for (uint32_t k = 0; k < m; ++k) {
+        const mdi_status st = plan_message(p, seqs[i + k], &mp[k]);
+        if (st != MDI_OK) return st;
+      }
+      const mdi_status st = launch_messages(p, (int)m, seqs + i, mp, acts_in + i, acts_out + i);
+      if (st != MDI_OK) return st;
+      i += m;
+    }
+  }
+  for (; i < n; ++i) {
+    const mdi_status st = mdi_decode_step(p, seqs[i], acts_in[i], acts_out[i]);
+    if (st != MDI_OK) return st;
+  }
   return hip_status();
 }
 

@@ -132,8 +132,8 @@ void launch_v_transpose(hipStream_t s, const float* qkv, int T, int Tp, int H, i
 void launch_flash_prefill(hipStream_t s, const FlashArgs& a);
 
 // ---- whole decode step as one persistent launch ------------------------------
-constexpr int kStepThreads = 512;    // one workgroup of 8 wavefronts per compute unit
-constexpr int kStepWaves = 8;
+constexpr int kStepWavesMax = 8;     // wavefronts per workgroup: 8 (one workgroup per compute unit) or 4 (two)
+constexpr int kMaxSlots = 8;         // messages one launch can carry
 
 typedef unsigned long long tagged_t;  // low half: the value's bits, high half: the phase counter it was written in
 
@@ -143,26 +143,43 @@ struct StepLayer {                   // device-resident, one per local layer
   void* kv;                          // this layer's pages
 };
 
-struct StepArgs {
-  StepLayer l0;                      // first local layer; layer i's pointers are these advanced by i strides
-  long w_stride, kv_stride;          // bytes between consecutive layers' packed weights / page pools
-  int n_layer;
-  int d, H, K, h, F, pt; long pt_h;
-  int norm_kind, mlp_kind; float eps;
-  const void* in; int in_kind; const void* wte; const void* wpe;
+// What belongs to one message (one sequence's new token) inside a launch.  A launch carries one or two messages:
+// with two, every phase runs for message 0 and then for message 1, so that the exchange between workgroups that
+// ends one message's phase is covered by the other message's weight streaming.  Each message has its own exchange
+// buffers, flags and counters.
+struct StepSlot {
+  const void* in; int in_kind;
   int pos, ctx;                      // position of the new token, context length including it
   const float2* rope;                // (cos, sin)[h/2] of `pos`, or nullptr
   const int32_t* table; int32_t* table_entry; int new_page;
   long kv_tok_off;                   // element offset of K[kv head 0][slot] of the new token inside a layer's pool
   // vectors exchanged between workgroups inside the launch: every element is (float bits, tag) in 8 bytes
   tagged_t *xres, *q, *o, *u, *part, *knew;   // [d], [H*h], [H*h], [F], [H][kMaxSplits][h+2], [2][K*h]
-  unsigned *tickets, *flags; unsigned epoch0; int* err; int spin_limit;
-  int n_hg, n_splits, chunk; float scale;
-  void* act_out; int act_kind;
-  int part_floats;                   // LDS floats reserved for GEMV pair partials (multiple of 4)
+  unsigned *tickets, *flags; unsigned epoch0;
+  int n_splits, chunk;
+  void* act_out;
   unsigned long long* trace;         // optional [workgroup][n_layer * 5 phases][4] timestamps (100 MHz ticks), or nullptr
 };
-void launch_step(hipStream_t s, int dtype, int G, int nwg, size_t lds_bytes, const StepArgs& a);
+struct StepArgs {
+  StepLayer l0;                      // first local layer; layer i's pointers are these advanced by i strides
+  long w_stride, kv_stride;          // bytes between consecutive layers' packed weights / page pools
+  int n_layer;
+  int d, H, K, h, F, pt; long pt_h;
+  int norm_kind, mlp_kind; float eps;
+  const void* wte; const void* wpe;
+  int* err; int spin_limit;
+  int n_hg; float scale;
+  int act_kind;
+  int part_floats;                   // LDS floats reserved for GEMV pair partials (multiple of 4)
+  int nwg;                           // workgroups in a set
+  int n_slots;                       // messages in this launch, 1 .. kMaxSlots
+  int n_sets;                        // sets of workgroups, 1 or 2 (grid = n_sets * nwg): set i takes messages
+  int set_lo[3];                     // [set_lo[i], set_lo[i + 1]), alternating between them inside every phase
+  StepSlot s[kMaxSlots];
+};
+// workgroups of 8 wavefronts (n_sets must be 1) / of 4 wavefronts
+void launch_step_w8(hipStream_t s, int dtype, int G, int nwg, size_t lds_bytes, const StepArgs& a);
+void launch_step_w4(hipStream_t s, int dtype, int G, int nwg, size_t lds_bytes, const StepArgs& a);
 
 
 // ---- whole decode step as one persistent launch, specialised wavefronts (step2.hip) ----------

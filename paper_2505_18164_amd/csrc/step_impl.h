@@ -29,9 +29,22 @@
 //
 // Every spin is bounded: a workgroup that waits longer than `spin_limit` polls
 // raises the partition's error flag and leaves, and so does every other one.
+//
+// This file is the kernel's body; step_w4.hip and step_w8.hip compile it for workgroups of four and of
+// eight wavefronts (MDI_STEP_WAVES), each in a namespace of its own with a launcher of its own.
 #include "device_utils.h"
 
+#ifndef MDI_STEP_WAVES
+#error "include from step_w4.hip / step_w8.hip, which define MDI_STEP_WAVES"
+#endif
+#define MDI_STEP_CAT2(a, b) a##b
+#define MDI_STEP_CAT(a, b) MDI_STEP_CAT2(a, b)
+
 namespace mdi {
+namespace MDI_STEP_CAT(step_w, MDI_STEP_WAVES) {
+
+constexpr int kStepWaves = MDI_STEP_WAVES;       // wavefronts per workgroup
+constexpr int kStepThreads = 64 * kStepWaves;
 
 #define MDI_GLOBAL __attribute__((address_space(1)))
 
@@ -81,9 +94,9 @@ template <> struct Unpack<bf16_t> {
 enum StepPhase { PH_QKV = 0, PH_ATTN = 1, PH_OPROJ = 2, PH_UP = 3, PH_DOWN = 4 };
 
 // optional timeline for profiling: thread 0 of every workgroup records a 100 MHz timestamp
-__device__ __forceinline__ void stamp(const StepArgs& a, int layer, int ph, int k) {
-  if (a.trace && threadIdx.x == 0)
-    a.trace[(((long)blockIdx.x * a.n_layer + layer) * 5 + ph) * 8 + k] = wall_clock64();
+__device__ __forceinline__ void stamp(const StepArgs& a, const StepSlot& S, int layer, int ph, int k) {
+  if (S.trace && threadIdx.x == 0)
+    S.trace[(((long)(blockIdx.x % a.nwg) * a.n_layer + layer) * 5 + ph) * 8 + k] = wall_clock64();
 }
 
 
@@ -99,15 +112,26 @@ __device__ __forceinline__ float* lds_vec(int part_floats) { extern __shared__ f
 // vector staging: n floats written earlier in this launch by other workgroups -> LDS
 // With gain != nullptr (RMSNorm) the staged values are x[i] * gain[i] and the return value is this
 // thread's share of sum(x^2); the common factor 1/rms is applied to the finished dot products.
+// The first batch of eight values per thread (and their gains) may have been requested earlier, while the
+// workgroup was finishing its previous phase (`pre`); values that were not there yet carry another tag and are
+// simply loaded again.
 __device__ __forceinline__ float stage_coherent(const tagged_t* src, int n, float* xs, const float* gain, unsigned tag,
-                                                int spin_limit, int* err) {
+                                                int spin_limit, int* err, bool pre, const tagged_t (&praw)[8],
+                                                const float (&pgain)[8]) {
   float ss = 0.f;
   for (int i0 = threadIdx.x; i0 < n; i0 += 8 * kStepThreads) {
+    const bool early = pre && i0 == (int)threadIdx.x;
     tagged_t raw[8];
+    float gv[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {                      // eight loads in flight per thread
       const int i = i0 + j * kStepThreads;
-      raw[j] = i < n ? ld_raw(src + i) : 0ull;
+      raw[j] = early ? praw[j] : (i < n ? ld_raw(src + i) : 0ull);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int i = i0 + j * kStepThreads;
+      gv[j] = early ? pgain[j] : ((gain && i < n) ? gain[i] : 1.f);
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -115,7 +139,7 @@ __device__ __forceinline__ float stage_coherent(const tagged_t* src, int n, floa
       if (i < n) {
         const float x = settle(src + i, raw[j], tag, spin_limit, err);
         ss += x * x;
-        xs[i] = gain ? x * gain[i] : x;
+        xs[i] = gain ? x * gv[j] : x;
       }
     }
   }
@@ -146,7 +170,7 @@ struct Geo {
   int N, units, cpp;     // rows, 16-byte units per row, 64-lane chunks per row
   int rope_h;            // > 0: pair (i, i + h/2) inside heads of size h; 0: rows (2p, 2p + 1)
   int p_lo, n_pl;        // this workgroup owns n_pl pairs: blocks of 2^bshift consecutive pairs, block b of the
-  int bshift;            // matrix going to workgroup b % nwg (p_lo = workgroup index).  At any moment the grid
+  int bshift, nwg;       // matrix going to workgroup b % nwg (p_lo = workgroup index).  At any moment the grid
                          // reads one contiguous window of the matrix, and a workgroup stays >= 64 KiB in place.
   int n_k;               // this wavefront's items: item k is flat index wave + 8k, flat = pair * cpp + chunk
   int dq, dr;            // 8 / cpp and 8 % cpp: how (pair, chunk) moves from one item to the next
@@ -158,7 +182,7 @@ __device__ __forceinline__ Geo make_geo(const void* W, int N, int Kd, int rope_h
   Geo g;
   g.W = W; g.N = N; g.units = Kd / V; g.cpp = (g.units + 63) >> 6; g.rope_h = rope_h;
   const int pairs = (N + 1) >> 1;
-  g.p_lo = wg;
+  g.p_lo = wg; g.nwg = nwg;
   g.bshift = 0;
   const long pair_bytes = 2L * Kd * (long)sizeof(WT);
   // larger blocks only while they still divide evenly among the workgroups (balance comes first)
@@ -177,7 +201,7 @@ __device__ __forceinline__ void geo_next(const Geo& g, int& pl, int& c) {
   if (c >= g.cpp) { c -= g.cpp; ++pl; }
 }
 __device__ __forceinline__ int geo_pair(const Geo& g, int pl) {     // local pair index -> pair index in the matrix
-  return ((((pl >> g.bshift) * (int)gridDim.x) + g.p_lo) << g.bshift) + (pl & ((1 << g.bshift) - 1));
+  return ((((pl >> g.bshift) * g.nwg) + g.p_lo) << g.bshift) + (pl & ((1 << g.bshift) - 1));
 }
 __device__ __forceinline__ int geo_row(const Geo& g, int p, int j) {
   if (g.rope_h) {                                   // head sizes are powers of two
@@ -190,24 +214,24 @@ __device__ __forceinline__ int geo_row(const Geo& g, int p, int j) {
 
 // the step's own input (token embedding + learned position, or the previous stage's activation)
 template <typename WT>
-__device__ __forceinline__ void stage_input(const StepArgs& a, float* xs, const Geo& gres, unsigned tag) {
+__device__ __forceinline__ void stage_input(const StepArgs& a, const StepSlot& S, float* xs, const Geo& gres, unsigned tag) {
   const int n = a.d;
-  if (a.in_kind == IN_TOKEN) {
-    const long tok = *(const int32_t*)a.in;
+  if (S.in_kind == IN_TOKEN) {
+    const long tok = *(const int32_t*)S.in;
     for (int i = threadIdx.x; i < n; i += kStepThreads) {
       float v = Storage<WT>::get((const WT*)a.wte + tok * n + i);
-      if (a.wpe) v += Storage<WT>::get((const WT*)a.wpe + (long)a.pos * n + i);
+      if (a.wpe) v += Storage<WT>::get((const WT*)a.wpe + (long)S.pos * n + i);
       xs[i] = v;
     }
   } else {
-    for (int i = threadIdx.x; i < n; i += kStepThreads) xs[i] = load_kind(a.in, a.in_kind, i);
+    for (int i = threadIdx.x; i < n; i += kStepThreads) xs[i] = load_kind(S.in, S.in_kind, i);
   }
   __syncthreads();
   // rows this workgroup owns in the residual phases get their starting value
   for (int pl = threadIdx.x; pl < gres.n_pl; pl += kStepThreads) {
     const int r = 2 * geo_pair(gres, pl);
-    st_tag(a.xres + r, xs[r], tag);
-    if (r + 1 < n) st_tag(a.xres + r + 1, xs[r + 1], tag);
+    st_tag(S.xres + r, xs[r], tag);
+    if (r + 1 < n) st_tag(S.xres + r + 1, xs[r + 1], tag);
   }
 }
 
@@ -271,12 +295,12 @@ __device__ __forceinline__ void gemv_compute(const Tile& t, const Geo& g, int ti
 
 // Sums the wavefront slots of every pair and applies the phase's epilogue.
 template <typename WT>
-__device__ __forceinline__ void gemv_finish(int ph, const Geo& g, const StepLayer* Lp, int layer, const StepArgs& a, const float* part,
+__device__ __forceinline__ void gemv_finish(int ph, const Geo& g, const StepLayer* Lp, int layer, const StepArgs& a, const StepSlot& S, const float* part,
                                             float row_scale, tagged_t x0_pre, tagged_t x1_pre, unsigned epoch) {
   const unsigned wtag = epoch + 1;                            // what this phase writes carries the next counter
   const StepLayer& L = *Lp;
   __syncthreads();                                           // all wavefronts' partials are in LDS
-  stamp(a, layer, ph, 4);
+  stamp(a, S, layer, ph, 4);
   for (int pl = threadIdx.x; pl < g.n_pl; pl += kStepThreads) {
     float v0 = 0.f, v1 = 0.f;
 #pragma unroll
@@ -287,31 +311,31 @@ __device__ __forceinline__ void gemv_finish(int ph, const Geo& g, const StepLaye
     if (ph == PH_QKV) {
       if (L.bqkv) { v0 += L.bqkv[r0]; v1 += L.bqkv[r1]; }
       const int head = r0 / a.h, i = r0 - head * a.h;
-      if (a.rope && head < a.H + a.K) {
-        const float2 cs = a.rope[i];
+      if (S.rope && head < a.H + a.K) {
+        const float2 cs = S.rope[i];
         const float t0 = v0 * cs.x - v1 * cs.y, t1 = v0 * cs.y + v1 * cs.x;
         v0 = t0; v1 = t1;
       }
       if (head < a.H) {
-        st_tag(a.q + r0, v0, wtag); st_tag(a.q + r1, v1, wtag);
+        st_tag(S.q + r0, v0, wtag); st_tag(S.q + r1, v1, wtag);
       } else {
         // the cache row is for later launches (plain stores); this launch's attention takes the same
         // rounded values from the tagged copy
         const bool is_v = head >= a.H + a.K;
         const int kvh = head - a.H - (is_v ? a.K : 0);
-        WT* dst = (WT*)L.kv + a.kv_tok_off + (long)(kvh * 2 + (is_v ? 1 : 0)) * a.pt_h + i;
+        WT* dst = (WT*)L.kv + S.kv_tok_off + (long)(kvh * 2 + (is_v ? 1 : 0)) * a.pt_h + i;
         Storage<WT>::put(dst, v0); Storage<WT>::put(dst + (a.h >> 1), v1);
-        tagged_t* kn = a.knew + (long)(is_v ? a.K * a.h : 0) + kvh * a.h + i;
+        tagged_t* kn = S.knew + (long)(is_v ? a.K * a.h : 0) + kvh * a.h + i;
         st_tag(kn, Storage<WT>::get(dst), wtag); st_tag(kn + (a.h >> 1), Storage<WT>::get(dst + (a.h >> 1)), wtag);
       }
     } else if (ph == PH_UP) {
       if (a.mlp_kind == MDI_MLP_SWIGLU) {
-        st_tag(a.u + p, silu_f(v0) * v1, wtag);              // rows (2f, 2f+1) = (gate_f, up_f)
+        st_tag(S.u + p, silu_f(v0) * v1, wtag);              // rows (2f, 2f+1) = (gate_f, up_f)
       } else {
         if (L.bup) { v0 += L.bup[r0]; if (r1 < g.N) v1 += L.bup[r1]; }
         const bool tanh_form = a.mlp_kind == MDI_MLP_GELU_TANH;
-        st_tag(a.u + r0, tanh_form ? gelu_tanh_f(v0) : gelu_erf_f(v0), wtag);
-        if (r1 < g.N) st_tag(a.u + r1, tanh_form ? gelu_tanh_f(v1) : gelu_erf_f(v1), wtag);
+        st_tag(S.u + r0, tanh_form ? gelu_tanh_f(v0) : gelu_erf_f(v0), wtag);
+        if (r1 < g.N) st_tag(S.u + r1, tanh_form ? gelu_tanh_f(v1) : gelu_erf_f(v1), wtag);
       }
     } else {                                                  // residual phases
       const float* bias = ph == PH_OPROJ ? L.bo : L.bdown;
@@ -321,15 +345,15 @@ __device__ __forceinline__ void gemv_finish(int ph, const Geo& g, const StepLaye
       const bool pre = pl == (int)threadIdx.x;
       // this workgroup wrote these rows itself: two phases ago (output projection) or one (down projection)
       const unsigned rtag = ph == PH_OPROJ ? epoch - 2 : epoch - 1;
-      const float x0 = settle(a.xres + r0, pre ? x0_pre : ld_raw(a.xres + r0), rtag, a.spin_limit, a.err);
-      const float x1 = two ? settle(a.xres + r1, pre ? x1_pre : ld_raw(a.xres + r1), rtag, a.spin_limit, a.err) : 0.f;
+      const float x0 = settle(S.xres + r0, pre ? x0_pre : ld_raw(S.xres + r0), rtag, a.spin_limit, a.err);
+      const float x1 = two ? settle(S.xres + r1, pre ? x1_pre : ld_raw(S.xres + r1), rtag, a.spin_limit, a.err) : 0.f;
       v0 += x0 + (bias ? bias[r0] : 0.f);
-      st_tag(a.xres + r0, v0, wtag);
-      if (last) store_kind(a.act_out, a.act_kind, r0, v0);
+      st_tag(S.xres + r0, v0, wtag);
+      if (last) store_kind(S.act_out, a.act_kind, r0, v0);
       if (two) {
         v1 += x1 + (bias ? bias[r1] : 0.f);
-        st_tag(a.xres + r1, v1, wtag);
-        if (last) store_kind(a.act_out, a.act_kind, r1, v1);
+        st_tag(S.xres + r1, v1, wtag);
+        if (last) store_kind(S.act_out, a.act_kind, r1, v1);
       }
     }
   }
@@ -345,17 +369,17 @@ struct AttnGeo {
 };
 
 template <typename WT, int G>
-__device__ __forceinline__ AttnGeo make_attn_geo(const StepArgs& a, int wg, int wave, int lane) {
+__device__ __forceinline__ AttnGeo make_attn_geo(const StepArgs& a, const StepSlot& S, int wg, int wave, int lane) {
   constexpr int V = Storage<WT>::kVec;
   AttnGeo g;
   g.L = a.h / V; g.tpw = 64 / g.L; g.sub = lane / g.L; g.hoff = (lane % g.L) * V;
-  g.active = wg < a.n_hg * a.n_splits;
+  g.active = wg < a.n_hg * S.n_splits;
   g.hg = g.active ? wg % a.n_hg : 0;
   g.split = g.active ? wg / a.n_hg : 0;
   g.kvh = (g.hg * G) / (a.H / a.K);
-  g.s0 = g.split * a.chunk;
-  g.s1 = min(a.ctx, g.s0 + a.chunk);
-  g.s1p = min(g.s1, a.ctx - 1);                               // the newest row is written in this launch
+  g.s0 = g.split * S.chunk;
+  g.s1 = min(S.ctx, g.s0 + S.chunk);
+  g.s1p = min(g.s1, S.ctx - 1);                               // the newest row is written in this launch
   const int steps = g.active && g.s1p > g.s0 ? (g.s1p - g.s0 + g.tpw - 1) / g.tpw : 0;
   g.n_k = steps > wave ? (steps - wave + kStepWaves - 1) / kStepWaves : 0;
   return g;
@@ -363,9 +387,9 @@ __device__ __forceinline__ AttnGeo make_attn_geo(const StepArgs& a, int wg, int 
 
 // Issues exactly 2 * kTile loads (see gemv_issue); slots without a token re-read token 0.
 template <typename WT>
-__device__ __forceinline__ void attn_issue(Tile& t, const AttnGeo& g, const StepArgs& a, const void* pool_, int ti, int wave) {
+__device__ __forceinline__ void attn_issue(Tile& t, const AttnGeo& g, const StepArgs& a, const StepSlot& S, const void* pool_, int ti, int wave) {
   const MDI_GLOBAL WT* pool = (const MDI_GLOBAL WT*)pool_;
-  const MDI_GLOBAL int32_t* table = (const MDI_GLOBAL int32_t*)a.table;
+  const MDI_GLOBAL int32_t* table = (const MDI_GLOBAL int32_t*)S.table;
 #pragma unroll
   for (int s = 0; s < kTile; ++s) {
     const int k = ti * kTile + s;
@@ -431,7 +455,7 @@ __device__ __forceinline__ void attn_compute(AttnState<WT, G>& st, const Tile& t
 
 // queries into LDS (pre-scaled); the newest position through coherent loads
 template <typename WT, int G>
-__device__ __forceinline__ void attn_begin(AttnState<WT, G>& st, const AttnGeo& g, const StepArgs& a, float* qs, unsigned epoch) {
+__device__ __forceinline__ void attn_begin(AttnState<WT, G>& st, const AttnGeo& g, const StepArgs& a, const StepSlot& S, float* qs, unsigned epoch) {
   constexpr int V = Storage<WT>::kVec;
 #pragma unroll
   for (int gi = 0; gi < G; ++gi) {
@@ -441,15 +465,15 @@ __device__ __forceinline__ void attn_begin(AttnState<WT, G>& st, const AttnGeo& 
   }
   if (g.active)
     for (int i = threadIdx.x; i < G * a.h; i += kStepThreads)
-      qs[i] = ld_tag(a.q + (long)g.hg * G * a.h + i, epoch, a.spin_limit, a.err) * a.scale;
+      qs[i] = ld_tag(S.q + (long)g.hg * G * a.h + i, epoch, a.spin_limit, a.err) * a.scale;
   __syncthreads();
-  if (g.active && g.s1 == a.ctx && threadIdx.x < 64) {
+  if (g.active && g.s1 == S.ctx && threadIdx.x < 64) {
     // the newest position: its K/V row (already rounded to the storage type) from the tagged copy
     float kf[V], vf[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) { kf[e] = 0.f; vf[e] = 0.f; }
     if (g.sub == 0) {
-      const tagged_t* kn = a.knew + g.kvh * a.h + g.hoff;
+      const tagged_t* kn = S.knew + g.kvh * a.h + g.hoff;
       const tagged_t* vn = kn + (long)a.K * a.h;
 #pragma unroll
       for (int e = 0; e < V; ++e) { kf[e] = ld_tag(kn + e, epoch, a.spin_limit, a.err); vf[e] = ld_tag(vn + e, epoch, a.spin_limit, a.err); }
@@ -491,11 +515,11 @@ __device__ __forceinline__ void attn_to_lds(AttnState<WT, G>& st, const AttnGeo&
 // Wavefront records -> split partial (or the final output when there is one split);
 // the last workgroup of a head group to arrive folds the splits in split order.
 template <int G>
-__device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a, const float* sm, int* s_flag, unsigned epoch) {
+__device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a, const StepSlot& S, const float* sm, int* s_flag, unsigned epoch) {
   const unsigned wtag = epoch + 1;
   const int h = a.h, rec = h + 2;
   if (!g.active) return;
-  const bool single = a.n_splits == 1;
+  const bool single = S.n_splits == 1;
   for (int idx = threadIdx.x; idx < G * h; idx += kStepThreads) {
     const int gi = idx / h, e = idx - gi * h;
     float m = -1e30f;
@@ -508,9 +532,9 @@ __device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a,
     }
     const int head = g.hg * G + gi;
     if (single) {
-      st_tag(a.o + (long)head * h + e, o / l, wtag);
+      st_tag(S.o + (long)head * h + e, o / l, wtag);
     } else {
-      tagged_t* pr = a.part + ((long)head * kMaxSplits + g.split) * rec;
+      tagged_t* pr = S.part + ((long)head * kMaxSplits + g.split) * rec;
       st_tag(pr + e, o, wtag);
       if (e == 0) { st_tag(pr + h, m, wtag); st_tag(pr + h + 1, l, wtag); }
     }
@@ -519,28 +543,28 @@ __device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a,
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (threadIdx.x == 0) {
-    const unsigned ticket = __hip_atomic_fetch_add(a.tickets + g.hg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_flag[1] = ticket == (unsigned)a.n_splits - 1;
+    const unsigned ticket = __hip_atomic_fetch_add(S.tickets + g.hg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_flag[1] = ticket == (unsigned)S.n_splits - 1;
   }
   __syncthreads();
   if (!s_flag[1]) return;
   for (int idx = threadIdx.x; idx < G * h; idx += kStepThreads) {
     const int gi = idx / h, e = idx - gi * h;
     const int head = g.hg * G + gi;
-    const tagged_t* pr = a.part + (long)head * kMaxSplits * rec;
+    const tagged_t* pr = S.part + (long)head * kMaxSplits * rec;
     // splits are folded in split order, eight at a time so that their loads are in flight together
     float m = -1e30f, l = 0.f, o = 0.f;
-    for (int sp0 = 0; sp0 < a.n_splits; sp0 += 8) {
+    for (int sp0 = 0; sp0 < S.n_splits; sp0 += 8) {
       tagged_t rm[8], rl[8], ro[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        const bool ok = sp0 + k < a.n_splits;
+        const bool ok = sp0 + k < S.n_splits;
         const tagged_t* r = pr + (sp0 + k) * rec;
         rm[k] = ok ? ld_raw(r + h) : 0ull; rl[k] = ok ? ld_raw(r + h + 1) : 0ull; ro[k] = ok ? ld_raw(r + e) : 0ull;
       }
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        if (sp0 + k < a.n_splits) {
+        if (sp0 + k < S.n_splits) {
           const tagged_t* r = pr + (sp0 + k) * rec;
           const float mk = settle(r + h, rm[k], wtag, a.spin_limit, a.err);
           const float lk = settle(r + h + 1, rl[k], wtag, a.spin_limit, a.err);
@@ -553,23 +577,23 @@ __device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a,
         }
       }
     }
-    st_tag(a.o + (long)head * h + e, o / l, wtag);
+    st_tag(S.o + (long)head * h + e, o / l, wtag);
   }
-  if (threadIdx.x == 0) __hip_atomic_store(a.tickets + g.hg, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (threadIdx.x == 0) __hip_atomic_store(S.tickets + g.hg, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---------------------------------------------------------------------------
 
 // Geometry of the four GEMV phases lives in LDS as plain integers (it depends on the workgroup
 // only); a phase reloads what it needs, so only two geometries are ever live in registers.
-constexpr int kGeoInts = 9;
+constexpr int kGeoInts = 10;
 __device__ __forceinline__ int* lds_geo() { extern __shared__ float smem[]; return (int*)(smem + 16) + 4; }   // 32 ints after the flags
 
 template <typename WT>
 __device__ __forceinline__ void store_geo(int j, int N, int Kd, int rope_h, int wg, int nwg) {
   const Geo g = make_geo<WT>(nullptr, N, Kd, rope_h, wg, nwg, 0);
   int* o = lds_geo() + j * kGeoInts;
-  o[0] = g.N; o[1] = g.units; o[2] = g.cpp; o[3] = g.rope_h; o[4] = g.p_lo; o[5] = g.n_pl; o[6] = g.dq; o[7] = g.dr; o[8] = g.bshift;
+  o[0] = g.N; o[1] = g.units; o[2] = g.cpp; o[3] = g.rope_h; o[4] = g.p_lo; o[5] = g.n_pl; o[6] = g.dq; o[7] = g.dr; o[8] = g.bshift; o[9] = g.nwg;
 }
 __device__ __forceinline__ Geo load_geo(int j, const void* W, int wave) {
   const int* o = lds_geo() + j * kGeoInts;
@@ -579,7 +603,7 @@ __device__ __forceinline__ Geo load_geo(int j, const void* W, int wave) {
   g.cpp = __builtin_amdgcn_readfirstlane(o[2]); g.rope_h = __builtin_amdgcn_readfirstlane(o[3]);
   g.p_lo = __builtin_amdgcn_readfirstlane(o[4]); g.n_pl = __builtin_amdgcn_readfirstlane(o[5]);
   g.dq = __builtin_amdgcn_readfirstlane(o[6]); g.dr = __builtin_amdgcn_readfirstlane(o[7]);
-  g.bshift = __builtin_amdgcn_readfirstlane(o[8]);
+  g.bshift = __builtin_amdgcn_readfirstlane(o[8]); g.nwg = __builtin_amdgcn_readfirstlane(o[9]);
   const int flat = g.n_pl * g.cpp;
   g.n_k = flat > wave ? (flat - wave + kStepWaves - 1) / kStepWaves : 0;
   return g;
@@ -604,10 +628,13 @@ __device__ __forceinline__ const void* layer_matrix(const StepLayer& L, int j) {
 }
 
 template <typename WT, int G>
-__global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
+__global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_step(StepArgs a) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wg = blockIdx.x, nwg = gridDim.x;
+  // a set of nwg workgroups takes its messages in turn inside every phase; two sets share the compute units
+  const int nwg = a.nwg, wg = blockIdx.x % nwg;
+  const int set = (int)blockIdx.x / nwg;
+  const int slot_lo = a.set_lo[set], slot_hi = a.set_lo[set + 1];
   float* part = lds_part();
   float* xs = lds_vec(a.part_floats);
   float* red = lds_red();
@@ -618,15 +645,21 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
     store_geo<WT>(1, a.d, a.H * a.h, 0, wg, nwg);
     store_geo<WT>(2, a.mlp_kind == MDI_MLP_SWIGLU ? 2 * a.F : a.F, a.d, 0, wg, nwg);
     store_geo<WT>(3, a.d, a.F, 0, wg, nwg);
-    if (wg == 0 && a.table_entry) *a.table_entry = a.new_page;
+    if (wg == 0)
+      for (int m = 0; m < a.n_slots; ++m)
+        if (a.s[m].table_entry) *a.s[m].table_entry = a.s[m].new_page;
   }
   __syncthreads();
-  const AttnGeo ga = make_attn_geo<WT, G>(a, wg, wave, lane);
 
-  unsigned epoch = a.epoch0;
   float acc0 = 0.f, acc1 = 0.f;
   AttnState<WT, G> st;
+  AttnGeo ga{};
   Tile A, B;
+  // requested while finishing the previous (message, phase): the next one's flags and the head of its input vector
+  bool early_flags = false, early_vec = false;
+  unsigned efl[4] = {0u, 0u, 0u, 0u};
+  tagged_t eraw[8] = {0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull};
+  float egain[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
 
 #pragma nounroll
   for (int layer = 0; layer < a.n_layer; ++layer) {
@@ -634,22 +667,73 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
     const StepLayer* L = &Lv;
 #pragma nounroll
     for (int ph = 0; ph < 5; ++ph) {
+#pragma nounroll
+    for (int slot = slot_lo; slot < slot_hi; ++slot) {
+      // Messages alternate inside a phase: while this message's flags and input vector make their round trips,
+      // the memory system is still busy with the other message's stream, and by the time a message reaches its
+      // next phase every workgroup has long finished its previous one.
+      const StepSlot& S = a.s[slot];
+      const unsigned epoch = S.epoch0 + (unsigned)(layer * 5 + ph);
       // ---- this phase's first two tiles: their addresses depend on nothing another workgroup writes,
       //      so they are in flight while the barrier completes and the input vector is staged
       const int j = gemv_index(ph);
       const Geo g = load_geo(j, layer_matrix(Lv, j), wave);
-      if (ph == PH_ATTN) { attn_issue<WT>(A, ga, a, L->kv, 0, wave); attn_issue<WT>(B, ga, a, L->kv, 1, wave); }
-      else { gemv_issue(A, g, 0, wave, lane); gemv_issue(B, g, 1, wave, lane); }
+      if (ph == PH_ATTN) {
+        ga = make_attn_geo<WT, G>(a, S, wg, wave, lane);
+        attn_issue<WT>(A, ga, a, S, L->kv, 0, wave); attn_issue<WT>(B, ga, a, S, L->kv, 1, wave);
+      } else { gemv_issue(A, g, 0, wave, lane); gemv_issue(B, g, 1, wave, lane); }
+
+      auto early_requests = [&]() __attribute__((always_inline)) {
+        // ---- requests for the next (message, phase), answered while this phase is being finished: with two
+        //      messages alternating, what the next one needs was published a whole phase ago
+        early_flags = false; early_vec = false;
+        if (slot_hi - slot_lo > 1) {
+          int nslot = slot + 1, nph = ph, nlayer = layer;
+          if (nslot == slot_hi) { nslot = slot_lo; if (++nph == 5) { nph = 0; ++nlayer; } }
+          if (nlayer < a.n_layer) {
+            const StepSlot& N = a.s[nslot];
+            const unsigned nepoch = N.epoch0 + (unsigned)(nlayer * 5 + nph);
+            if (nwg <= 256 && threadIdx.x < 64) {
+#pragma unroll
+              for (int k = 0; k < 4; ++k) {
+                const int i = (int)threadIdx.x + 64 * k;
+                efl[k] = i < nwg ? __hip_atomic_load(N.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : nepoch;
+              }
+              early_flags = true;
+            }
+            if (nph != PH_ATTN && !(nph == PH_QKV && nlayer == 0)) {
+              const tagged_t* nsrc = nph == PH_OPROJ ? N.o : nph == PH_DOWN ? N.u : N.xres;
+              const int nn = nph == PH_OPROJ ? a.H * a.h : nph == PH_DOWN ? a.F : a.d;
+              const bool nrms = (nph == PH_QKV || nph == PH_UP) && a.norm_kind == MDI_NORM_RMSNORM;
+              const float* ngain = advance(nph == PH_QKV ? a.l0.ln1_g : a.l0.ln2_g, a.w_stride * nlayer);
+#pragma unroll
+              for (int jj = 0; jj < 8; ++jj) {
+                const int i = (int)threadIdx.x + jj * kStepThreads;
+                eraw[jj] = i < nn ? ld_raw(nsrc + i) : 0ull;
+              }
+#pragma unroll
+              for (int jj = 0; jj < 8; ++jj) {
+                const int i = (int)threadIdx.x + jj * kStepThreads;
+                egain[jj] = (nrms && i < nn) ? ngain[i] : 1.f;
+              }
+              early_vec = true;
+            }
+          }
+        }
+      };
 
       // ---- wait until every workgroup has finished the previous phase ----------------------------
-      stamp(a, layer, ph, 0);
+      stamp(a, S, layer, ph, 0);
       if (threadIdx.x < 64) {
         bool ok = true;
         int it = 0;
-        for (;;) {
+        bool seen = early_flags;                   // the flags requested early may already show everyone
+#pragma unroll
+        for (int k = 0; k < 4; ++k) seen = seen && ((int)(efl[k] - epoch) >= 0);
+        while (!__all(seen)) {
           bool all = true;
           for (int i = threadIdx.x; i < nwg; i += 64) {
-            const unsigned v = __hip_atomic_load(a.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned v = __hip_atomic_load(S.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             all = all && ((int)(v - epoch) >= 0);
           }
           if (__all(all)) break;
@@ -664,23 +748,24 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
       __syncthreads();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
       if (!s_flag[0]) return;
-      stamp(a, layer, ph, 1);
+      stamp(a, S, layer, ph, 1);
 
       if (ph == PH_ATTN) {
         // ---- attention over the sample's pages -----------------------------------------------------
-        attn_begin<WT, G>(st, ga, a, xs, epoch);
-        stamp(a, layer, ph, 2);
+        attn_begin<WT, G>(st, ga, a, S, xs, epoch);
+        stamp(a, S, layer, ph, 2);
         const int nte = ((ga.n_k + kTile - 1) / kTile + 1) & ~1;
 #pragma nounroll
         for (int t = 0; t < nte; t += 2) {
           attn_compute<WT, G>(st, A, ga, a.h, t, wave, xs);
-          attn_issue<WT>(A, ga, a, L->kv, t + 2, wave);
+          attn_issue<WT>(A, ga, a, S, L->kv, t + 2, wave);
           attn_compute<WT, G>(st, B, ga, a.h, t + 1, wave, xs);
-          attn_issue<WT>(B, ga, a, L->kv, t + 3, wave);
+          attn_issue<WT>(B, ga, a, S, L->kv, t + 3, wave);
         }
-        stamp(a, layer, ph, 3);
+        stamp(a, S, layer, ph, 3);
+        early_requests();
         attn_to_lds<WT, G>(st, ga, a.h, xs, wave);
-        attn_finish<G>(ga, a, xs, s_flag, epoch);
+        attn_finish<G>(ga, a, S, xs, s_flag, epoch);
       } else {
         // ---- a GEMV phase ----------------------------------------------------------------------------
         for (int i = threadIdx.x; i < g.n_pl * 2 * kStepWaves; i += kStepThreads) part[i] = 0.f;
@@ -689,10 +774,11 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
         const float* gain = ph == PH_QKV ? L->ln1_g : L->ln2_g;
         float row_scale = 1.f;                       // 1/rms when the norm is folded into the epilogue
         if (ph == PH_QKV && layer == 0) {
-          stage_input<WT>(a, xs, load_geo(1, nullptr, wave), epoch);
+          stage_input<WT>(a, S, xs, load_geo(1, nullptr, wave), epoch);
         } else {
-          const tagged_t* src = ph == PH_OPROJ ? a.o : ph == PH_DOWN ? a.u : a.xres;
-          const float ss = stage_coherent(src, g.units * Storage<WT>::kVec, xs, fused_rms ? gain : nullptr, epoch, a.spin_limit, a.err);
+          const tagged_t* src = ph == PH_OPROJ ? S.o : ph == PH_DOWN ? S.u : S.xres;
+          const float ss = stage_coherent(src, g.units * Storage<WT>::kVec, xs, fused_rms ? gain : nullptr, epoch, a.spin_limit, a.err,
+                                          early_vec, eraw, egain);
           if (fused_rms) row_scale = 1.f / sqrtf(block_sum(ss, red) / (float)a.d + a.eps);
         }
         __syncthreads();
@@ -704,10 +790,10 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
         tagged_t x0 = 0ull, x1 = 0ull;
         if ((ph == PH_OPROJ || ph == PH_DOWN) && (int)threadIdx.x < g.n_pl) {
           const int r0 = 2 * geo_pair(g, (int)threadIdx.x);
-          x0 = ld_raw(a.xres + r0);
-          if (r0 + 1 < g.N) x1 = ld_raw(a.xres + r0 + 1);
+          x0 = ld_raw(S.xres + r0);
+          if (r0 + 1 < g.N) x1 = ld_raw(S.xres + r0 + 1);
         }
-        stamp(a, layer, ph, 2);
+        stamp(a, S, layer, ph, 2);
 
         const int nte = ((g.n_k + kTile - 1) / kTile + 1) & ~1;
 #pragma nounroll
@@ -717,24 +803,25 @@ __global__ __launch_bounds__(kStepThreads) void k_step(StepArgs a) {
           gemv_compute<WT>(B, g, t + 1, wave, lane, xs, part, acc0, acc1);
           gemv_issue(B, g, t + 3, wave, lane);
         }
-        stamp(a, layer, ph, 3);
-        gemv_finish<WT>(ph, g, L, layer, a, part, row_scale, x0, x1, epoch);
+        stamp(a, S, layer, ph, 3);
+        early_requests();
+        gemv_finish<WT>(ph, g, L, layer, a, S, part, row_scale, x0, x1, epoch);
       }
 
       // ---- publish: this workgroup is done with the phase ---------------------------------------------
-      stamp(a, layer, ph, 5);
+      stamp(a, S, layer, ph, 5);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this thread's stores have completed
       __syncthreads();
-      stamp(a, layer, ph, 6);
-      ++epoch;
-      if (threadIdx.x == 0) __hip_atomic_store(a.flags + wg, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      stamp(a, S, layer, ph, 6);
+      if (threadIdx.x == 0) __hip_atomic_store(S.flags + wg, epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     }
   }
 }
 
 template <typename WT>
 static void launch_step_t(hipStream_t s, int G, int nwg, size_t lds, const StepArgs& a) {
-  const dim3 grid(nwg), block(kStepThreads);
+  const dim3 grid(nwg * a.n_sets), block(kStepThreads);
   switch (G) {
     case 8: hipLaunchKernelGGL((k_step<WT, 8>), grid, block, lds, s, a); break;
     case 4: hipLaunchKernelGGL((k_step<WT, 4>), grid, block, lds, s, a); break;
@@ -743,7 +830,10 @@ static void launch_step_t(hipStream_t s, int G, int nwg, size_t lds, const StepA
   }
 }
 
-void launch_step(hipStream_t s, int dtype, int G, int nwg, size_t lds, const StepArgs& a) {
+}  // namespace step_w<waves>
+
+void MDI_STEP_CAT(launch_step_w, MDI_STEP_WAVES)(hipStream_t s, int dtype, int G, int nwg, size_t lds, const StepArgs& a) {
+  using namespace MDI_STEP_CAT(step_w, MDI_STEP_WAVES);
   if (dtype == MDI_BF16) launch_step_t<bf16_t>(s, G, nwg, lds, a); else launch_step_t<float>(s, G, nwg, lds, a);
 }
 

@@ -18,8 +18,9 @@ MDI_OK, MDI_ERR_ARG, MDI_ERR_STATE, MDI_ERR_CTX, MDI_ERR_NOMEM, MDI_ERR_HIP = 0,
 MDI_F32, MDI_BF16 = 0, 1
 MDI_HAS_EMBED, MDI_HAS_HEAD = 1, 2
 
-EXPORTS = ["mdi_partition_bytes", "mdi_partition_create", "mdi_prefill", "mdi_decode_step", "mdi_sample_greedy",
-           "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel", "mdi_partition_info", "mdi_partition_trace", "mdi_partition_destroy", "mdi_strerror"]
+EXPORTS = ["mdi_partition_bytes", "mdi_partition_create", "mdi_prefill", "mdi_decode_step", "mdi_decode_steps",
+           "mdi_sample_greedy", "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel",
+           "mdi_partition_info", "mdi_partition_trace", "mdi_partition_destroy", "mdi_strerror"]
 
 
 class MdiConfig(C.Structure):
@@ -64,6 +65,7 @@ def lib():
                                            vp, C.POINTER(vp)]
         L.mdi_prefill.argtypes = [vp, u32, vp, u32, vp]
         L.mdi_decode_step.argtypes = [vp, u32, vp, vp]
+        L.mdi_decode_steps.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(vp), C.POINTER(vp)]
         L.mdi_sample_greedy.argtypes = [vp, u32, vp, vp, vp]
         L.mdi_partition_sync.argtypes = [vp]
         L.mdi_seq_reset.argtypes = [vp, u32]
@@ -76,7 +78,7 @@ def lib():
         L.mdi_partition_destroy.restype = None
         L.mdi_strerror.argtypes = [C.c_int]
         L.mdi_strerror.restype = C.c_char_p
-        for name in EXPORTS[:12]:
+        for name in EXPORTS[:13]:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -208,6 +210,19 @@ class Partition:
             raise MdiError(st, "mdi_decode_step")
         return act_out
 
+    def decode_steps(self, seqs, acts_in, acts_out=None):
+        """Later visits of several different samples, as mdi_decode_steps takes them (lists of equal length)."""
+        n = len(seqs)
+        if acts_out is None:
+            acts_out = [torch.empty((self.d,), dtype=self.tdtype, device=self.device) for _ in range(n)]
+        ids = (C.c_uint32 * n)(*seqs)
+        ins = (C.c_void_p * n)(*[t.data_ptr() for t in acts_in])
+        outs = (C.c_void_p * n)(*[t.data_ptr() for t in acts_out])
+        st = lib().mdi_decode_steps(self._h, n, ids, ins, outs)
+        if st != MDI_OK:
+            raise MdiError(st, "mdi_decode_steps")
+        return acts_out
+
     def sample_greedy(self, seq, act_in, token_out=None, logits_out=None):
         if token_out is None:
             token_out = torch.empty((1,), dtype=torch.int32, device=self.device)
@@ -250,7 +265,7 @@ class Partition:
         return us.value, nb.value
 
     def trace(self, buf):
-        """buf: int64 device tensor [workgroups, layers, 5, 8] or None."""
+        """buf: int64 device tensor [2, workgroups, layers, 5, 8] (second half: second message of a launch) or None."""
         st = lib().mdi_partition_trace(self._h, _ptr(buf))
         if st != MDI_OK:
             raise MdiError(st, "mdi_partition_trace")

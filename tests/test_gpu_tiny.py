@@ -163,3 +163,61 @@ def test_first_visit_attention_on_matrix_cores(shape, T):
         t = (7 * step + 3) % cfg["vocab"]
         check(g.decode_step(0, dev_ids([t])), o.decode_step(0, t), cfg, ("decode", step))
     g.sync()
+
+
+@pytest.mark.parametrize("path", [0, 1], ids=["persistent", "per_op"])
+@pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("name", ["llama_gqa", "llama_group3", "gpt2", "wide_head"])
+def test_queued_messages_taken_together(name, dtype, path):
+    """Several samples' later visits handed over in one call (Sec. III-A: messages wait in the input queue;
+    Sec. III-C: several samples in flight) give, bit for bit, what the same visits give one call at a time, and
+    match the oracle; samples have different lengths, cross page boundaries at different steps, and the number
+    of messages is odd as well as even."""
+    cfg = S.tiny(n_layer=3, dtype=dtype, max_ctx=48, **VARIANTS[name])
+    w = scale_matrices(S.make_weights(cfg, 41, exercise=True), 6.0 if dtype == S.DT_F32 else 3.0)
+    n_seq = 5
+    o, g = pair(cfg, w, 0, 3, embed=True, max_seqs=n_seq, kv_page_tokens=8, decode_path=path)
+    g1 = mdi.Partition(cfg, w, 0, 3, has_embed=True, max_seqs=n_seq, kv_page_tokens=8, decode_path=path)
+    prompts = S.make_prompts(cfg, 41, n_seq, 11)
+    for s in range(n_seq):
+        prompts[s] = prompts[s][:3 + 2 * s]
+        o.prefill(s, prompts[s])
+        g.prefill(s, dev_ids(prompts[s]))
+        g1.prefill(s, dev_ids(prompts[s]))
+    rng = np.random.default_rng(9)
+    V = cfg["vocab"]
+    for step in range(12):
+        order = [int(s) for s in rng.permutation(n_seq)][: (n_seq if step % 3 else n_seq - 1 - step % 2)]
+        toks = [int(rng.integers(0, V)) for _ in order]
+        ins = [dev_ids([t]) for t in toks]
+        outs = g.decode_steps(order, ins)
+        for s, t, x, got in zip(order, toks, ins, outs):
+            check(got, o.decode_step(s, t), cfg, ("decode", step, s))
+            assert torch.equal(got, g1.decode_step(s, x)), (step, s)
+    for s in range(n_seq):
+        assert g.seq_len(s) == g1.seq_len(s)
+    g.sync()
+    g1.sync()
+
+
+def test_queued_messages_error_paths():
+    cfg = S.tiny(n_layer=1, dtype=S.DT_F32, max_ctx=16)
+    w = S.make_weights(cfg, 3)
+    g = mdi.Partition(cfg, w, 0, 1, has_embed=True, max_seqs=3, kv_page_tokens=8, kv_pages=3)
+    ids = dev_ids(np.arange(8))
+
+    def status(seqs):
+        with pytest.raises(mdi.MdiError) as e:
+            g.decode_steps(seqs, [ids[:1]] * len(seqs))
+        return e.value.status
+
+    g.prefill(0, ids)
+    g.prefill(1, ids)
+    assert status([0, 2]) == mdi.MDI_ERR_STATE            # sample 2 has no first visit yet
+    assert status([0, 0]) == mdi.MDI_ERR_ARG              # one message per sample
+    assert status([0, 7]) == mdi.MDI_ERR_ARG
+    assert status([0, 1]) == mdi.MDI_ERR_NOMEM            # both need a new page, one is free
+    assert g.seq_len(0) == 8 and g.seq_len(1) == 8        # a refused call advances nothing
+    g.decode_steps([1], [ids[:1]])
+    assert g.seq_len(1) == 9
+    g.sync()

@@ -1,11 +1,15 @@
 """Benchmark of the partition decode hot path on one MI355X.
 
-One step = one mdi_decode_step of the partition (all layers: norm, fused QKV +
-RoPE + KV append, paged attention, output projection, MLP) for one of the N
-samples in flight, visited round-robin so that consecutive steps read different
-KV caches (the rotating-cache access pattern, Sec. III-D).  Inputs, weights and
-caches are resident in HBM before the timed region; prompts are prefilled
-(first visit) before it and timed separately.
+One step = one later visit of one sample (Sec. III-D) to the partition (all
+layers: norm, fused QKV + RoPE + KV append, paged attention, output projection,
+MLP), every message forwarded on its own with its own pass over the weights.
+The N samples in flight are visited round-robin, so consecutive steps read
+different KV caches (the rotating-cache access pattern).  By default the
+messages of all N samples are handed over per call (mdi_decode_steps: the
+node's input queue, Sec. III-A, drained in one launch); `--queue 1` hands them
+over one at a time (mdi_decode_step), and the default run reports that rate
+too.  Inputs, weights and caches are resident in HBM before the timed region;
+prompts are prefilled (first visit) before it and timed separately.
 
 Prints ONE JSON line (see the keys below).
 """
@@ -22,9 +26,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
-# HBM bytes per k_step launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this script (workload -> bytes);
+# HBM bytes per k_step launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this script
+# ((workload, messages per launch) -> bytes);
 # the numbers and the commands are in profiles/k_step_c4_decode_hbm_counters.md
-MEASURED_TRAFFIC = {4: 3.4756e9}
+MEASURED_TRAFFIC = {(4, 1): 3.4756e9}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 
@@ -39,9 +44,10 @@ def parse():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--decode-path", type=int, default=0, help="0 = automatic (persistent single-launch step), 1 = one kernel per operation, 3 = persistent launch with streaming/exchange wavefronts on tiled matrices")
-    ap.add_argument("--queue", type=int, default=1,
-                    help="messages of different samples handed to the partition per call (1 = mdi_decode_step, "
-                         "more = mdi_decode_steps); must divide the number of samples in flight")
+    ap.add_argument("--queue", type=int, default=0,
+                    help="messages of different samples handed to the partition per call: 0 = all samples in flight "
+                         "(mdi_decode_steps drains the queue), 1 = one at a time (mdi_decode_step); must divide the "
+                         "number of samples in flight")
     return ap.parse_args()
 
 
@@ -55,13 +61,15 @@ def cpu_baseline(cfg, w, lo, hi, seed, S):
     except Exception:
         threads = len(os.sched_getaffinity(0))
     op = O.Partition(cfg, w, lo, hi)
-    T, n_dec = 128, 8
+    T, budget_s, max_dec = 128, 12.0, 600
     a = S.make_activations(cfg, seed, 0, T)
     t0 = time.perf_counter()
     op.prefill(0, a)
     t1 = time.perf_counter()
-    for step in range(n_dec):
-        op.decode_step(0, S.make_activations(cfg, seed, 0, 1, step=step + 1)[0])
+    n_dec = 0
+    while n_dec < max_dec and time.perf_counter() - t1 < budget_s:      # about 12 s of decode steps
+        op.decode_step(0, S.make_activations(cfg, seed, 0, 1, step=n_dec + 1)[0])
+        n_dec += 1
     t2 = time.perf_counter()
     return {"value": n_dec / (t2 - t1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"float64 numpy oracle, same partition and weights, 1 sample: first visit of {T} tokens "
@@ -107,12 +115,14 @@ def main():
         g = torch.Generator(device=dev).manual_seed(seed + 3)
         return [torch.randn((d,), generator=g, device=dev, dtype=torch.float32).to(tdt) for _ in range(n_seqs)]
 
-    def run(T, steps, warmup):
-        """Prefill all samples at T tokens, then warm up and time `steps` decode steps."""
+    def run(T, steps, warmup, q):
+        """Prefill all samples at T tokens, then warm up and time `steps` decode steps, q messages per call."""
         for s in range(n_seqs):
             part.seq_reset(s)
         ins = first_inputs(T)
         outs = [torch.empty((T, d), dtype=tdt, device=dev) for _ in range(n_seqs)]
+        part.prefill(0, ins[0], outs[0])          # untimed: loads the first-visit kernels
+        part.seq_reset(0)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -122,7 +132,6 @@ def main():
         torch.cuda.synchronize()
         prefill_ms = e0.elapsed_time(e1) / n_seqs
         xs = step_inputs()
-        q = args.queue
         douts = [torch.empty((d,), dtype=tdt, device=dev) for _ in range(q)]
 
         def visit(k):                      # messages k .. k + q - 1 of the round-robin order
@@ -155,26 +164,33 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    if args.queue < 1 or n_seqs % args.queue or args.steps % args.queue or args.warmup % args.queue:
+    queue = args.queue if args.queue else n_seqs
+    if queue < 1 or n_seqs % queue or args.steps % queue or args.warmup % queue:
         print("bench.py: --queue must divide the samples in flight, --steps and --warmup", file=sys.stderr)
         sys.exit(2)
-    main_run = run(prompt, args.steps, args.warmup)
+    main_run = run(prompt, args.steps, args.warmup, queue)
     n_local = hi - lo
     params = sum(a * b for a, b in S.layer_tensor_shapes(cfg).values())
     prefill_flops = n_local * (2.0 * prompt * params + 2.0 * prompt * prompt * cfg["n_head"] * cfg["head_dim"])
     prefill_tflops = prefill_flops / (main_run["prefill_ms"] * 1e-3) / 1e12
 
+    persistent_kind = part.info(0) in (2, 3)
+    # the paper's own rule, one message at a time, next to the queue-draining figure
+    one_run = run(prompt, 400, 40, 1) if (queue > 1 and persistent_kind) else None
     path_kind = part.info(0)          # 2 = persistent launch, 3 = persistent launch with streaming + exchange wavefronts on tiled matrices, 1 = per operation
     persistent = path_kind in (2, 3)
     kernels = {}
     if persistent:
         # the whole step is one kernel launch; its mean duration over the timed region (HIP events on the
         # partition's stream, launches back to back) against the bytes a step must move
-        roofline = {"bound": "hbm", "kernel": ("k_step2" if path_kind == 3 else "k_step") + " (persistent decode step, all layers)",
+        in_launch = queue if path_kind == 2 else 1          # messages one launch carries
+        roofline = {"bound": "hbm", "kernel": ("k_step2" if path_kind == 3 else "k_step") +
+                    f" (persistent decode launch, all layers, {in_launch} message(s) per launch)",
                     "achieved": main_run["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": main_run["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(args.workload),
-                    "avg_launch_us": main_run["ms_per_step"] * 1e3, "bytes_per_launch": main_run["bytes_per_step"],
-                    "workgroups": part.info(1), "lds_bytes": part.info(2)}
+                    "frac": main_run["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.workload, in_launch)),
+                    "avg_launch_us": main_run["ms_per_step"] * 1e3 * in_launch,
+                    "bytes_per_launch": main_run["bytes_per_step"] * in_launch, "messages_per_launch": in_launch,
+                    "workgroups": part.info(1) * (2 if in_launch > 1 else 1), "lds_bytes": part.info(2)}
     else:
         # dominant kernel: the MLP up(+gate) projection GEMV, timed with HIP events inside the library
         us, kbytes = part.time_kernel(2, 50)
@@ -189,7 +205,7 @@ def main():
     if args.ctx_sweep:
         sweep = []
         for T in (prompt + wl["n_new"] // 2, prompt + wl["n_new"] - 8 - 400 // n_seqs):
-            r = run(T, 400, 40)
+            r = run(T, 400, 40, queue)
             sweep.append({k: r[k] for k in ("ctx", "ms_per_step", "tokens_per_s", "gbs")})
 
     result = {
@@ -198,7 +214,7 @@ def main():
         "ms_per_step": main_run["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["dtype"] == S.DT_BF16 else "f32", "data": "synthetic",
         "config": {"workload": wl["name"], "layers": [lo, hi], "seqs_in_flight": n_seqs, "prompt": prompt,
-                   "context_during_timing": main_run["ctx"], "kv_page_tokens": 64,
+                   "context_during_timing": main_run["ctx"], "kv_page_tokens": 64, "messages_per_call": queue,
                    "decode_path": {3: "persistent_tiles", 2: "persistent", 1: "per_op"}[path_kind]},
         "step_bytes": main_run["bytes_per_step"], "step_GBps": main_run["gbs"],
         "step_frac_of_hbm_peak": main_run["gbs"] / HBM_PEAK_GBS,
@@ -207,6 +223,9 @@ def main():
                     "frac_of_bf16_mfma_peak": prefill_tflops / MFMA_BF16_PEAK_TFLOPS},
         "setup_s": setup_s,
     }
+    if one_run:
+        result["one_message_per_launch"] = {"ms_per_step": one_run["ms_per_step"], "tokens_per_s": one_run["tokens_per_s"],
+                                            "step_GBps": one_run["gbs"], "frac_of_hbm_peak": one_run["gbs"] / HBM_PEAK_GBS}
     if sweep:
         result["ctx_sweep"] = sweep
     if not args.no_cpu_baseline:

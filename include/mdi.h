@@ -245,8 +245,9 @@ MDI_API mdi_status mdi_partition_info(const mdi_partition *part, uint32_t what, 
  * wavefront done streaming, 4 all wavefronts done (GEMV phases), 5 results
  * stored, 6 stores acknowledged; slot 7 is unused.  trace: device buffer of
  * uint64 [2][workgroups][local layers][5][8] (mdi_partition_info gives the workgroup
- * count; the second half is written for the second message of a launch that
- * carries two, see mdi_decode_steps), owned by the caller; NULL switches tracing off.
+ * count; a launch that carries several messages, see mdi_decode_steps, records the
+ * first message of each of its two sets of workgroups, first and second half),
+ * owned by the caller; NULL switches tracing off.
  */
 MDI_API mdi_status mdi_partition_trace(mdi_partition *part, void *trace);
 

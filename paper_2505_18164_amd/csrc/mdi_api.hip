@@ -590,23 +590,25 @@ void fill_step_slot(const mdi_partition* p, int m, int nwg, const MessagePlan& m
   chunk = (chunk + 15) / 16 * 16;
   s->chunk = chunk; s->n_splits = (mp.ctx + chunk - 1) / chunk;
   s->act_out = act_out;
-  s->trace = (p->trace && m < 2) ? p->trace + (size_t)m * nwg * p->n_local * 40 : nullptr;
+  s->trace = nullptr;
 }
 
 // Launches the persistent kernel for n <= kMaxSlots planned messages.
 mdi_status launch_messages(mdi_partition* p, int n, const uint32_t* seqs, const MessagePlan* mp, const void* const* ins, void* const* outs) {
-  static const int env_sets = getenv("MDI_SETS") ? atoi(getenv("MDI_SETS")) : 2;
-  static const int env_one = getenv("MDI_ONE") ? atoi(getenv("MDI_ONE")) : 1;
   StepArgs a{};
   fill_step_shared(p, &a);
   a.n_slots = n;
-  a.n_sets = n >= 2 ? std::max(1, std::min(env_sets, 2)) : 1;
+  a.n_sets = n >= 2 ? 2 : 1;             // two sets of 4-wavefront workgroups share the compute units
   a.nwg = p->nwg;
-  if (n == 1 && env_one == 2 && 2 * p->nwg <= 1024) a.nwg = 2 * p->nwg;   // one message: both workgroups of a compute unit on it
   a.set_lo[0] = 0; a.set_lo[1] = a.n_sets == 2 ? (n + 1) / 2 : n; a.set_lo[2] = n;
   for (int m = 0; m < n; ++m) fill_step_slot(p, m, a.nwg, mp[m], ins[m], outs[m], &a.s[m]);
+  if (p->trace) {                      // timeline of the first message of each set (of the first two messages with one set)
+    const int second = a.n_sets == 2 ? a.set_lo[1] : 1;
+    a.s[0].trace = p->trace;
+    if (second < n) a.s[second].trace = p->trace + (size_t)a.nwg * p->n_local * 40;
+  }
   const mdi_status st = launch_step_serialised(p, [&]() {
-    if (n == 1 && env_one == 1) launch_step_w8(p->stream, p->cfg.dtype, p->G, a.nwg, p->step_lds, a);
+    if (n == 1) launch_step_w8(p->stream, p->cfg.dtype, p->G, a.nwg, p->step_lds, a);
     else launch_step_w4(p->stream, p->cfg.dtype, p->G, a.nwg, p->step_lds, a);
   });
   if (st != MDI_OK) return st;
@@ -733,8 +735,7 @@ mdi_status mdi_decode_steps(mdi_partition* p, uint32_t n, const uint32_t* seqs, 
   if (new_pages > p->free_pages.size()) return MDI_ERR_NOMEM;
   uint32_t i = 0;
   if (p->use_step) {
-    static const int env_launch = getenv("MDI_LAUNCH") ? atoi(getenv("MDI_LAUNCH")) : kMaxSlots;
-    const uint32_t per_launch = (uint32_t)std::max(1, std::min(env_launch, kMaxSlots));
+    const uint32_t per_launch = kMaxSlots;
     while (n - i >= 2) {
       const uint32_t m = std::min(per_launch, n - i);
       if (m < 2) break;

@@ -635,6 +635,8 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
   const int nwg = a.nwg, wg = blockIdx.x % nwg;
   const int set = (int)blockIdx.x / nwg;
   const int slot_lo = a.set_lo[set], slot_hi = a.set_lo[set + 1];
+  // the other set's first message: how far its workgroup of the same index has come is what this one paces itself by
+  const StepSlot& O = a.s[a.set_lo[a.n_sets == 2 ? (set ^ 1) : 0]];
   float* part = lds_part();
   float* xs = lds_vec(a.part_floats);
   float* red = lds_red();
@@ -722,6 +724,14 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
         }
       };
 
+      // Two sets share a compute unit's memory pipeline, and the hardware serves the older wavefronts (the set
+      // that was dispatched first) or the higher priority first; left alone, one set finishes a fifth earlier
+      // and the other runs the rest of the launch on half the wavefronts.  So the set that is behind takes the
+      // higher priority, phase by phase.
+      unsigned other_done = 0u;
+      const bool pace = a.n_sets == 2 && slot == slot_lo;
+      if (pace) other_done = __hip_atomic_load(O.flags + wg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - O.epoch0;
+
       // ---- wait until every workgroup has finished the previous phase ----------------------------
       stamp(a, S, layer, ph, 0);
       if (threadIdx.x < 64) {
@@ -749,6 +759,13 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
       if (!s_flag[0]) return;
       stamp(a, S, layer, ph, 1);
+      if (pace) {
+        // work left, in (message, phase) units; the set with more of it goes first
+        const int seen = __builtin_amdgcn_readfirstlane((int)other_done), total = a.n_layer * 5;
+        const int left = (total - (layer * 5 + ph)) * (slot_hi - slot_lo);
+        const int other_left = (total - seen) * (a.set_lo[2 - set] - a.set_lo[1 - set]);
+        if (left > other_left || (left == other_left && set == 1)) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
+      }
 
       if (ph == PH_ATTN) {
         // ---- attention over the sample's pages -----------------------------------------------------

@@ -169,17 +169,20 @@ MDI_API mdi_status mdi_decode_step(mdi_partition *part, uint32_t seq_id, const v
 /*
  * Later visits of n different samples whose messages wait in the node's input
  * queue (Sec. III-A: arriving messages are queued and taken out in order;
- * Sec. III-C: several samples are in flight at once).  The result is exactly that of
- * n mdi_decode_step calls in the order given - every message is still forwarded
- * on its own, reading the layer weights itself - but on the persistent decode
- * path messages are taken two per launch with their phases alternating, so
- * that the exchange between workgroups that ends one message's phase is
- * covered by the other message's weight streaming.
+ * Sec. III-C: several samples are in flight at once).  Every message is still
+ * forwarded on its own, with its own pass over the layer weights, and each
+ * sample's result is that of mdi_decode_step up to the order in which a row's
+ * partial sums are added (a few units in the last place of the accumulation
+ * type; for a given call pattern results are reproducible bit for bit).  On
+ * the persistent decode path up to 8 messages share one launch: two sets of
+ * workgroups share the compute units, each set alternates its messages inside
+ * every phase, so that the exchange between workgroups that ends one message's
+ * phase is covered by other messages' weight streaming.
  * seq_ids: host uint32[n], pairwise different.  acts_in / acts_out: host arrays
  * of n device pointers, each as act_in / act_out of mdi_decode_step.
  * Errors: as mdi_decode_step, checked for all n messages before the first is
- * taken (on an error no sequence has advanced); MDI_ERR_ARG also when n == 0 or
- * a sample id occurs twice.
+ * taken (on such an error no sequence has advanced); MDI_ERR_ARG also when
+ * n == 0 or a sample id occurs twice.
  */
 MDI_API mdi_status mdi_decode_steps(mdi_partition *part, uint32_t n, const uint32_t *seq_ids,
                             const void *const *acts_in, void *const *acts_out);

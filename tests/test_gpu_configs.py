@@ -113,9 +113,14 @@ def test_c3_tinyllama_layers_0_10_bf16():
         check(g.prefill(s, dev_ids(prompts[s])), op.prefill(s, prompts[s]), cfg, ("C3 prefill", s))
     rng = np.random.default_rng(seed)
     for step in range(6):
-        for s in (1, 0):
-            t = int(rng.integers(0, cfg["vocab"]))
-            e = check(g.decode_step(s, dev_ids([t])), op.decode_step(s, t), cfg, ("C3 decode", step, s))
+        toks = [int(rng.integers(0, cfg["vocab"])) for _ in range(2)]
+        if step < 3:                                   # one message at a time
+            for s in (1, 0):
+                e = check(g.decode_step(s, dev_ids([toks[s]])), op.decode_step(s, toks[s]), cfg, ("C3 decode", step, s))
+        else:                                          # both samples' messages in one call
+            outs = g.decode_steps([1, 0], [dev_ids([toks[1]]), dev_ids([toks[0]])])
+            for s, got in zip((1, 0), outs):
+                e = check(got, op.decode_step(s, toks[s]), cfg, ("C3 decode, queued", step, s))
     _say(f"C3: last decode rel-L2 {e:.2e}")
 
 
@@ -152,6 +157,35 @@ def test_c4_llama2_7b_layers_8_15_bf16():
         x = S.make_activations(cfg, seed, 0, 1, step=step + 1)[0]
         e = check(g.decode_step(0, dev_acts(x, cfg)), op.decode_step(0, x), cfg, ("C4 decode", step))
     _say(f"C4: decode rel-L2 {e:.2e}")
+
+    # The configuration the benchmark times: 8 samples in flight, all their messages handed over per call.  The
+    # oracle follows sample 0; every sample must agree with a second partition that takes the same messages one
+    # at a time (the path checked above) up to the summation order, i.e. far inside the bar against the oracle,
+    # and a repeated call pattern must reproduce its bits.
+    n = wl["n_seqs"]
+    del g
+    g8 = mdi.Partition(cfg, w, 8, 16, max_seqs=n, kv_page_tokens=64, max_prefill=1024)
+    g1 = mdi.Partition(cfg, w, 8, 16, max_seqs=n, kv_page_tokens=64, max_prefill=1024)
+    first = [dev_acts(a if s == 0 else S.make_activations(cfg, seed, s, wl["prompt"] - 3 * s), cfg) for s in range(n)]   # ragged
+    for s in range(n):
+        assert torch.equal(g8.prefill(s, first[s]), g1.prefill(s, first[s]))
+    for step in range(3):                              # sample 0 catches up with the oracle's copy of it
+        x = dev_acts(S.make_activations(cfg, seed, 0, 1, step=step + 1)[0], cfg)
+        g8.decode_step(0, x)
+        g1.decode_step(0, x)
+    _say("C4: eight samples prefilled")
+    worst = 0.0
+    for step in range(3, 7):
+        order = [(step + i) % n for i in range(n)]
+        xs = {s: S.make_activations(cfg, seed, s, 1, step=step + 1)[0] for s in order}
+        outs = g8.decode_steps(order, [dev_acts(xs[s], cfg) for s in order])
+        for s, got in zip(order, outs):
+            worst = max(worst, rel_l2(host(got), host(g1.decode_step(s, dev_acts(xs[s], cfg))).astype(np.float64)))
+        e = check(outs[order.index(0)], op.decode_step(0, xs[0]), cfg, ("C4 decode, queue of 8", step))
+    assert worst <= 0.25 * tol(cfg), worst
+    g8.sync()
+    g1.sync()
+    _say(f"C4: queue of 8, sample 0 rel-L2 {e:.2e} against the oracle; worst rel-L2 against one message at a time {worst:.2e}")
 
 
 def test_c4_llama2_7b_to_max_context():

@@ -170,20 +170,23 @@ def test_first_visit_attention_on_matrix_cores(shape, T):
 @pytest.mark.parametrize("name", ["llama_gqa", "llama_group3", "gpt2", "wide_head"])
 def test_queued_messages_taken_together(name, dtype, path):
     """Several samples' later visits handed over in one call (Sec. III-A: messages wait in the input queue;
-    Sec. III-C: several samples in flight) give, bit for bit, what the same visits give one call at a time, and
-    match the oracle; samples have different lengths, cross page boundaries at different steps, and the number
-    of messages is odd as well as even."""
+    Sec. III-C: several samples in flight) match the oracle, agree with the same visits taken one call at a time
+    far inside that bar (only the order of a row's partial sums may differ) and reproduce their own bits when
+    the same calls are made again; samples have different lengths, cross page boundaries at different steps, and
+    the number of messages is odd as well as even."""
     cfg = S.tiny(n_layer=3, dtype=dtype, max_ctx=48, **VARIANTS[name])
     w = scale_matrices(S.make_weights(cfg, 41, exercise=True), 6.0 if dtype == S.DT_F32 else 3.0)
     n_seq = 5
     o, g = pair(cfg, w, 0, 3, embed=True, max_seqs=n_seq, kv_page_tokens=8, decode_path=path)
     g1 = mdi.Partition(cfg, w, 0, 3, has_embed=True, max_seqs=n_seq, kv_page_tokens=8, decode_path=path)
+    g2 = mdi.Partition(cfg, w, 0, 3, has_embed=True, max_seqs=n_seq, kv_page_tokens=8, decode_path=path)
     prompts = S.make_prompts(cfg, 41, n_seq, 11)
     for s in range(n_seq):
         prompts[s] = prompts[s][:3 + 2 * s]
         o.prefill(s, prompts[s])
         g.prefill(s, dev_ids(prompts[s]))
         g1.prefill(s, dev_ids(prompts[s]))
+        g2.prefill(s, dev_ids(prompts[s]))
     rng = np.random.default_rng(9)
     V = cfg["vocab"]
     for step in range(12):
@@ -191,13 +194,16 @@ def test_queued_messages_taken_together(name, dtype, path):
         toks = [int(rng.integers(0, V)) for _ in order]
         ins = [dev_ids([t]) for t in toks]
         outs = g.decode_steps(order, ins)
-        for s, t, x, got in zip(order, toks, ins, outs):
+        again = g2.decode_steps(order, ins)
+        for s, t, x, got, rep in zip(order, toks, ins, outs, again):
             check(got, o.decode_step(s, t), cfg, ("decode", step, s))
-            assert torch.equal(got, g1.decode_step(s, x)), (step, s)
+            assert torch.equal(got, rep), (step, s)
+            assert rel_l2(host(got), host(g1.decode_step(s, x)).astype(np.float64)) <= 0.25 * tol(cfg), (step, s)
     for s in range(n_seq):
-        assert g.seq_len(s) == g1.seq_len(s)
+        assert g.seq_len(s) == g1.seq_len(s) == g2.seq_len(s)
     g.sync()
     g1.sync()
+    g2.sync()
 
 
 def test_queued_messages_error_paths():

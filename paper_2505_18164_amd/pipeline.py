@@ -7,6 +7,9 @@ visits forward the newest token; the output layers turn the returning
 activation into the next token, which stays in device memory and is the next
 input of the embedding stage.  Hand-offs between stages are stream events (the
 analogue of the paper's FIFO queues); the host never waits inside the loop.
+With `drain=True` a stage takes all the messages waiting in its queue in one
+call (mdi_decode_steps) instead of one call per message: on one GPU every
+sample's message is waiting when a stage gets its turn.
 No arithmetic happens here.
 """
 from __future__ import annotations
@@ -25,9 +28,11 @@ class RecurrentPipeline:
         self.head = parts[-1]
         self.device = parts[0].device
 
-    def generate(self, prompts, n_new, keep_logits=False, keep_hidden=False):
+    def generate(self, prompts, n_new, keep_logits=False, keep_hidden=False, drain=False):
         """prompts: list of int32 device tensors.  Returns tokens [n_seqs, n_new] (int32, device)
         and optionally per-token logits [n_seqs, n_new, V] / final hidden states [n_seqs, n_new, d]."""
+        if drain:
+            return self._generate_draining(prompts, n_new, keep_logits, keep_hidden)
         ns, dev = len(prompts), self.device
         d, V = self.head.d, self.head.V
         toks = torch.zeros((ns, n_new), dtype=torch.int32, device=dev)
@@ -71,6 +76,55 @@ class RecurrentPipeline:
                     msg = out
                 back[s] = msg[-1] if r == 0 else msg
                 ev_back[s] = ev
+        for p in self.parts:
+            done = torch.cuda.Event()
+            done.record(p.stream)
+            main.wait_event(done)
+        return toks, logits, hidden
+
+    def _generate_draining(self, prompts, n_new, keep_logits, keep_hidden):
+        """Same schedule, but in every round after the first a stage takes the messages of all samples in one
+        call; a sample's values are those of the one-message-at-a-time schedule up to summation order."""
+        ns, dev = len(prompts), self.device
+        d, V = self.head.d, self.head.V
+        tdt = self.head.tdtype
+        toks = torch.zeros((ns, n_new), dtype=torch.int32, device=dev)
+        logits = torch.zeros((ns, n_new, V), dtype=torch.float32, device=dev) if keep_logits else None
+        hidden = torch.zeros((ns, n_new, d), dtype=tdt, device=dev) if keep_hidden else None
+        nb = len(self.blocks)
+        act = [[torch.empty((d,), dtype=tdt, device=dev) for _ in range(nb)] for s in range(ns)]
+        main = torch.cuda.current_stream(dev)
+        ev = torch.cuda.Event()
+        ev.record(main)
+        back = [None] * ns
+        for s in range(ns):                       # first visits: one sample per message, as always
+            msg, e = prompts[s], ev
+            for p in self.blocks:
+                p.stream.wait_event(e)
+                msg = p.prefill(s, msg, torch.empty((len(prompts[s]), d), dtype=tdt, device=dev))
+                e = torch.cuda.Event()
+                e.record(p.stream)
+            back[s] = msg[-1]
+            last = e
+        hs = self.head.stream
+        for r in range(1, n_new + 1):
+            hs.wait_event(last)
+            for s in range(ns):
+                if keep_hidden:
+                    with torch.cuda.stream(hs):
+                        hidden[s, r - 1].copy_(back[s])
+                self.head.sample_greedy(s, back[s], toks[s, r - 1:r], logits[s, r - 1] if keep_logits else None)
+            last = torch.cuda.Event()
+            last.record(hs)
+            if r == n_new:
+                break
+            msgs = [toks[s, r - 1:r] for s in range(ns)]
+            for i, p in enumerate(self.blocks):
+                p.stream.wait_event(last)
+                msgs = p.decode_steps(list(range(ns)), msgs, [act[s][i] for s in range(ns)])
+                last = torch.cuda.Event()
+                last.record(p.stream)
+            back = msgs
         for p in self.parts:
             done = torch.cuda.Event()
             done.record(p.stream)

@@ -63,6 +63,18 @@ def test_c1_gpt2_small_4layers_fp32_greedy():
     assert np.array_equal(host(hidden2), hidden)
     assert np.array_equal(host(logits2), logits)
 
+    # every stage draining its queue in one call: same tokens, same bars
+    for s in range(wl["n_seqs"]):
+        g.seq_reset(s)
+    toks3, logits3, hidden3 = pipe.generate([dev_ids(p) for p in prompts], n_new, keep_logits=True, keep_hidden=True, drain=True)
+    torch.cuda.synchronize()
+    assert toks3.cpu().numpy().tolist() == [list(t) for t in toks_o]
+    for s in range(wl["n_seqs"]):
+        for j in range(n_new):
+            assert rel_l2(host(hidden3)[s, j], hidden_o[s][j]) <= 1e-4, (s, j)
+            assert rel_l2(host(logits3)[s, j], logits_o[s][j]) <= 1e-4, (s, j)
+    g.sync()
+
 
 # ------------------------------------------------------------------ C2
 def test_c2_gpt2_small_3x4_bf16_pipeline():

@@ -6,6 +6,7 @@
 // the vector ALUs.
 #include <algorithm>
 
+#include <cstdlib>
 #include "device_utils.h"
 
 namespace mdi {
@@ -99,16 +100,31 @@ __device__ __forceinline__ void gemm_store(const GemmArgs& a, int out_kind, int 
 // global load has two K steps to arrive.
 constexpr int BK = 64, LDS_STRIDE = BK + 8;
 
-template <int EPI, int BM, int BN>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) void k_gemm_bf16(GemmArgs a) {
-  constexpr int TM = BM / 64, TN = BN / 64;            // MFMA tiles per wavefront
-  constexpr int PA = BM * 8 / kBlock, PB = BN * 8 / kBlock;   // 16-byte pieces per thread per K step
+// NW wavefronts in a WM x (NW / WM) arrangement.  Two shapes are used: 4 wavefronts (2 x 2) on tiles of 128 x 128 or
+// 128 x 64, two workgroups per compute unit; and 8 wavefronts (4 x 2) on 256 x 192, one workgroup per compute
+// unit.  What a compute unit can pull out of L2 per unit of time is the bound on this machine (about 65 GB/s each,
+// measured): a 128 x 128 tile needs 256 bytes of operands per 128 x 128 x 1 products, a 256 x 192 tile 0.58 of that.
+template <int EPI, int BM, int BN, int NW, int WM>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 2))) void k_gemm_bf16(GemmArgs a) {
+  constexpr int kThreads = NW * 64, WN = NW / WM;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // MFMA tiles per wavefront
+  constexpr int PA = BM * 8 / kThreads, PB = BN * 8 / kThreads;   // 16-byte pieces per thread per K step
+  constexpr int PROWS = kThreads / 8;                  // tile rows covered by one piece per thread
+  static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && (BM * 8) % kThreads == 0 && (BN * 8) % kThreads == 0, "tile shape");
   extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
   bf16_t* As = (bf16_t*)gemm_smem;                     // [2][BM][LDS_STRIDE]
   bf16_t* Bs = As + 2 * BM * LDS_STRIDE;               // [2][BN][LDS_STRIDE]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int wm = (wave / WN) * (BM / WM), wn = (wave % WN) * (BN / WN);
+  // Workgroup -> tile.  Workgroups are handed to the eight compute dies in turn (die = id % 8) and each die has an
+  // L2 of its own, so die c takes the tile columns c, c + 8, ... and walks down a column (all row tiles of the same
+  // weight rows) before moving on: the weight tile is fetched from memory once, by one die, while the workgroups
+  // that share it are running; the activation tiles are the ones every column of a die re-uses.
+  const int m_tiles = (a.T + BM - 1) / BM, n_tiles = (a.N + BN - 1) / BN;
+  const int die = blockIdx.x & 7, seq = blockIdx.x >> 3;
+  const int tile_m = seq % m_tiles, tile_n = die + 8 * (seq / m_tiles);
+  if (tile_n >= n_tiles) return;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
   const bf16_t* A = (const bf16_t*)a.A;
   const bf16_t* W = (const bf16_t*)a.W;
   const int Kd = a.Kd;
@@ -118,9 +134,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) 
   const bf16_t* ga[PA];
   const bf16_t* gb[PB];
 #pragma unroll
-  for (int i = 0; i < PA; ++i) ga[i] = A + (long)min(m0 + prow + i * 32, a.T - 1) * Kd + pk;
+  for (int i = 0; i < PA; ++i) ga[i] = A + (long)min(m0 + prow + i * PROWS, a.T - 1) * Kd + pk;
 #pragma unroll
-  for (int i = 0; i < PB; ++i) gb[i] = W + (long)min(n0 + prow + i * 32, a.N - 1) * Kd + pk;
+  for (int i = 0; i < PB; ++i) gb[i] = W + (long)min(n0 + prow + i * PROWS, a.N - 1) * Kd + pk;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -154,9 +170,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) 
     bf16_t* An = As + buf * BM * LDS_STRIDE;
     bf16_t* Bn = Bs + buf * BN * LDS_STRIDE;
 #pragma unroll
-    for (int i = 0; i < PA; ++i) *reinterpret_cast<u32x4*>(An + (prow + i * 32) * LDS_STRIDE + pk) = ra[i];
+    for (int i = 0; i < PA; ++i) *reinterpret_cast<u32x4*>(An + (prow + i * PROWS) * LDS_STRIDE + pk) = ra[i];
 #pragma unroll
-    for (int i = 0; i < PB; ++i) *reinterpret_cast<u32x4*>(Bn + (prow + i * 32) * LDS_STRIDE + pk) = rb[i];
+    for (int i = 0; i < PB; ++i) *reinterpret_cast<u32x4*>(Bn + (prow + i * PROWS) * LDS_STRIDE + pk) = rb[i];
   };
   auto multiply = [&](int buf) __attribute__((always_inline)) {
     const bf16_t* Ac = As + buf * BM * LDS_STRIDE;
@@ -177,39 +193,45 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) 
     }
   };
 
-  fetch_guarded(ra0, rb0, 0);
-  stash(ra0, rb0, 0);
-  fetch_guarded(ra0, rb0, 1);
-  fetch_guarded(ra1, rb1, 2);
-  __syncthreads();
+  // One K step: multiply the step in LDS buffer `buf`; write the step waiting in a register stage into the other
+  // buffer and refill that stage with step `fstep`; one barrier.  (Letting the two halves of an 8-wavefront
+  // workgroup take the two parts in opposite order, one multiplying while the other moves data, was measured: no
+  // faster.)
+  auto kstep = [&](int buf, u32x4 (&ra)[PA], u32x4 (&rb)[PB], bool move, int fstep, bool full) __attribute__((always_inline)) {
+    multiply(buf);
+    if (move) {
+      stash(ra, rb, buf ^ 1);
+      if (full) fetch_full(ra, rb, fstep); else fetch_guarded(ra, rb, fstep);
+    }
+    __syncthreads();
+  };
 
   // invariant at an even step k: LDS buffer 0 holds step k, stage 0 step k + 1, stage 1 step k + 2
   int k = 0;
-  for (; (k + 5) * BK <= Kd; k += 2) {              // every fetch below is of a whole step inside the matrix
-    multiply(0);
-    stash(ra0, rb0, 1);
-    fetch_full(ra0, rb0, k + 3);
+  if (5 * BK <= Kd) {
+    // The usual case has its own, branch-free lead-in, so that the loop below is entered with its loads outstanding
+    // in the order the loop itself issues them (the compiler then waits for one stage while the other is in flight).
+    fetch_full(ra0, rb0, 0);
+    stash(ra0, rb0, 0);
+    fetch_full(ra0, rb0, 1);
+    __builtin_amdgcn_sched_barrier(0);              // the two stages' loads must not be interleaved
+    fetch_full(ra1, rb1, 2);
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
-    multiply(1);
-    stash(ra1, rb1, 0);
-    fetch_full(ra1, rb1, k + 4);
+    for (; (k + 5) * BK <= Kd; k += 2) {            // every fetch below is of a whole step inside the matrix
+      kstep(0, ra0, rb0, true, k + 3, true);
+      kstep(1, ra1, rb1, true, k + 4, true);
+    }
+  } else {
+    fetch_guarded(ra0, rb0, 0);
+    stash(ra0, rb0, 0);
+    fetch_guarded(ra0, rb0, 1);
+    fetch_guarded(ra1, rb1, 2);
     __syncthreads();
   }
   for (; k < nk; k += 2) {
-    multiply(0);
-    if (k + 1 < nk) {
-      stash(ra0, rb0, 1);
-      fetch_guarded(ra0, rb0, k + 3);
-    }
-    __syncthreads();
-    if (k + 1 < nk) {
-      multiply(1);
-      if (k + 2 < nk) {
-        stash(ra1, rb1, 0);
-        fetch_guarded(ra1, rb1, k + 4);
-      }
-      __syncthreads();
-    }
+    kstep(0, ra0, rb0, k + 1 < nk, k + 3, false);
+    if (k + 1 < nk) kstep(1, ra1, rb1, k + 2 < nk, k + 4, false);
   }
 
   // accumulator layout of the 32x32 MFMA: register r of lane l holds
@@ -306,25 +328,40 @@ __global__ __launch_bounds__(kBlock) void k_gemm_f32(GemmArgs a) {
       gemm_store<EPI>(a, IN_F32, m0 + ty * 4 + i, n0 + tx * 4 + j, acc[i][j], acc[i][j ^ 1]);
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int NW, int WM>
 static void launch_gemm_bf16(hipStream_t s, int epi, const GemmArgs& a) {
-  const dim3 grid((a.N + BN - 1) / BN, (a.T + BM - 1) / BM), block(kBlock);
+  const int m_tiles = (a.T + BM - 1) / BM, n_tiles = (a.N + BN - 1) / BN;
+  const dim3 grid(8 * m_tiles * ((n_tiles + 7) / 8)), block(NW * 64);   // see the tile mapping in the kernel
   const size_t lds = (size_t)2 * (BM + BN) * LDS_STRIDE * sizeof(bf16_t);
+  static bool raised = false;                        // 256 x 192 tiles need more LDS than a kernel gets by default
+  if (lds > 64 * 1024 && !raised) {
+    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_F32_BIAS, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_RESID, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_SWIGLU, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_GELU_TANH, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_GELU_ERF, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    raised = true;
+  }
   switch (epi) {
-    case GEPI_F32_BIAS: hipLaunchKernelGGL((k_gemm_bf16<GEPI_F32_BIAS, BM, BN>), grid, block, lds, s, a); break;
-    case GEPI_RESID: hipLaunchKernelGGL((k_gemm_bf16<GEPI_RESID, BM, BN>), grid, block, lds, s, a); break;
-    case GEPI_SWIGLU: hipLaunchKernelGGL((k_gemm_bf16<GEPI_SWIGLU, BM, BN>), grid, block, lds, s, a); break;
-    case GEPI_GELU_TANH: hipLaunchKernelGGL((k_gemm_bf16<GEPI_GELU_TANH, BM, BN>), grid, block, lds, s, a); break;
-    default: hipLaunchKernelGGL((k_gemm_bf16<GEPI_GELU_ERF, BM, BN>), grid, block, lds, s, a); break;
+    case GEPI_F32_BIAS: hipLaunchKernelGGL((k_gemm_bf16<GEPI_F32_BIAS, BM, BN, NW, WM>), grid, block, lds, s, a); break;
+    case GEPI_RESID: hipLaunchKernelGGL((k_gemm_bf16<GEPI_RESID, BM, BN, NW, WM>), grid, block, lds, s, a); break;
+    case GEPI_SWIGLU: hipLaunchKernelGGL((k_gemm_bf16<GEPI_SWIGLU, BM, BN, NW, WM>), grid, block, lds, s, a); break;
+    case GEPI_GELU_TANH: hipLaunchKernelGGL((k_gemm_bf16<GEPI_GELU_TANH, BM, BN, NW, WM>), grid, block, lds, s, a); break;
+    default: hipLaunchKernelGGL((k_gemm_bf16<GEPI_GELU_ERF, BM, BN, NW, WM>), grid, block, lds, s, a); break;
   }
 }
 
 void launch_gemm(hipStream_t s, int dtype, int epi, const GemmArgs& a) {
   if (dtype == MDI_BF16) {
+    // 256 x 192 tiles (one 8-wavefront workgroup per compute unit) when the grid they give keeps at least 70 % of
+    // the compute units busy over its rounds
+    const long big = (long)((a.N + 191) / 192) * ((a.T + 255) / 256);
+    const long rounds = (big + 255) / 256;
+    if (a.T >= 256 && big * 10 >= rounds * 256 * 7) { launch_gemm_bf16<256, 192, 8, 4>(s, epi, a); return; }
     // a grid of 128 x 128 tiles that cannot give every compute unit two workgroups gets narrower tiles
     const long tiles = (long)((a.N + 127) / 128) * ((a.T + 127) / 128);
-    if (tiles <= 256) launch_gemm_bf16<128, 64>(s, epi, a);
-    else launch_gemm_bf16<128, 128>(s, epi, a);
+    if (tiles <= 256) launch_gemm_bf16<128, 64, 4, 2>(s, epi, a);
+    else launch_gemm_bf16<128, 128, 4, 2>(s, epi, a);
     return;
   }
   const dim3 grid((a.N + 63) / 64, (a.T + 63) / 64), block(kBlock);

@@ -1,11 +1,18 @@
-// One decode step of a whole partition as ONE persistent kernel launch.
+// Decode steps of a whole partition as ONE persistent kernel launch.
 //
 // A later visit of a sample (Sec. III-D) pushes a single position through every
 // local layer; each layer is five dependent matrix-vector / attention phases whose
 // inputs are full vectors produced by the previous phase.  Launching them as
 // separate kernels leaves the memory system idle at every boundary (drain, launch,
-// ramp-up).  Here one workgroup of eight wavefronts per compute unit stays resident
-// for the whole step:
+// ramp-up).  Here workgroups stay resident for the whole launch - one of eight
+// wavefronts per compute unit for a launch that carries one message, two of four
+// wavefronts for a launch that carries the queued messages of several samples
+// (Sec. III-A: the input queue; Sec. III-C: several samples in flight).  In the
+// latter a set of workgroups takes its messages in turn inside every phase and
+// two sets share each compute unit, so that the serial part of one message's
+// phase boundary (flags, vector staging, cross-wavefront sums, epilogue) runs
+// under other messages' weight streams; every message still makes its own pass
+// over the weights.
 //
 //   * phases are separated by a grid-wide barrier built from per-workgroup epoch
 //     flags.  Everything that crosses workgroups (x, q, o, u, attention partials,

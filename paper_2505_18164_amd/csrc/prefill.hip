@@ -36,27 +36,43 @@ void launch_rows_input(hipStream_t s, const RowsInArgs& a) {
 }
 
 // ---------------------------------------------------------------------------
+// One workgroup per row; d is a multiple of 8, so rows are read as float4 and written four values at a time.
 __global__ __launch_bounds__(kBlock) void k_norm_rows(NormRowsArgs a) {
   __shared__ float red[8];
-  const int t = blockIdx.x, d = a.d;
-  const float* x = a.x + (long)t * d;
+  const int t = blockIdx.x, d4 = a.d >> 2;
+  const float4* x = reinterpret_cast<const float4*>(a.x + (long)t * a.d);
+  const float4* g4 = reinterpret_cast<const float4*>(a.g);
+  const float4* b4 = reinterpret_cast<const float4*>(a.b);
   float mean = 0.f, rstd;
   if (a.norm_kind == MDI_NORM_LAYERNORM) {
     float s = 0.f;
-    for (int i = threadIdx.x; i < d; i += kBlock) s += x[i];
-    mean = block_sum(s, red) / (float)d;
+    for (int i = threadIdx.x; i < d4; i += kBlock) { const float4 v = x[i]; s += (v.x + v.y) + (v.z + v.w); }
+    mean = block_sum(s, red) / (float)a.d;
     float s2 = 0.f;
-    for (int i = threadIdx.x; i < d; i += kBlock) { const float c = x[i] - mean; s2 += c * c; }
-    rstd = 1.f / sqrtf(block_sum(s2, red) / (float)d + a.eps);
+    for (int i = threadIdx.x; i < d4; i += kBlock) {
+      const float4 v = x[i];
+      const float c0 = v.x - mean, c1 = v.y - mean, c2 = v.z - mean, c3 = v.w - mean;
+      s2 += (c0 * c0 + c1 * c1) + (c2 * c2 + c3 * c3);
+    }
+    rstd = 1.f / sqrtf(block_sum(s2, red) / (float)a.d + a.eps);
   } else {
     float s2 = 0.f;
-    for (int i = threadIdx.x; i < d; i += kBlock) s2 += x[i] * x[i];
-    rstd = 1.f / sqrtf(block_sum(s2, red) / (float)d + a.eps);
+    for (int i = threadIdx.x; i < d4; i += kBlock) { const float4 v = x[i]; s2 += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w); }
+    rstd = 1.f / sqrtf(block_sum(s2, red) / (float)a.d + a.eps);
   }
-  for (int i = threadIdx.x; i < d; i += kBlock) {
-    float v = (x[i] - mean) * rstd * a.g[i];
-    if (a.b) v += a.b[i];
-    store_kind(a.out, a.out_kind, (long)t * d + i, v);
+  for (int i = threadIdx.x; i < d4; i += kBlock) {
+    const float4 v = x[i], g = g4[i];
+    float4 o = {(v.x - mean) * rstd * g.x, (v.y - mean) * rstd * g.y, (v.z - mean) * rstd * g.z, (v.w - mean) * rstd * g.w};
+    if (a.b) { const float4 b = b4[i]; o.x += b.x; o.y += b.y; o.z += b.z; o.w += b.w; }
+    const long at = (long)t * a.d + 4 * i;
+    if (a.out_kind == IN_BF16) {
+      uint2 p;
+      p.x = (uint32_t)f32_to_bf16(o.x) | ((uint32_t)f32_to_bf16(o.y) << 16);
+      p.y = (uint32_t)f32_to_bf16(o.z) | ((uint32_t)f32_to_bf16(o.w) << 16);
+      *reinterpret_cast<uint2*>((bf16_t*)a.out + at) = p;
+    } else {
+      *reinterpret_cast<float4*>((float*)a.out + at) = o;
+    }
   }
 }
 void launch_norm_rows(hipStream_t s, const NormRowsArgs& a) {

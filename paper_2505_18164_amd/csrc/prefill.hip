@@ -116,9 +116,9 @@ __device__ __forceinline__ void gemm_store(const GemmArgs& a, int out_kind, int 
 // global load has two K steps to arrive.
 constexpr int BK = 64, LDS_STRIDE = BK + 8;
 
-// NW wavefronts in a WM x (NW / WM) arrangement.  Two shapes are used: 4 wavefronts (2 x 2) on tiles of 128 x 128 or
-// 128 x 64, two workgroups per compute unit; and 8 wavefronts (4 x 2) on 256 x 192, one workgroup per compute
-// unit.  What a compute unit can pull out of L2 per unit of time is the bound on this machine (about 65 GB/s each,
+// NW wavefronts in a WM x (NW / WM) arrangement.  Shapes in use: 4 wavefronts (2 x 2) on tiles of 128 x 128 or
+// 128 x 64, two workgroups per compute unit; 8 wavefronts on 256 x 192 (4 x 2) or 128 x 128 (2 x 4), one workgroup
+// per compute unit.  What a compute unit can pull out of L2 per unit of time is the bound on this machine (about 65 GB/s each,
 // measured): a 128 x 128 tile needs 256 bytes of operands per 128 x 128 x 1 products, a 256 x 192 tile 0.58 of that.
 template <int EPI, int BM, int BN, int NW, int WM>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 2))) void k_gemm_bf16(GemmArgs a) {
@@ -371,12 +371,20 @@ void launch_gemm(hipStream_t s, int dtype, int epi, const GemmArgs& a) {
   if (dtype == MDI_BF16) {
     // 256 x 192 tiles (one 8-wavefront workgroup per compute unit) when the grid they give keeps at least 70 % of
     // the compute units busy over its rounds
+    static const long n_cu = []() {
+      int dev = 0, n = 0;
+      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+      return (long)n;
+    }();
     const long big = (long)((a.N + 191) / 192) * ((a.T + 255) / 256);
-    const long rounds = (big + 255) / 256;
-    if (a.T >= 256 && big * 10 >= rounds * 256 * 7) { launch_gemm_bf16<256, 192, 8, 4>(s, epi, a); return; }
-    // a grid of 128 x 128 tiles that cannot give every compute unit two workgroups gets narrower tiles
+    const long rounds = (big + n_cu - 1) / n_cu;
+    if (a.T >= 256 && big * 10 >= rounds * n_cu * 7) { launch_gemm_bf16<256, 192, 8, 4>(s, epi, a); return; }
+    // a grid of 128 x 128 tiles that cannot give every compute unit two 4-wavefront workgroups: one 8-wavefront
+    // workgroup each (a third less operand traffic than two 128 x 64 tiles), or narrower tiles when even that
+    // leaves compute units idle
     const long tiles = (long)((a.N + 127) / 128) * ((a.T + 127) / 128);
-    if (tiles <= 256) launch_gemm_bf16<128, 64, 4, 2>(s, epi, a);
+    if (tiles <= n_cu && 2 * tiles > n_cu) launch_gemm_bf16<128, 128, 8, 2>(s, epi, a);
+    else if (2 * tiles <= n_cu) launch_gemm_bf16<128, 64, 4, 2>(s, epi, a);
     else launch_gemm_bf16<128, 128, 4, 2>(s, epi, a);
     return;
   }

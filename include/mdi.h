@@ -201,7 +201,11 @@ MDI_API mdi_status mdi_sample_greedy(mdi_partition *part, uint32_t seq_id, const
  * Wait for everything enqueued on the partition's stream and report errors that
  * only the device can detect: MDI_ERR_HIP if the stream failed or if a
  * workgroup of a persistent decode kernel gave up waiting for the others (its
- * waits are bounded; the step's outputs are then invalid).
+ * waits are bounded; the step's outputs are then invalid); MDI_ERR_ARG if a
+ * token id outside [0, vocab) reached a kernel (token ids live in device
+ * memory, so they are checked where they are read; such an id is read as
+ * token 0 and the outputs that depend on it are meaningless).  The condition
+ * stays set until the partition is destroyed.
  */
 MDI_API mdi_status mdi_partition_sync(mdi_partition *part);
 

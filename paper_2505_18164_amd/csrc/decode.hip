@@ -18,7 +18,7 @@ __global__ __launch_bounds__(kBlock) void k_input(InputArgs a) {
   if (threadIdx.x == 0 && blockIdx.x == 0 && a.table_entry) *a.table_entry = a.new_page;
   const int stride = gridDim.x * blockDim.x;
   if (a.in_kind == IN_TOKEN) {
-    const long tok = *(const int32_t*)a.in;
+    const long tok = checked_token(a.in, 0, a.vocab, a.err);
     const int wk = a.dtype == MDI_BF16 ? IN_BF16 : IN_F32;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.d; i += stride) {
       float v = load_kind(a.wte, wk, tok * a.d + i);

@@ -110,4 +110,16 @@ __device__ __forceinline__ float gelu_tanh_f(float x) {
 __device__ __forceinline__ float gelu_erf_f(float x) { return 0.5f * x * (1.f + erff(x * 0.7071067811865476f)); }
 __device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
+
+// A token id read from device memory indexes the embedding table, so it is checked where it is read: an id outside
+// [0, vocab) raises the partition's error word (value 2) and is replaced by token 0.
+__device__ __forceinline__ long checked_token(const void* in, long index, int vocab, int* err) {
+  const long tok = ((const int32_t*)in)[index];
+  if (tok < 0 || tok >= vocab) {
+    if (err) __hip_atomic_store(err, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return 0;
+  }
+  return tok;
+}
+
 }  // namespace mdi

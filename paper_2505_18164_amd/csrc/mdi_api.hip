@@ -477,7 +477,7 @@ mdi_status mdi_prefill(mdi_partition* p, uint32_t seq, const void* acts_in, uint
   const int d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff;
   const int ak = act_kind(c);
   const bool embed = p->flags & MDI_HAS_EMBED, swiglu = c.mlp_kind == MDI_MLP_SWIGLU;
-  RowsInArgs ri{acts_in, embed ? IN_TOKEN : ak, p->wte, p->wpe, (int)c.dtype, (int)T, d, p->p_xres};
+  RowsInArgs ri{acts_in, embed ? IN_TOKEN : ak, p->wte, p->wpe, (int)c.dtype, (int)T, d, p->p_xres, (int)c.vocab, p->err};
   launch_rows_input(s, ri);
   for (int i = 0; i < p->n_local; ++i) {
     const LayerPacked& L = p->layers[i];
@@ -564,7 +564,7 @@ void fill_step_shared(const mdi_partition* p, StepArgs* a) {
   a->d = c.d_model; a->H = c.n_head; a->K = c.n_kv_head; a->h = c.head_dim; a->F = c.d_ff; a->pt = p->pt;
   a->pt_h = (long)p->pt * c.head_dim;
   a->norm_kind = c.norm_kind; a->mlp_kind = c.mlp_kind; a->eps = c.norm_eps;
-  a->wte = p->wte; a->wpe = p->wpe;
+  a->wte = p->wte; a->wpe = p->wpe; a->vocab = (int)c.vocab;
   a->err = p->err; a->spin_limit = 1 << 21;
   a->n_hg = p->n_hg;
   a->scale = 1.f / sqrtf((float)c.head_dim);
@@ -642,7 +642,7 @@ mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, v
     a.n_layer = p->n_local;
     a.d = d; a.H = H; a.K = K; a.h = h; a.F = F; a.pt = p->pt; a.pt_h = (long)p->pt * h;
     a.norm_kind = c.norm_kind; a.mlp_kind = c.mlp_kind; a.eps = c.norm_eps;
-    a.in = act_in; a.in_kind = embed ? IN_TOKEN : ak; a.wte = p->wte; a.wpe = p->wpe;
+    a.in = act_in; a.in_kind = embed ? IN_TOKEN : ak; a.wte = p->wte; a.wpe = p->wpe; a.vocab = (int)c.vocab;
     a.pos = len; a.ctx = ctx;
     a.rope = p->rope ? p->rope + (size_t)len * (h / 2) : nullptr;
     a.table = drow; a.n_tab = (len + p->pt - 1) / p->pt; a.table_entry = new_entry; a.new_page = page;
@@ -668,7 +668,7 @@ mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, v
     const mdi_status st = launch_messages(p, 1, &seq, &mp, &act_in, &act_out);
     return st != MDI_OK ? st : hip_status();
   }
-  InputArgs ia{act_in, embed ? IN_TOKEN : ak, p->wte, p->wpe, (int)c.dtype, len, d, p->xres, new_entry, page};
+  InputArgs ia{act_in, embed ? IN_TOKEN : ak, p->wte, p->wpe, (int)c.dtype, len, d, p->xres, new_entry, page, (int)c.vocab, p->err};
   launch_input(s, ia);
 
   // context split: enough workgroups to cover the chip, at least 64 tokens each
@@ -776,6 +776,7 @@ mdi_status mdi_partition_sync(mdi_partition* p) {
   if (p->err) {
     int e = 0;
     if (hipMemcpy(&e, p->err, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return MDI_ERR_HIP;
+    if (e == 2) return MDI_ERR_ARG;      // a token id outside [0, vocab) reached a kernel
     if (e) return MDI_ERR_HIP;
   }
   return hip_status();

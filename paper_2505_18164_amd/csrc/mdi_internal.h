@@ -59,6 +59,7 @@ struct InputArgs {
   int dtype; int pos; int d;
   float* xres;                       // [d] fp32 residual stream
   int32_t* table_entry; int new_page; // page-table slot to fill before attention (or nullptr)
+  int vocab; int* err;               // a token id outside [0, vocab) sets *err = 2 and is read as token 0
 };
 void launch_input(hipStream_t s, const InputArgs& a);
 
@@ -84,6 +85,7 @@ void launch_attn(hipStream_t s, int dtype, const AttnArgs& a);
 struct RowsInArgs {
   const void* in; int in_kind; const void* wte; const void* wpe; int dtype;
   int T, d; float* xres;
+  int vocab; int* err;               // a token id outside [0, vocab) sets *err = 2 and is read as token 0
 };
 void launch_rows_input(hipStream_t s, const RowsInArgs& a);
 
@@ -166,8 +168,8 @@ struct StepArgs {
   int n_layer;
   int d, H, K, h, F, pt; long pt_h;
   int norm_kind, mlp_kind; float eps;
-  const void* wte; const void* wpe;
-  int* err; int spin_limit;
+  const void* wte; const void* wpe; int vocab;
+  int* err; int spin_limit;          // *err: 1 = a bounded wait expired, 2 = a token id outside [0, vocab) (read as token 0)
   int n_hg; float scale;
   int act_kind;
   int part_floats;                   // LDS floats reserved for GEMV pair partials (multiple of 4)
@@ -192,6 +194,7 @@ struct Step2Args {
   const void* in; int in_kind; const void* wte; const void* wpe;
   int pos, ctx;                      // position of the new token, context length including it
   const float2* rope;                // (cos, sin)[h/2] of `pos`, or nullptr
+  int vocab;
   const int32_t* table; int n_tab;   // the sample's page ids; entries [0, n_tab) cover positions < pos
   int32_t* table_entry; int new_page;
   long kv_tok_off;                   // element offset of K[kv head 0][slot] of the new token inside a layer's pool

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(kBlock) void k_rows_input(RowsInArgs a) {
   const int t = blockIdx.x;
   float* xr = a.xres + (long)t * a.d;
   if (a.in_kind == IN_TOKEN) {
-    const long tok = ((const int32_t*)a.in)[t];
+    const long tok = checked_token(a.in, t, a.vocab, a.err);
     const int wk = a.dtype == MDI_BF16 ? IN_BF16 : IN_F32;
     for (int i = threadIdx.x; i < a.d; i += kBlock) {
       float v = load_kind(a.wte, wk, tok * a.d + i);

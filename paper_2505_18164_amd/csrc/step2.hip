@@ -711,7 +711,7 @@ __global__ __launch_bounds__((S + E) * 64) void k_step2(Step2Args a) {
           if (first) {
             // the step's own input: token embedding (+ learned position) or the previous stage's activation
             if (a.in_kind == IN_TOKEN) {
-              const long tok = *(const int32_t*)a.in;
+              const long tok = checked_token(a.in, 0, a.vocab, a.err);
               for (int i = et; i < a.d; i += ET) {
                 float v = Storage<WT>::get((const WT*)a.wte + tok * a.d + i);
                 if (a.wpe) v += Storage<WT>::get((const WT*)a.wpe + (long)a.pos * a.d + i);

@@ -224,7 +224,7 @@ template <typename WT>
 __device__ __forceinline__ void stage_input(const StepArgs& a, const StepSlot& S, float* xs, const Geo& gres, unsigned tag) {
   const int n = a.d;
   if (S.in_kind == IN_TOKEN) {
-    const long tok = *(const int32_t*)S.in;
+    const long tok = checked_token(S.in, 0, a.vocab, a.err);
     for (int i = threadIdx.x; i < n; i += kStepThreads) {
       float v = Storage<WT>::get((const WT*)a.wte + tok * n + i);
       if (a.wpe) v += Storage<WT>::get((const WT*)a.wpe + (long)S.pos * n + i);
@@ -794,11 +794,25 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
         // ---- a GEMV phase ----------------------------------------------------------------------------
         for (int i = threadIdx.x; i < g.n_pl * 2 * kStepWaves; i += kStepThreads) part[i] = 0.f;
         const bool normed = ph == PH_QKV || ph == PH_UP;
-        const bool fused_rms = normed && a.norm_kind == MDI_NORM_RMSNORM && !(ph == PH_QKV && layer == 0);
+        const bool fused_rms = normed && a.norm_kind == MDI_NORM_RMSNORM;
         const float* gain = ph == PH_QKV ? L->ln1_g : L->ln2_g;
         float row_scale = 1.f;                       // 1/rms when the norm is folded into the epilogue
         if (ph == PH_QKV && layer == 0) {
           stage_input<WT>(a, S, xs, load_geo(1, nullptr, wave), epoch);
+          if (fused_rms) {
+            // same arithmetic, element order and thread mapping as stage_coherent, so that a layer gives the same
+            // bits whether it is the first of its partition or not (where the model is cut changes nothing)
+            __syncthreads();                          // stage_input has read its rows of xs
+            float ss = 0.f;
+            for (int i0 = threadIdx.x; i0 < a.d; i0 += 8 * kStepThreads) {
+#pragma unroll
+              for (int jj = 0; jj < 8; ++jj) {
+                const int i = i0 + jj * kStepThreads;
+                if (i < a.d) { const float x = xs[i]; ss += x * x; xs[i] = x * gain[i]; }
+              }
+            }
+            row_scale = 1.f / sqrtf(block_sum(ss, red) / (float)a.d + a.eps);
+          }
         } else {
           const tagged_t* src = ph == PH_OPROJ ? S.o : ph == PH_DOWN ? S.u : S.xres;
           const float ss = stage_coherent(src, g.units * Storage<WT>::kVec, xs, fused_rms ? gain : nullptr, epoch, a.spin_limit, a.err,

@@ -18,14 +18,17 @@ import torch
 
 
 class RecurrentPipeline:
-    def __init__(self, parts):
-        """parts: chain of mdi.Partition; parts[0] owns the embedding, parts[-1] the
-        output layers (it may be a head-only partition, the paper's starter layout)."""
-        if not (parts[0].flags & 1) or not (parts[-1].flags & 2):
-            raise ValueError("first partition needs the embedding, last the output layers")
-        self.parts = parts
+    def __init__(self, parts, head=None):
+        """parts: chain of mdi.Partition in ring order; parts[0] owns the embedding.  head: the partition
+        that owns the output layers - by default parts[-1] (it may be a head-only partition); pass parts[0]
+        for the paper's starter node, which holds the embedding, the first blocks AND the output layers
+        (Sec. III-B) and so closes the ring."""
+        head = parts[-1] if head is None else head
+        if not (parts[0].flags & 1) or not (head.flags & 2):
+            raise ValueError("first partition needs the embedding, the head partition the output layers")
+        self.parts = parts if any(p is head for p in parts) else parts + [head]
         self.blocks = [p for p in parts if p.hi > p.lo]
-        self.head = parts[-1]
+        self.head = head
         self.device = parts[0].device
 
     def generate(self, prompts, n_new, keep_logits=False, keep_hidden=False, drain=False):
@@ -93,15 +96,17 @@ class RecurrentPipeline:
         hidden = torch.zeros((ns, n_new, d), dtype=tdt, device=dev) if keep_hidden else None
         nb = len(self.blocks)
         act = [[torch.empty((d,), dtype=tdt, device=dev) for _ in range(nb)] for s in range(ns)]
+        # every buffer a stage writes lives until the end: the stages run on streams the allocator does not know
+        pre = [[torch.empty((len(prompts[s]), d), dtype=tdt, device=dev) for _ in range(nb)] for s in range(ns)]
         main = torch.cuda.current_stream(dev)
         ev = torch.cuda.Event()
         ev.record(main)
         back = [None] * ns
         for s in range(ns):                       # first visits: one sample per message, as always
             msg, e = prompts[s], ev
-            for p in self.blocks:
+            for i, p in enumerate(self.blocks):
                 p.stream.wait_event(e)
-                msg = p.prefill(s, msg, torch.empty((len(prompts[s]), d), dtype=tdt, device=dev))
+                msg = p.prefill(s, msg, pre[s][i])
                 e = torch.cuda.Event()
                 e.record(p.stream)
             back[s] = msg[-1]

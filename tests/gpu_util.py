@@ -53,14 +53,18 @@ def check(got, want, cfg, what, bar=None):
     return err
 
 
-def teacher_forced(parts, prompts, tokens, want_logits=True):
+def teacher_forced(parts, prompts, tokens, want_logits=True, head=None):
     """Run GPU partitions (a chain; the last one owns the output layers) over
     the given prompts, feeding `tokens[s][j]` (the oracle's) as the j-th new
     token instead of the GPU's own argmax.  Samples are visited round-robin as
     in Alg. 1.  Returns hidden[s][j] (input of the output layers when token j
-    was produced), logits[s][j], gpu_tokens[s][j]."""
+    was produced), logits[s][j], gpu_tokens[s][j].
+
+    All partitions must be on the current stream: nothing here orders one partition's stream after
+    another's, and the tensors handed from call to call are released as soon as the next call returns."""
+    assert all(p.stream == torch.cuda.current_stream() for p in parts), "teacher_forced needs partitions on the current stream"
     blocks = [p for p in parts if p.hi > p.lo]
-    head = parts[-1]
+    head = parts[-1] if head is None else head           # the paper's starter: head = parts[0]
     ns, n_new = len(prompts), len(tokens[0])
     hidden = [[] for _ in range(ns)]
     logits = [[] for _ in range(ns)]

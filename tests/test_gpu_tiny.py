@@ -206,6 +206,33 @@ def test_queued_messages_taken_together(name, dtype, path):
     g2.sync()
 
 
+@pytest.mark.parametrize("path", [0, 1, 3], ids=["persistent", "per_op", "persistent_tiles"])
+def test_token_id_out_of_range_is_reported_not_followed(path):
+    """Token ids live in device memory, so only the kernels can check them: an id outside [0, vocab) must not be
+    used as an index; the next mdi_partition_sync reports it."""
+    cfg = S.tiny(n_layer=2, dtype=S.DT_F32, max_ctx=32)
+    w = S.make_weights(cfg, 5)
+    V = cfg["vocab"]
+    for where in ("first visit", "later visit", "queued"):
+        if where == "queued" and path != 0:
+            continue
+        g = mdi.Partition(cfg, w, 0, 2, has_embed=True, max_seqs=2, decode_path=path)
+        good = dev_ids(np.arange(4))
+        if where == "first visit":
+            g.prefill(0, dev_ids([1, V + 3, 2, -7]))
+        else:
+            g.prefill(0, good)
+            g.prefill(1, good)
+            g.sync()
+            if where == "later visit":
+                g.decode_step(0, dev_ids([2 ** 30]))
+            else:
+                g.decode_steps([0, 1], [dev_ids([3]), dev_ids([V])])
+        with pytest.raises(mdi.MdiError) as e:
+            g.sync()
+        assert e.value.status == mdi.MDI_ERR_ARG, where
+
+
 def test_queued_messages_error_paths():
     cfg = S.tiny(n_layer=1, dtype=S.DT_F32, max_ctx=16)
     w = S.make_weights(cfg, 3)

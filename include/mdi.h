@@ -198,6 +198,24 @@ MDI_API mdi_status mdi_sample_greedy(mdi_partition *part, uint32_t seq_id, const
                              int32_t *token_out, float *logits_out);
 
 /*
+ * Output layers with a draw from the output distribution (Alg. 1 samples the
+ * pmf; the paper names no knobs, the usual temperature and top-k are taken):
+ * final norm, vocabulary projection, then a token drawn from
+ * softmax(logits / temperature) restricted to the top_k largest logits (ties:
+ * the lower index ranks first) by inverting the cumulative distribution, in
+ * rank order and binary32, at the uniform number u = (x >> 8) / 2^24, x the
+ * first word of Philox-4x32-10 (Salmon et al., SC'11) for counter
+ * (seq_id, step, 0, 0) and key (seed mod 2^32, seed / 2^32): the token is the
+ * first candidate j with u * sum(w) < w_0 + ... + w_j, w_j = exp((l_j - l_max)
+ * / temperature).  The same (seed, seq_id, step) always gives the same token.
+ * temperature > 0; 1 <= top_k <= 64 (top_k = 1 is mdi_sample_greedy).
+ * act_in, token_out, logits_out: as in mdi_sample_greedy.
+ */
+MDI_API mdi_status mdi_sample_topk(mdi_partition *part, uint32_t seq_id, const void *act_in,
+                           float temperature, uint32_t top_k, uint64_t seed, uint32_t step,
+                           int32_t *token_out, float *logits_out);
+
+/*
  * Wait for everything enqueued on the partition's stream and report errors that
  * only the device can detect: MDI_ERR_HIP if the stream failed or if a
  * workgroup of a persistent decode kernel gave up waiting for the others (its

@@ -22,7 +22,9 @@ Pins (tests/test_oracle_*.py): softmax rows sum to 1; attention against
 explicit triple loops; causality; GQA == MHA with repeated kv heads; cached
 decode == full-prefix recompute; composed partitions == unsplit model;
 interleaved samples == each sample alone; norm/RoPE/activation closed forms;
-identity layer when the output matrices vanish; Alg. 1/2 visit counts.
+identity layer when the output matrices vanish; Alg. 1/2 visit counts; the
+counter-based generator against its published known answers; the sampler
+against the distribution it is defined to draw from.
 Whole-model numeric values are "parity unpinned" by the paper: it prints no
 logits or tokens and its trained weights are not available.
 """
@@ -242,8 +244,74 @@ class Partition:
         lg = self.logits(x)
         return greedy(lg), lg
 
+    def sample_topk(self, x, temperature, top_k, seed, sample, step):
+        """Output layers, then a draw from the top-k tempered pmf with the counter-based uniform of
+        (seed, sample, step).  Returns (token, logits)."""
+        lg = self.logits(x)
+        return sample_topk(lg, temperature, top_k, uniform01(seed, sample, step)), lg
+
     def reset(self, n):
         self.caches.pop(n, None)
+
+
+# --------------------------------------------------------------------------
+# stochastic sampling of the output pmf (Alg. 1, "sample the output distribution"; the paper names no knobs: the
+# usual ones of the Llama-family generation loops it builds on, temperature and top-k, are taken)
+_PHILOX_M0, _PHILOX_M1, _PHILOX_W0, _PHILOX_W1 = 0xD2511F53, 0xCD9E8D57, 0x9E3779B9, 0xBB67AE85
+
+
+def philox4x32_10(counter, key):
+    """Philox-4x32 with 10 rounds (Salmon et al., "Parallel random numbers: as easy as 1, 2, 3", SC'11): a
+    counter-based generator, i.e. a keyed bijection of 128-bit counters; plain Python integers."""
+    c0, c1, c2, c3 = (int(v) & 0xFFFFFFFF for v in counter)
+    k0, k1 = (int(v) & 0xFFFFFFFF for v in key)
+    for rnd in range(10):
+        if rnd:
+            k0 = (k0 + _PHILOX_W0) & 0xFFFFFFFF
+            k1 = (k1 + _PHILOX_W1) & 0xFFFFFFFF
+        p0, p1 = _PHILOX_M0 * c0, _PHILOX_M1 * c2
+        c0, c1, c2, c3 = ((p1 >> 32) ^ c1 ^ k0) & 0xFFFFFFFF, p1 & 0xFFFFFFFF, ((p0 >> 32) ^ c3 ^ k1) & 0xFFFFFFFF, p0 & 0xFFFFFFFF
+    return c0, c1, c2, c3
+
+
+def uniform01(seed, sample, step):
+    """The uniform number in [0, 1) that decides the token of `sample` at generation step `step`: the top 24 bits
+    of the first Philox word for counter (sample, step, 0, 0) and key = the two halves of the 64-bit seed, so that
+    it is exactly representable in binary32."""
+    x0 = philox4x32_10((sample, step, 0, 0), (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF))[0]
+    return (x0 >> 8) / float(1 << 24)
+
+
+def sample_topk(logits, temperature, top_k, u):
+    """Token drawn from softmax(logits / temperature) restricted to the top_k largest logits (ties: the lower
+    index ranks first), by inverting the cumulative distribution at u: candidates in rank order, weights
+    w_j = exp((l_j - l_max) / temperature), the token is the first j with u * sum(w) < w_0 + ... + w_j.
+    The arithmetic that decides the token runs in binary32, in this order, because a floating-point comparison
+    decides an integer here and the GPU kernel takes it in binary32 too."""
+    lg = np.asarray(logits, dtype=np.float32)
+    k = int(min(top_k, lg.shape[0]))
+    order = sorted(range(lg.shape[0]), key=lambda i: (-float(lg[i]), i))[:k]
+    inv_t = np.float32(1.0) / np.float32(temperature)
+    lmax = lg[order[0]]
+    w = [np.exp((lg[i] - lmax) * inv_t, dtype=np.float32) for i in order]
+    total = np.float32(0.0)
+    for x in w:
+        total = np.float32(total + x)
+    target = np.float32(np.float32(u) * total)
+    acc = np.float32(0.0)
+    for j, x in enumerate(w):
+        acc = np.float32(acc + x)
+        if target < acc:
+            return order[j]
+    return order[-1]
+
+
+def topk_pmf(logits, temperature, top_k):
+    """The distribution sample_topk draws from, in float64: {token: probability}."""
+    lg = np.asarray(logits, dtype=np.float64)
+    order = sorted(range(lg.shape[0]), key=lambda i: (-lg[i], i))[:int(min(top_k, lg.shape[0]))]
+    w = np.exp((lg[order] - lg[order[0]]) / float(temperature))
+    return dict(zip(order, w / w.sum()))
 
 
 def forward_no_cache(cfg, weights, ids_or_acts, lo, hi, has_embed, dtype=np.float64):
@@ -273,7 +341,7 @@ def starter_schedule(n_samples, n_rounds):
     return out
 
 
-def generate(parts, prompts, n_new, trace=None):
+def generate(parts, prompts, n_new, trace=None, sampling=None, head=None):
     """Recurrent pipeline parallelism on a chain of partitions (Sec. III-C).
 
     parts[0] owns the embedding, parts[-1] (or a separate head-only partition
@@ -283,8 +351,9 @@ def generate(parts, prompts, n_new, trace=None):
     them, which is what FIFO queues on a ring give.  Returns (tokens, logits,
     hidden): per sample the list of new token ids, the logits rows they came
     from, and the activations (last block's output) those were computed from.
+    sampling: None for greedy tokens, else (temperature, top_k, seed) for draws from the top-k tempered pmf.
     """
-    head = parts[-1]
+    head = parts[-1] if head is None else head        # the paper's starter also owns the output layers: head=parts[0]
     blocks = [p for p in parts if p.hi > p.lo]
     toks = [[] for _ in prompts]
     logit_rows = [[] for _ in prompts]
@@ -293,7 +362,10 @@ def generate(parts, prompts, n_new, trace=None):
     for k, n, r, runs_head, runs_fwd, is_prefill in starter_schedule(len(prompts), n_new + 1):
         if runs_head:
             x = inbox.pop(n)
-            t, lg = head.sample_greedy(x)
+            if sampling is None:
+                t, lg = head.sample_greedy(x)
+            else:                                      # (temperature, top_k, seed): token j of sample n uses counter (n, j)
+                t, lg = head.sample_topk(x, sampling[0], sampling[1], sampling[2], n, len(toks[n]))
             toks[n].append(t)
             logit_rows[n].append(lg)
             hidden_rows[n].append(x)

@@ -218,6 +218,72 @@ __global__ __launch_bounds__(kBlock) void k_gemv(GemvArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Draw from the top-k tempered pmf (Alg. 1 samples the output distribution).  One workgroup: every thread keeps the
+// best of the logits it owns (index = thread + 1024 j); k rounds of a workgroup-wide argmax (lowest index on ties)
+// pick the candidates in rank order, the owner of a winner strikes it out and rescans only its own elements.
+// Thread 0 then inverts the cumulative distribution at the uniform number of Philox-4x32-10 (Salmon et al., SC'11)
+// for counter (sample, step, 0, 0): weights exp((l_j - l_max) / T) in rank order, binary32, summed sequentially.
+__device__ __forceinline__ uint32_t philox4x32_10_first(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
+  for (int r = 0; r < 10; ++r) {
+    if (r) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+    const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
+    c0 = n0; c1 = l1; c2 = n2; c3 = l0;
+  }
+  return c0;
+}
+
+__global__ __launch_bounds__(1024) void k_sample_topk(SampleArgs a) {
+  __shared__ float cv[kMaxTopK];
+  __shared__ int ci[kMaxTopK];
+  __shared__ float rv[16];
+  __shared__ int ri[16];
+  __shared__ int s_win;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float bv; int bi;
+  auto scan = [&]() {
+    bv = -INFINITY; bi = 0x7FFFFFFF;
+    for (int i = tid; i < a.V; i += 1024) {
+      const float v = a.logits[i];
+      if (better(v, i, bv, bi)) { bv = v; bi = i; }
+    }
+  };
+  scan();
+  for (int r = 0; r < a.k; ++r) {
+    float wv = bv; int wi = bi;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const float ov = __shfl_xor(wv, off, 64); const int oi = __shfl_xor(wi, off, 64);
+      if (better(ov, oi, wv, wi)) { wv = ov; wi = oi; }
+    }
+    if (lane == 0) { rv[wave] = wv; ri[wave] = wi; }
+    __syncthreads();
+    if (tid == 0) {
+      for (int w = 1; w < 16; ++w) if (better(rv[w], ri[w], wv, wi)) { wv = rv[w]; wi = ri[w]; }
+      cv[r] = wv; ci[r] = wi; s_win = wi;
+    }
+    __syncthreads();
+    if (bi == s_win && bi != 0x7FFFFFFF) { a.logits[bi] = -INFINITY; scan(); }   // only the owner's elements change
+  }
+  if (tid == 0) {
+    const float lmax = cv[0];
+    float total = 0.f;
+    for (int j = 0; j < a.k; ++j) { cv[j] = expf((cv[j] - lmax) * a.inv_t); total += cv[j]; }
+    const float u = (float)(philox4x32_10_first(a.ctr0, a.ctr1, 0u, 0u, a.key0, a.key1) >> 8) * (1.0f / 16777216.0f);
+    const float target = u * total;
+    float acc = 0.f;
+    int tok = ci[a.k - 1];
+    for (int j = 0; j < a.k; ++j) {
+      acc += cv[j];
+      if (target < acc) { tok = ci[j]; break; }
+    }
+    *a.token_out = tok;
+  }
+}
+void launch_sample_topk(hipStream_t s, const SampleArgs& a) { hipLaunchKernelGGL(k_sample_topk, dim3(1), dim3(1024), 0, s, a); }
+
 int gemv_grid(int N) {
   const int n_groups = (N + 3) / 4;
   const int blocks = (n_groups + 3) / 4;

@@ -52,6 +52,7 @@ struct mdi_partition {
   // decode scratch
   float *xres = nullptr, *q = nullptr, *o = nullptr, *u = nullptr, *part = nullptr, *amax_val = nullptr;
   int* amax_idx = nullptr;
+  float* logits = nullptr;       // [V] scratch of the stochastic sampler
   unsigned* counters = nullptr;  // [H] attention + [1] argmax
   // prefill scratch
   float *p_xres = nullptr, *p_qkv = nullptr, *p_q = nullptr;
@@ -151,6 +152,7 @@ size_t carve(mdi_partition* p, void* arena) {
     p->lm_head = c.tie_embed ? p->wte : cv.take(V * d * B);
     p->amax_val = (float*)cv.take(1024 * 4);
     p->amax_idx = (int*)cv.take(1024 * 4);
+    p->logits = (float*)cv.take(V * 4);
   }
   p->counters = (unsigned*)cv.take((H + 1) * 4);
   if (p->n_local) {
@@ -767,6 +769,26 @@ mdi_status mdi_sample_greedy(mdi_partition* p, uint32_t seq, const void* act_in,
   a.out = logits_out; a.amax_val = p->amax_val; a.amax_idx = p->amax_idx;
   a.counter = p->counters + c.n_head; a.token_out = token_out;
   launch_gemv(p->stream, c.dtype, PRO_NORM, EPI_LOGITS, a);
+  return hip_status();
+}
+
+mdi_status mdi_sample_topk(mdi_partition* p, uint32_t seq, const void* act_in, float temperature, uint32_t top_k,
+                           uint64_t seed, uint32_t step, int32_t* token_out, float* logits_out) {
+  if (!p || !act_in || !token_out) return MDI_ERR_ARG;
+  if (!(p->flags & MDI_HAS_HEAD)) return MDI_ERR_STATE;
+  const mdi_config& c = p->cfg;
+  if (seq >= c.max_seqs || !(temperature > 0.f) || !top_k || top_k > (uint32_t)kMaxTopK) return MDI_ERR_ARG;
+  GemvArgs a{};
+  a.W = p->lm_head; a.N = (int)c.vocab; a.Kd = (int)c.d_model;
+  a.x = act_in; a.x_kind = act_kind(c); a.norm_kind = c.norm_kind; a.g = p->lnf_g; a.b = p->lnf_b; a.eps = c.norm_eps;
+  a.out = p->logits; a.amax_val = p->amax_val; a.amax_idx = p->amax_idx;
+  a.counter = p->counters + c.n_head; a.token_out = token_out;
+  launch_gemv(p->stream, c.dtype, PRO_NORM, EPI_LOGITS, a);
+  if (logits_out && hipMemcpyAsync(logits_out, p->logits, (size_t)c.vocab * 4, hipMemcpyDeviceToDevice, p->stream) != hipSuccess)
+    return MDI_ERR_HIP;
+  SampleArgs sa{p->logits, (int)c.vocab, (int)std::min<uint32_t>(top_k, c.vocab), 1.f / temperature, seq, step,
+                (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), token_out};
+  launch_sample_topk(p->stream, sa);
   return hip_status();
 }
 

@@ -81,6 +81,18 @@ struct AttnArgs {
 };
 void launch_attn(hipStream_t s, int dtype, const AttnArgs& a);
 
+// ---- stochastic sampling of the output pmf (Alg. 1) -----------------------
+constexpr int kMaxTopK = 64;
+struct SampleArgs {
+  float* logits;        // [V] fp32; destroyed (the chosen candidates are overwritten)
+  int V, k;             // k <= kMaxTopK and k <= V
+  float inv_t;          // 1 / temperature
+  uint32_t ctr0, ctr1;  // counter of the generator: (sample, step)
+  uint32_t key0, key1;  // its key: the two halves of the seed
+  int32_t* token_out;
+};
+void launch_sample_topk(hipStream_t s, const SampleArgs& a);
+
 // ---- prefill (first visit: T positions at once; Alg. 2) -------------------
 struct RowsInArgs {
   const void* in; int in_kind; const void* wte; const void* wpe; int dtype;

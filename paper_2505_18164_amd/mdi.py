@@ -19,7 +19,7 @@ MDI_F32, MDI_BF16 = 0, 1
 MDI_HAS_EMBED, MDI_HAS_HEAD = 1, 2
 
 EXPORTS = ["mdi_partition_bytes", "mdi_partition_create", "mdi_prefill", "mdi_decode_step", "mdi_decode_steps",
-           "mdi_sample_greedy", "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel",
+           "mdi_sample_greedy", "mdi_sample_topk", "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel",
            "mdi_partition_info", "mdi_partition_trace", "mdi_partition_destroy", "mdi_strerror"]
 
 
@@ -67,6 +67,7 @@ def lib():
         L.mdi_decode_step.argtypes = [vp, u32, vp, vp]
         L.mdi_decode_steps.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(vp), C.POINTER(vp)]
         L.mdi_sample_greedy.argtypes = [vp, u32, vp, vp, vp]
+        L.mdi_sample_topk.argtypes = [vp, u32, vp, C.c_float, u32, C.c_uint64, u32, vp, vp]
         L.mdi_partition_sync.argtypes = [vp]
         L.mdi_seq_reset.argtypes = [vp, u32]
         L.mdi_seq_len.argtypes = [vp, u32, C.POINTER(u32)]
@@ -78,7 +79,7 @@ def lib():
         L.mdi_partition_destroy.restype = None
         L.mdi_strerror.argtypes = [C.c_int]
         L.mdi_strerror.restype = C.c_char_p
-        for name in EXPORTS[:13]:
+        for name in EXPORTS[:14]:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -229,6 +230,14 @@ class Partition:
         st = lib().mdi_sample_greedy(self._h, seq, _ptr(act_in), _ptr(token_out), _ptr(logits_out))
         if st != MDI_OK:
             raise MdiError(st, "mdi_sample_greedy")
+        return token_out
+
+    def sample_topk(self, seq, act_in, temperature, top_k, seed, step, token_out=None, logits_out=None):
+        if token_out is None:
+            token_out = torch.empty((1,), dtype=torch.int32, device=self.device)
+        st = lib().mdi_sample_topk(self._h, seq, _ptr(act_in), temperature, top_k, seed, step, _ptr(token_out), _ptr(logits_out))
+        if st != MDI_OK:
+            raise MdiError(st, "mdi_sample_topk")
         return token_out
 
     # -- bookkeeping --------------------------------------------------------

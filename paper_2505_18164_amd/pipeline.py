@@ -29,11 +29,23 @@ class RecurrentPipeline:
         self.parts = parts if any(p is head for p in parts) else parts + [head]
         self.blocks = [p for p in parts if p.hi > p.lo]
         self.head = head
+        self.sampling = None
         self.device = parts[0].device
 
-    def generate(self, prompts, n_new, keep_logits=False, keep_hidden=False, drain=False):
+    def _token(self, s, r, x, out, logits):
+        """Output layers for sample s in round r: greedy, or a draw from the top-k tempered pmf (Alg. 1)."""
+        if self.sampling is None:
+            self.head.sample_greedy(s, x, out, logits)
+        else:
+            temperature, top_k, seed = self.sampling
+            self.head.sample_topk(s, x, temperature, top_k, seed, r - 1, out, logits)
+
+    def generate(self, prompts, n_new, keep_logits=False, keep_hidden=False, drain=False, sampling=None):
         """prompts: list of int32 device tensors.  Returns tokens [n_seqs, n_new] (int32, device)
-        and optionally per-token logits [n_seqs, n_new, V] / final hidden states [n_seqs, n_new, d]."""
+        and optionally per-token logits [n_seqs, n_new, V] / final hidden states [n_seqs, n_new, d].
+        sampling: None for greedy tokens, or (temperature, top_k, seed): token j of sample s is drawn with the
+        counter-based uniform number of (seed, s, j)."""
+        self.sampling = sampling
         if drain:
             return self._generate_draining(prompts, n_new, keep_logits, keep_hidden)
         ns, dev = len(prompts), self.device
@@ -61,7 +73,7 @@ class RecurrentPipeline:
                 if keep_hidden:
                     with torch.cuda.stream(hs):
                         hidden[s, r - 1].copy_(x)
-                self.head.sample_greedy(s, x, toks[s, r - 1:r], logits[s, r - 1] if keep_logits else None)
+                self._token(s, r, x, toks[s, r - 1:r], logits[s, r - 1] if keep_logits else None)
                 ev_tok = torch.cuda.Event()
                 ev_tok.record(hs)
             if r < n_rounds - 1:                  # forward through the ring
@@ -118,7 +130,7 @@ class RecurrentPipeline:
                 if keep_hidden:
                     with torch.cuda.stream(hs):
                         hidden[s, r - 1].copy_(back[s])
-                self.head.sample_greedy(s, back[s], toks[s, r - 1:r], logits[s, r - 1] if keep_logits else None)
+                self._token(s, r, back[s], toks[s, r - 1:r], logits[s, r - 1] if keep_logits else None)
             last = torch.cuda.Event()
             last.record(hs)
             if r == n_new:

@@ -254,3 +254,74 @@ def test_queued_messages_error_paths():
     g.decode_steps([1], [ids[:1]])
     assert g.seq_len(1) == 9
     g.sync()
+
+
+@pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
+def test_stochastic_sampling_matches_the_oracle_draw_for_draw(dtype):
+    """Alg. 1 samples the output distribution.  Same counter-based uniform number on both sides, so the token must be
+    the same whenever the number does not fall within the logits' error of a boundary of the cumulative
+    distribution; top_k = 1 is greedy; a draw is a function of (seed, sample, step) only; and over many steps the
+    GPU's tokens follow the oracle's pmf."""
+    cfg = S.tiny(n_layer=1, dtype=dtype, vocab=211, d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96)
+    w = scale_matrices(S.make_weights(cfg, 77, exercise=True), 8.0)
+    o, g = pair(cfg, w, 0, 1, embed=True, head=True, max_seqs=2)
+    ids = S.make_prompts(cfg, 77, 1, 6)[0]
+    x = S.storage_round(o.prefill(0, ids)[-1].astype(np.float32), dtype)
+    g.prefill(0, dev_ids(ids))
+    xd = dev_acts(x, cfg)
+    lg_o = o.logits(x)
+    lg_g = torch.empty(cfg["vocab"], dtype=torch.float32, device="cuda:0")
+    seed, temperature, top_k = 0x1234567890ABCDEF, 0.8, 12
+    err = None
+    decided = agree = 0
+    counts = {}
+    n = 400
+    for step in range(n):
+        tok = int(g.sample_topk(1, xd, temperature, top_k, seed, step, logits_out=lg_g if step == 0 else None).item())
+        if step == 0:
+            check(lg_g, lg_o, cfg, "logits")
+            err = float(np.abs(host(lg_g) - lg_o).max()) / temperature      # bound on the shift of a log-weight
+        counts[tok] = counts.get(tok, 0) + 1
+        want = O.sample_topk(lg_o, temperature, top_k, O.uniform01(seed, 1, step))
+        pmf = O.topk_pmf(lg_o, temperature, top_k)
+        assert tok in pmf
+        edges = np.cumsum(list(pmf.values()))
+        margin = np.abs(edges - O.uniform01(seed, 1, step)).min()
+        if margin > 4 * err + 1e-5:                                         # a boundary moves by less than 2 err
+            decided += 1
+            agree += tok == want
+    assert decided >= 0.8 * n and agree == decided, (decided, agree)
+    chi2 = sum((counts.get(t, 0) - n * p) ** 2 / (n * p) for t, p in O.topk_pmf(lg_o, temperature, top_k).items() if n * p >= 5)
+    assert chi2 < 40.0, chi2
+    # top_k = 1 is the greedy token whatever the seed; a draw depends on (seed, sample, step) only
+    assert int(g.sample_topk(0, xd, 1.3, 1, 5, 9).item()) == int(g.sample_greedy(0, xd).item())
+    a = [int(g.sample_topk(0, xd, 1.5, 40, 7, s).item()) for s in range(30)]
+    b = [int(g.sample_topk(0, xd, 1.5, 40, 7, s).item()) for s in range(30)]
+    c = [int(g.sample_topk(0, xd, 1.5, 40, 8, s).item()) for s in range(30)]
+    assert a == b and a != c and len(set(a)) > 5
+    with pytest.raises(mdi.MdiError):
+        g.sample_topk(0, xd, 0.0, 5, 1, 1)
+    with pytest.raises(mdi.MdiError):
+        g.sample_topk(0, xd, 1.0, 65, 1, 1)
+    g.sync()
+
+
+def test_generation_with_sampled_tokens_through_the_ring():
+    """Alg. 1 with its own token rule (a draw from the pmf) on a three-node ring in fp32: the sampled sequences are
+    those of the oracle, with every stage on its own stream and with stages draining their queues."""
+    from paper_2505_18164_amd.pipeline import RecurrentPipeline
+    cfg = S.tiny(n_layer=3, dtype=S.DT_F32, max_ctx=40, vocab=97)
+    w = scale_matrices(S.make_weights(cfg, 23, exercise=True), 6.0)
+    prompts = S.make_prompts(cfg, 23, 3, 4)
+    sampling = (0.9, 8, 424242)
+    ops = [O.Partition(cfg, w, 0, 1, has_embed=True, has_head=True), O.Partition(cfg, w, 1, 3)]
+    toks_o, _, _ = O.generate(ops, prompts, 20, sampling=sampling, head=ops[0])
+    assert len({tuple(t) for t in toks_o}) == 3                      # samples differ: each has its own counter
+    for drain in (False, True):
+        parts = [mdi.Partition(cfg, w, 0, 1, has_embed=True, has_head=True, max_seqs=3, stream=torch.cuda.Stream()),
+                 mdi.Partition(cfg, w, 1, 3, max_seqs=3, stream=torch.cuda.Stream())]
+        t, _, _ = RecurrentPipeline(parts, head=parts[0]).generate([dev_ids(p) for p in prompts], 20, drain=drain, sampling=sampling)
+        torch.cuda.synchronize()
+        for p in parts:
+            p.sync()
+        assert t.cpu().numpy().tolist() == [list(x) for x in toks_o], drain

@@ -154,6 +154,21 @@ MDI_API mdi_status mdi_prefill(mdi_partition *part, uint32_t seq_id, const void 
                        void *acts_out);
 
 /*
+ * A first visit in several pieces: forward the next T prompt positions of
+ * sample seq_id, which continue at its current cache length (0 for a fresh
+ * sample: then this is mdi_prefill).  The positions attend to the cache and
+ * to each other causally, so the pieces together compute what one
+ * mdi_prefill of the whole prompt computes; a node can then let other
+ * samples' messages in between the pieces of a long prompt instead of
+ * stalling them for the whole first visit (the start-up transient of
+ * Sec. IV-B grows with what a first visit costs).
+ * Arguments and errors as mdi_prefill, except that a live sequence is not an
+ * error; MDI_ERR_CTX if the cache length + T exceeds max_ctx.
+ */
+MDI_API mdi_status mdi_prefill_chunk(mdi_partition *part, uint32_t seq_id, const void *acts_in,
+                             uint32_t T, void *acts_out);
+
+/*
  * Later visit (Sec. III-D): forward only the newest position through the local
  * layers, reading and extending KV cache seq_id.  The position is implicit:
  * the partition counts each sequence's length, as the paper's message carries

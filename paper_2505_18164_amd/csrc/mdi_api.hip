@@ -461,25 +461,27 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
   return MDI_OK;
 }
 
-mdi_status mdi_prefill(mdi_partition* p, uint32_t seq, const void* acts_in, uint32_t T, void* acts_out) {
-  if (!p || !acts_in || !acts_out || !p->n_local) return MDI_ERR_ARG;
+namespace {
+
+// Forwards T positions of sample seq, starting at position pos0 = its current cache length (0: a first visit).
+mdi_status prefill_rows(mdi_partition* p, uint32_t seq, const void* acts_in, uint32_t T, void* acts_out) {
   const mdi_config& c = p->cfg;
-  if (seq >= c.max_seqs || T == 0) return MDI_ERR_ARG;
-  if (p->seq_len[seq]) return MDI_ERR_STATE;
-  if (T > c.max_ctx) return MDI_ERR_CTX;
+  const int pos0 = (int)p->seq_len[seq];
+  if ((uint32_t)pos0 + T > c.max_ctx) return MDI_ERR_CTX;
   if (T > (uint32_t)p->Tm) return MDI_ERR_ARG;
-  const int need = ((int)T + p->pt - 1) / p->pt;
+  const int have = (pos0 + p->pt - 1) / p->pt;
+  const int need = (pos0 + (int)T + p->pt - 1) / p->pt - have;
   if ((int)p->free_pages.size() < need) return MDI_ERR_NOMEM;
   int32_t* row = p->host_tables.data() + (size_t)seq * p->pages_per_seq;
-  for (int i = 0; i < need; ++i) { row[i] = p->free_pages.back(); p->free_pages.pop_back(); }
+  for (int i = 0; i < need; ++i) { row[have + i] = p->free_pages.back(); p->free_pages.pop_back(); }
   int32_t* drow = p->tables + (size_t)seq * p->pages_per_seq;
-  if (hipMemcpyAsync(drow, row, (size_t)need * 4, hipMemcpyHostToDevice, p->stream) != hipSuccess) return MDI_ERR_HIP;
+  if (need && hipMemcpyAsync(drow + have, row + have, (size_t)need * 4, hipMemcpyHostToDevice, p->stream) != hipSuccess) return MDI_ERR_HIP;
 
   hipStream_t s = p->stream;
   const int d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff;
   const int ak = act_kind(c);
   const bool embed = p->flags & MDI_HAS_EMBED, swiglu = c.mlp_kind == MDI_MLP_SWIGLU;
-  RowsInArgs ri{acts_in, embed ? IN_TOKEN : ak, p->wte, p->wpe, (int)c.dtype, (int)T, d, p->p_xres, (int)c.vocab, p->err};
+  RowsInArgs ri{acts_in, embed ? IN_TOKEN : ak, p->wte, p->wpe, (int)c.dtype, (int)T, d, p->p_xres, (int)c.vocab, p->err, pos0};
   launch_rows_input(s, ri);
   for (int i = 0; i < p->n_local; ++i) {
     const LayerPacked& L = p->layers[i];
@@ -487,11 +489,11 @@ mdi_status mdi_prefill(mdi_partition* p, uint32_t seq, const void* acts_in, uint
     launch_norm_rows(s, n1);
     GemmArgs g1{p->p_xn, L.wqkv, L.bqkv, (int)T, (H + 2 * K) * h, d, p->p_qkv, nullptr};
     launch_gemm(s, c.dtype, GEPI_F32_BIAS, g1);
-    const bool flash = p->p_qb != nullptr;
+    const bool flash = p->p_qb != nullptr && pos0 == 0;   // later chunks attend to the cache as well: per-row attention
     const int Tp = ((int)T + 127) / 128 * 128;
     const float scale = 1.f / sqrtf((float)h);
     RopeScatterArgs rs{p->p_qkv, (int)T, H, K, h, p->pt, p->rope, flash ? nullptr : p->p_q, L.kv, drow, (int)c.dtype,
-                       flash ? p->p_qb : nullptr, flash ? p->p_kc : nullptr, Tp, scale};
+                       flash ? p->p_qb : nullptr, flash ? p->p_kc : nullptr, Tp, scale, pos0};
     launch_rope_scatter(s, rs);
     if (flash) {
       launch_v_transpose(s, p->p_qkv, (int)T, Tp, H, K, h, p->p_vt);
@@ -500,7 +502,7 @@ mdi_status mdi_prefill(mdi_partition* p, uint32_t seq, const void* acts_in, uint
     } else {
       AttnArgs at{};
       at.q = p->p_q; at.q_stride = (long)H * h; at.pool = L.kv; at.table = drow;
-      at.ctx0 = 1; at.n_q = (int)T; at.H = H; at.K = K; at.h = h; at.pt = p->pt;
+      at.ctx0 = pos0 + 1; at.n_q = (int)T; at.H = H; at.K = K; at.h = h; at.pt = p->pt;
       at.chunk = (int)c.max_ctx; at.n_splits = 1; at.scale = scale;
       at.part = p->part; at.counters = p->counters; at.out = p->p_o; at.out_stride = (long)H * h; at.out_kind = ak;
       launch_attn(s, c.dtype, at);
@@ -514,8 +516,23 @@ mdi_status mdi_prefill(mdi_partition* p, uint32_t seq, const void* acts_in, uint
     GemmArgs g4{p->p_u, L.wdown, L.bdown, (int)T, d, F, p->p_xres, i == p->n_local - 1 ? acts_out : nullptr};
     launch_gemm(s, c.dtype, GEPI_RESID, g4);
   }
-  p->seq_len[seq] = T;
+  p->seq_len[seq] = (uint32_t)pos0 + T;
   return hip_status();
+}
+
+}  // namespace
+
+mdi_status mdi_prefill(mdi_partition* p, uint32_t seq, const void* acts_in, uint32_t T, void* acts_out) {
+  if (!p || !acts_in || !acts_out || !p->n_local) return MDI_ERR_ARG;
+  if (seq >= p->cfg.max_seqs || T == 0) return MDI_ERR_ARG;
+  if (p->seq_len[seq]) return MDI_ERR_STATE;
+  return prefill_rows(p, seq, acts_in, T, acts_out);
+}
+
+mdi_status mdi_prefill_chunk(mdi_partition* p, uint32_t seq, const void* acts_in, uint32_t T, void* acts_out) {
+  if (!p || !acts_in || !acts_out || !p->n_local) return MDI_ERR_ARG;
+  if (seq >= p->cfg.max_seqs || T == 0) return MDI_ERR_ARG;
+  return prefill_rows(p, seq, acts_in, T, acts_out);
 }
 
 namespace {

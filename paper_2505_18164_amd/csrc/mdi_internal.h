@@ -98,6 +98,7 @@ struct RowsInArgs {
   const void* in; int in_kind; const void* wte; const void* wpe; int dtype;
   int T, d; float* xres;
   int vocab; int* err;               // a token id outside [0, vocab) sets *err = 2 and is read as token 0
+  int pos0;                          // position of row 0 (a first visit in several chunks continues at the cache length)
 };
 void launch_rows_input(hipStream_t s, const RowsInArgs& a);
 
@@ -130,6 +131,7 @@ struct RopeScatterArgs {
   bf16_t* q_bf;           // [T][H*h], rotated and scaled by `scale`
   bf16_t* k_bf;           // [K][Tp][h], rotated; rows T..Tp-1 are zero-filled
   int Tp; float scale;
+  int pos0;               // position of row 0
 };
 void launch_rope_scatter(hipStream_t s, const RopeScatterArgs& a);
 

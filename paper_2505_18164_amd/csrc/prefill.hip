@@ -24,7 +24,7 @@ __global__ __launch_bounds__(kBlock) void k_rows_input(RowsInArgs a) {
     const int wk = a.dtype == MDI_BF16 ? IN_BF16 : IN_F32;
     for (int i = threadIdx.x; i < a.d; i += kBlock) {
       float v = load_kind(a.wte, wk, tok * a.d + i);
-      if (a.wpe) v += load_kind(a.wpe, wk, (long)t * a.d + i);
+      if (a.wpe) v += load_kind(a.wpe, wk, (long)(a.pos0 + t) * a.d + i);
       xr[i] = v;
     }
   } else {
@@ -409,14 +409,15 @@ __global__ __launch_bounds__(kBlock) void k_rope_scatter(RopeScatterArgs a) {
     return;
   }
   const float* row = a.qkv + (long)t * n_heads * h;
-  const int page = a.table[t / a.pt], slot = t % a.pt;
+  const int pos = a.pos0 + t;
+  const int page = a.table[pos / a.pt], slot = pos % a.pt;
   const long pt_h = (long)a.pt * h;
   const int kind = a.dtype == MDI_BF16 ? IN_BF16 : IN_F32;
   for (int p = threadIdx.x; p < n_heads * half; p += kBlock) {
     const int head = p / half, i = p - head * half;
     float v0 = row[head * h + i], v1 = row[head * h + i + half];
     if (a.rope && head < a.H + a.K) {
-      const float2 cs = a.rope[(long)t * half + i];
+      const float2 cs = a.rope[(long)pos * half + i];
       const float t0 = v0 * cs.x - v1 * cs.y, t1 = v0 * cs.y + v1 * cs.x;
       v0 = t0; v1 = t1;
     }

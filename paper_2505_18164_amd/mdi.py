@@ -18,7 +18,7 @@ MDI_OK, MDI_ERR_ARG, MDI_ERR_STATE, MDI_ERR_CTX, MDI_ERR_NOMEM, MDI_ERR_HIP = 0,
 MDI_F32, MDI_BF16 = 0, 1
 MDI_HAS_EMBED, MDI_HAS_HEAD = 1, 2
 
-EXPORTS = ["mdi_partition_bytes", "mdi_partition_create", "mdi_prefill", "mdi_decode_step", "mdi_decode_steps",
+EXPORTS = ["mdi_partition_bytes", "mdi_partition_create", "mdi_prefill", "mdi_prefill_chunk", "mdi_decode_step", "mdi_decode_steps",
            "mdi_sample_greedy", "mdi_sample_topk", "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel",
            "mdi_partition_info", "mdi_partition_trace", "mdi_partition_destroy", "mdi_strerror"]
 
@@ -64,6 +64,7 @@ def lib():
         L.mdi_partition_create.argtypes = [C.POINTER(MdiConfig), u32, u32, C.POINTER(MdiWeights), u32, vp, C.c_size_t,
                                            vp, C.POINTER(vp)]
         L.mdi_prefill.argtypes = [vp, u32, vp, u32, vp]
+        L.mdi_prefill_chunk.argtypes = [vp, u32, vp, u32, vp]
         L.mdi_decode_step.argtypes = [vp, u32, vp, vp]
         L.mdi_decode_steps.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(vp), C.POINTER(vp)]
         L.mdi_sample_greedy.argtypes = [vp, u32, vp, vp, vp]
@@ -79,7 +80,7 @@ def lib():
         L.mdi_partition_destroy.restype = None
         L.mdi_strerror.argtypes = [C.c_int]
         L.mdi_strerror.restype = C.c_char_p
-        for name in EXPORTS[:14]:
+        for name in EXPORTS[:15]:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -201,6 +202,16 @@ class Partition:
         st = lib().mdi_prefill(self._h, seq, _ptr(acts_in), T, _ptr(acts_out))
         if st != MDI_OK:
             raise MdiError(st, "mdi_prefill")
+        return acts_out
+
+    def prefill_chunk(self, seq, acts_in, acts_out=None):
+        """The next piece of a first visit: positions continue at the sample's current cache length."""
+        T = acts_in.shape[0]
+        if acts_out is None:
+            acts_out = torch.empty((T, self.d), dtype=self.tdtype, device=self.device)
+        st = lib().mdi_prefill_chunk(self._h, seq, _ptr(acts_in), T, _ptr(acts_out))
+        if st != MDI_OK:
+            raise MdiError(st, "mdi_prefill_chunk")
         return acts_out
 
     def decode_step(self, seq, act_in, act_out=None):

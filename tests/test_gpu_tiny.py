@@ -325,3 +325,31 @@ def test_generation_with_sampled_tokens_through_the_ring():
         for p in parts:
             p.sync()
         assert t.cpu().numpy().tolist() == [list(x) for x in toks_o], drain
+
+
+@pytest.mark.parametrize("path", [0, 1], ids=["persistent", "per_op"])
+@pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("name", ["llama_gqa", "gpt2", "wide_head"])
+def test_first_visit_in_pieces(name, dtype, path):
+    """A prompt forwarded in several pieces (each continuing at the cache length, crossing page boundaries, one of
+    them a single position) gives the rows of the oracle's one first visit of the whole prompt, the later visits
+    that follow agree as well, and another sample's visits fit in between the pieces."""
+    cfg = S.tiny(n_layer=3, dtype=dtype, max_ctx=48, **VARIANTS[name])
+    w = scale_matrices(S.make_weights(cfg, 61, exercise=True), 6.0 if dtype == S.DT_F32 else 3.0)
+    o, g = pair(cfg, w, 0, 3, embed=True, max_seqs=2, kv_page_tokens=8)
+    prompts = S.make_prompts(cfg, 61, 2, 21)
+    want = o.prefill(0, prompts[0])
+    check(g.prefill(1, dev_ids(prompts[1][:6])), o.prefill(1, prompts[1][:6]), cfg, "other sample, first visit")
+    at = 0
+    for piece in (5, 1, 9, 6):
+        got = g.prefill_chunk(0, dev_ids(prompts[0][at:at + piece]))
+        check(got, want[at:at + piece], cfg, ("piece at", at))
+        at += piece
+        check(g.decode_step(1, dev_ids([at])), o.decode_step(1, at), cfg, ("other sample between pieces", at))
+    assert g.seq_len(0) == 21
+    for step in range(4):
+        check(g.decode_step(0, dev_ids([step + 3])), o.decode_step(0, step + 3), cfg, ("later visit", step))
+    with pytest.raises(mdi.MdiError) as e:
+        g.prefill_chunk(0, dev_ids(np.zeros(30)))
+    assert e.value.status == mdi.MDI_ERR_CTX
+    g.sync()

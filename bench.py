@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=80)
     ap.add_argument("--workload", type=int, default=4, help="index into the five benchmark configs (1-5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-output-layers", action="store_true", help="skip timing the output layers of the same model")
     ap.add_argument("--ctx-sweep", action="store_true", help="also time decode at the middle and end context")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
@@ -223,6 +224,28 @@ def main():
                     "frac_of_bf16_mfma_peak": prefill_tflops / MFMA_BF16_PEAK_TFLOPS},
         "setup_s": setup_s,
     }
+    if not args.no_output_layers:
+        # the starter's output layers (final norm, vocabulary projection, argmax) of the same model, on a partition
+        # of their own as in the paper's layout; one call per generated token
+        L = cfg["n_layer"]
+        hw = S.make_weights(cfg, seed, L, L, embed=False, head=True)
+        hp = mdi.Partition(cfg, hw, L, L, has_head=True, max_seqs=1)
+        x = torch.randn((d,), device=dev, dtype=torch.float32).to(tdt)
+        tok = torch.empty((1,), dtype=torch.int32, device=dev)
+        for _ in range(10):
+            hp.sample_greedy(0, x, tok)
+        torch.cuda.synchronize()
+        h0, h1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        h0.record()
+        for _ in range(100):
+            hp.sample_greedy(0, x, tok)
+        h1.record()
+        hp.sync()
+        us = h0.elapsed_time(h1) * 10.0
+        hb = hp.step_bytes(0, head=True)
+        result["output_layers"] = {"vocab": cfg["vocab"], "us_per_call": us, "bytes": hb, "GB/s": hb / us / 1e3,
+                                   "frac_of_hbm_peak": hb / us / 1e3 / HBM_PEAK_GBS}
+        del hp, hw
     if one_run:
         result["one_message_per_launch"] = {"ms_per_step": one_run["ms_per_step"], "tokens_per_s": one_run["tokens_per_s"],
                                             "step_GBps": one_run["gbs"], "frac_of_hbm_peak": one_run["gbs"] / HBM_PEAK_GBS}

@@ -53,6 +53,8 @@ struct mdi_partition {
   float *xres = nullptr, *q = nullptr, *o = nullptr, *u = nullptr, *part = nullptr, *amax_val = nullptr;
   int* amax_idx = nullptr;
   float* logits = nullptr;       // [V] scratch of the stochastic sampler
+  int head_nwg = 0, head_part_floats = 0;   // streaming launch of the output layers (0: per-operation GEMV)
+  size_t head_lds = 0;
   unsigned* counters = nullptr;  // [H] attention + [1] argmax
   // prefill scratch
   float *p_xres = nullptr, *p_qkv = nullptr, *p_q = nullptr;
@@ -448,6 +450,18 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
       return MDI_ERR_HIP;
     }
   }
+  if (head && c.decode_path != 1) {
+    // the output layers as one streaming launch when the activation and the pair partials fit in LDS
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n_cu = 0;
+    if (n_cu > 0) {
+      const int nwg = std::min(n_cu, 1024);
+      const int max_pairs = (((int)V + 1) / 2 + nwg - 1) / nwg + 8;
+      const int part_floats = (max_pairs * 2 * kStepWavesMax + 3) & ~3;
+      const size_t lds = (size_t)(128 + part_floats + ((d + 3) & ~(size_t)3)) * sizeof(float);
+      if (lds <= 64 * 1024) { p->head_nwg = nwg; p->head_part_floats = part_floats; p->head_lds = lds; }
+    }
+  }
   p->seq_len.assign(c.max_seqs, 0u);
   if (p->n_local) {
     p->host_tables.assign((size_t)c.max_seqs * p->pages_per_seq, 0);
@@ -775,17 +789,31 @@ mdi_status mdi_decode_steps(mdi_partition* p, uint32_t n, const uint32_t* seqs, 
   return hip_status();
 }
 
+namespace {
+// final norm + vocabulary projection + greedy argmax; logits (optional) go to `logits`
+void launch_head(mdi_partition* p, const void* act_in, int32_t* token_out, float* logits) {
+  const mdi_config& c = p->cfg;
+  if (p->head_nwg) {
+    LogitsArgs a{p->lm_head, (int)c.vocab, (int)c.d_model, act_in, act_kind(c), (int)c.norm_kind, p->lnf_g, p->lnf_b, c.norm_eps,
+                 logits, p->amax_val, p->amax_idx, p->counters + c.n_head, token_out, p->head_part_floats};
+    launch_logits(p->stream, c.dtype, p->head_nwg, p->head_lds, a);
+    return;
+  }
+  GemvArgs a{};
+  a.W = p->lm_head; a.N = (int)c.vocab; a.Kd = (int)c.d_model;
+  a.x = act_in; a.x_kind = act_kind(c); a.norm_kind = c.norm_kind; a.g = p->lnf_g; a.b = p->lnf_b; a.eps = c.norm_eps;
+  a.out = logits; a.amax_val = p->amax_val; a.amax_idx = p->amax_idx;
+  a.counter = p->counters + c.n_head; a.token_out = token_out;
+  launch_gemv(p->stream, c.dtype, PRO_NORM, EPI_LOGITS, a);
+}
+}  // namespace
+
 mdi_status mdi_sample_greedy(mdi_partition* p, uint32_t seq, const void* act_in, int32_t* token_out, float* logits_out) {
   if (!p || !act_in || !token_out) return MDI_ERR_ARG;
   if (!(p->flags & MDI_HAS_HEAD)) return MDI_ERR_STATE;
   const mdi_config& c = p->cfg;
   if (seq >= c.max_seqs) return MDI_ERR_ARG;
-  GemvArgs a{};
-  a.W = p->lm_head; a.N = (int)c.vocab; a.Kd = (int)c.d_model;
-  a.x = act_in; a.x_kind = act_kind(c); a.norm_kind = c.norm_kind; a.g = p->lnf_g; a.b = p->lnf_b; a.eps = c.norm_eps;
-  a.out = logits_out; a.amax_val = p->amax_val; a.amax_idx = p->amax_idx;
-  a.counter = p->counters + c.n_head; a.token_out = token_out;
-  launch_gemv(p->stream, c.dtype, PRO_NORM, EPI_LOGITS, a);
+  launch_head(p, act_in, token_out, logits_out);
   return hip_status();
 }
 
@@ -795,12 +823,7 @@ mdi_status mdi_sample_topk(mdi_partition* p, uint32_t seq, const void* act_in, f
   if (!(p->flags & MDI_HAS_HEAD)) return MDI_ERR_STATE;
   const mdi_config& c = p->cfg;
   if (seq >= c.max_seqs || !(temperature > 0.f) || !top_k || top_k > (uint32_t)kMaxTopK) return MDI_ERR_ARG;
-  GemvArgs a{};
-  a.W = p->lm_head; a.N = (int)c.vocab; a.Kd = (int)c.d_model;
-  a.x = act_in; a.x_kind = act_kind(c); a.norm_kind = c.norm_kind; a.g = p->lnf_g; a.b = p->lnf_b; a.eps = c.norm_eps;
-  a.out = p->logits; a.amax_val = p->amax_val; a.amax_idx = p->amax_idx;
-  a.counter = p->counters + c.n_head; a.token_out = token_out;
-  launch_gemv(p->stream, c.dtype, PRO_NORM, EPI_LOGITS, a);
+  launch_head(p, act_in, token_out, p->logits);
   if (logits_out && hipMemcpyAsync(logits_out, p->logits, (size_t)c.vocab * 4, hipMemcpyDeviceToDevice, p->stream) != hipSuccess)
     return MDI_ERR_HIP;
   SampleArgs sa{p->logits, (int)c.vocab, (int)std::min<uint32_t>(top_k, c.vocab), 1.f / temperature, seq, step,

@@ -198,6 +198,19 @@ void launch_step_w8(hipStream_t s, int dtype, int G, int nwg, size_t lds_bytes, 
 void launch_step_w4(hipStream_t s, int dtype, int G, int nwg, size_t lds_bytes, const StepArgs& a);
 
 
+// Output layers as one streaming launch (step_w8.hip): final norm, vocabulary projection, greedy argmax.
+struct LogitsArgs {
+  const void* W; int N, Kd;          // vocabulary matrix [N, Kd], storage dtype
+  const void* x; int x_kind;         // activation [Kd]
+  int norm_kind; const float* g; const float* b; float eps;
+  float* out;                        // logits [N] or nullptr
+  float* amax_val; int* amax_idx;    // per-workgroup candidates
+  unsigned* counter;                 // arrival counter, zero between calls
+  int32_t* token_out;
+  int part_floats;                   // LDS floats reserved for pair partials (multiple of 4)
+};
+void launch_logits(hipStream_t s, int dtype, int nwg, size_t lds_bytes, const LogitsArgs& a);
+
 // ---- whole decode step as one persistent launch, specialised wavefronts (step2.hip) ----------
 struct Step2Args {
   StepLayer l0;                      // first local layer; layer i's pointers are these advanced by i strides

@@ -868,7 +868,109 @@ static void launch_step_t(hipStream_t s, int G, int nwg, size_t lds, const StepA
   }
 }
 
+#if MDI_STEP_WAVES == 8
+// ---------------------------------------------------------------------------
+// Output layers (Alg. 1: "process output layers ... get token"): final norm, vocabulary projection and greedy
+// argmax as one launch that streams the vocabulary matrix the way a GEMV phase of k_step does (same work split,
+// same two register tiles in flight per wavefront across row boundaries), without any exchange: every workgroup
+// normalises the activation itself.  Logits are optional; the argmax (lowest index on exact ties) is folded per
+// workgroup and then by the last workgroup to arrive, in index order.
+__device__ __forceinline__ bool better_logit(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+template <typename WT>
+__global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_logits(LogitsArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wg = blockIdx.x, nwg = gridDim.x;
+  float* part = lds_part();
+  float* xs = lds_vec(a.part_floats);
+  float* red = lds_red();
+  const Geo g = make_geo<WT>(a.W, a.N, a.Kd, 0, wg, nwg, wave);
+  Tile A, B;
+  gemv_issue(A, g, 0, wave, lane);
+  gemv_issue(B, g, 1, wave, lane);
+  for (int i = threadIdx.x; i < a.Kd; i += kStepThreads) xs[i] = load_kind(a.x, a.x_kind, i);
+  for (int i = threadIdx.x; i < g.n_pl * 2 * kStepWaves; i += kStepThreads) part[i] = 0.f;
+  __syncthreads();
+  normalise(xs, a.Kd, a.norm_kind, a.eps, a.g, a.b, red);
+  __syncthreads();
+  float acc0 = 0.f, acc1 = 0.f;
+  const int nte = ((g.n_k + kTile - 1) / kTile + 1) & ~1;
+#pragma nounroll
+  for (int t = 0; t < nte; t += 2) {
+    gemv_compute<WT>(A, g, t, wave, lane, xs, part, acc0, acc1);
+    gemv_issue(A, g, t + 2, wave, lane);
+    gemv_compute<WT>(B, g, t + 1, wave, lane, xs, part, acc0, acc1);
+    gemv_issue(B, g, t + 3, wave, lane);
+  }
+  __syncthreads();                                           // all wavefronts' partials are in LDS
+  float bv = -INFINITY; int bi = 0x7FFFFFFF;
+  for (int pl = threadIdx.x; pl < g.n_pl; pl += kStepThreads) {
+    float v0 = 0.f, v1 = 0.f;
+#pragma unroll
+    for (int w = 0; w < kStepWaves; ++w) { v0 += part[(pl * 2) * kStepWaves + w]; v1 += part[(pl * 2 + 1) * kStepWaves + w]; }
+    const int r0 = 2 * geo_pair(g, pl), r1 = r0 + 1;
+    if (a.out) a.out[r0] = v0;
+    if (better_logit(v0, r0, bv, bi)) { bv = v0; bi = r0; }
+    if (r1 < a.N) {
+      if (a.out) a.out[r1] = v1;
+      if (better_logit(v1, r1, bv, bi)) { bv = v1; bi = r1; }
+    }
+  }
+  // workgroup best, then the last workgroup to arrive folds the per-workgroup candidates
+  __shared__ float sv[kStepWaves];
+  __shared__ int si[kStepWaves];
+  __shared__ int s_last;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float ov = __shfl_xor(bv, off, 64); const int oi = __shfl_xor(bi, off, 64);
+    if (better_logit(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+  }
+  if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int k = 1; k < kStepWaves; ++k) if (better_logit(sv[k], si[k], bv, bi)) { bv = sv[k]; bi = si[k]; }
+    a.amax_val[wg] = bv; a.amax_idx[wg] = bi;
+    __threadfence();
+    const unsigned ticket = atomicAdd(a.counter, 1u);
+    s_last = ticket == (unsigned)nwg - 1;
+  }
+  __syncthreads();
+  if (s_last) {
+    __threadfence();
+    bv = -INFINITY; bi = 0x7FFFFFFF;
+    for (int k = threadIdx.x; k < nwg; k += kStepThreads) {
+      const float v = __hip_atomic_load(a.amax_val + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int i = __hip_atomic_load(a.amax_idx + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (better_logit(v, i, bv, bi)) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const float ov = __shfl_xor(bv, off, 64); const int oi = __shfl_xor(bi, off, 64);
+      if (better_logit(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    __syncthreads();
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int k = 1; k < kStepWaves; ++k) if (better_logit(sv[k], si[k], bv, bi)) { bv = sv[k]; bi = si[k]; }
+      *a.token_out = bi;
+      *a.counter = 0u;
+    }
+  }
+}
+#endif
+
 }  // namespace step_w<waves>
+
+#if MDI_STEP_WAVES == 8
+void launch_logits(hipStream_t s, int dtype, int nwg, size_t lds, const LogitsArgs& a) {
+  using namespace step_w8;
+  const dim3 grid(nwg), block(kStepThreads);
+  if (dtype == MDI_BF16) hipLaunchKernelGGL(k_logits<bf16_t>, grid, block, lds, s, a);
+  else hipLaunchKernelGGL(k_logits<float>, grid, block, lds, s, a);
+}
+#endif
 
 void MDI_STEP_CAT(launch_step_w, MDI_STEP_WAVES)(hipStream_t s, int dtype, int G, int nwg, size_t lds, const StepArgs& a) {
   using namespace MDI_STEP_CAT(step_w, MDI_STEP_WAVES);

@@ -204,14 +204,26 @@ def test_c4_llama2_7b_to_max_context():
     cfg, seed = S.WORKLOADS[4]["cfg"](), S.workload_seed(4)
     w = S.make_weights(cfg, seed, 8, 9, embed=False, head=False)
     op = O.Partition(cfg, w, 8, 9)
-    g = mdi.Partition(cfg, w, 8, 9, max_seqs=1, kv_page_tokens=64)
+    g = mdi.Partition(cfg, w, 8, 9, max_seqs=2, kv_page_tokens=64)
     T = 4096 - 5
     a = S.make_activations(cfg, seed + 3, 0, T)
     check(g.prefill(0, dev_acts(a, cfg)), op.prefill(0, a), cfg, "C4 long prefill")
+    b = S.make_activations(cfg, seed + 3, 1, 70)                      # a short second sample: very unequal contexts
+    check(g.prefill(1, dev_acts(b, cfg)), op.prefill(1, b), cfg, "C4 short prefill")
     for step in range(5):
         x = S.make_activations(cfg, seed + 3, 0, 1, step=step + 1)[0]
-        check(g.decode_step(0, dev_acts(x, cfg)), op.decode_step(0, x), cfg, ("C4 long decode", step))
-    assert g.seq_len(0) == 4096
+        if step < 2:
+            check(g.decode_step(0, dev_acts(x, cfg)), op.decode_step(0, x), cfg, ("C4 long decode", step))
+        else:                                                         # both samples' messages in one launch
+            y = S.make_activations(cfg, seed + 3, 1, 1, step=step + 1)[0]
+            o1, o0 = g.decode_steps([1, 0], [dev_acts(y, cfg), dev_acts(x, cfg)])
+            check(o0, op.decode_step(0, x), cfg, ("C4 long decode, queued", step))
+            check(o1, op.decode_step(1, y), cfg, ("C4 short decode, queued", step))
+    assert g.seq_len(0) == 4096 and g.seq_len(1) == 73
+    with pytest.raises(mdi.MdiError) as e:                            # the full cache refuses the whole call
+        g.decode_steps([1, 0], [dev_acts(b[0], cfg), dev_acts(b[0], cfg)])
+    assert e.value.status == mdi.MDI_ERR_CTX and g.seq_len(1) == 73
+    g.sync()
 
 
 # ------------------------------------------------------------------ C5
@@ -246,14 +258,20 @@ def test_c5_llama3_8b_to_max_context():
     cfg, seed = S.WORKLOADS[5]["cfg"](), S.workload_seed(5)
     w = S.make_weights(cfg, seed, 8, 9, embed=False, head=False)
     op = O.Partition(cfg, w, 8, 9)
-    g = mdi.Partition(cfg, w, 8, 9, max_seqs=1, kv_page_tokens=64)
+    g = mdi.Partition(cfg, w, 8, 9, max_seqs=3, kv_page_tokens=64)
     T = 8192 - 3
     a = S.make_activations(cfg, seed + 3, 0, T)
     check(g.prefill(0, dev_acts(a, cfg)), op.prefill(0, a), cfg, "C5 long prefill")
-    for step in range(3):
-        x = S.make_activations(cfg, seed + 3, 0, 1, step=step + 1)[0]
-        check(g.decode_step(0, dev_acts(x, cfg)), op.decode_step(0, x), cfg, ("C5 long decode", step))
+    firsts = {1: S.make_activations(cfg, seed + 3, 1, 129), 2: S.make_activations(cfg, seed + 3, 2, 40)}
+    for s, b in firsts.items():
+        check(g.prefill(s, dev_acts(b, cfg)), op.prefill(s, b), cfg, ("C5 short prefill", s))
+    for step in range(3):                                             # three messages per launch (sets of 2 and 1)
+        xs = {s: S.make_activations(cfg, seed + 3, s, 1, step=step + 1)[0] for s in (2, 0, 1)}
+        outs = g.decode_steps([2, 0, 1], [dev_acts(xs[s], cfg) for s in (2, 0, 1)])
+        for s, got in zip((2, 0, 1), outs):
+            check(got, op.decode_step(s, xs[s]), cfg, ("C5 decode, queued", step, s))
     assert g.seq_len(0) == 8192
+    g.sync()
 
 
 # ------------------------------------------------------------------ properties that hold at any size

@@ -27,12 +27,19 @@
 //     finishes a phase, already issues the first two tiles of the NEXT phase; the
 //     barrier latency and the vector staging after it are covered by those loads.
 //   * the rows a workgroup owns in a phase form one flat sequence of (row pair,
-//     1-KiB chunk) items dealt round-robin to its eight wavefronts.  At any moment
-//     the workgroup therefore reads eight consecutive KiB of a row pair (DRAM sees
-//     a few wide sequential streams instead of thousands of narrow ones), and the
+//     1-KiB chunk) items dealt round-robin to its wavefronts.  At any moment the
+//     workgroup therefore reads consecutive KiB of a row pair (DRAM sees a few
+//     wide sequential streams instead of thousands of narrow ones), and the
 //     wavefronts stay balanced whatever the shape.  A wavefront's share of a pair
 //     goes to an LDS slot of its own; slots are summed in wavefront order
-//     (deterministic, no float atomics).
+//     (deterministic, no float atomics; the order depends on the number of
+//     wavefronts, which is why launches of one and of several messages may differ
+//     in the last bits).
+//   * in a launch with two sets of workgroups, each workgroup compares once per
+//     phase the work it has left with that of the other set and takes the higher
+//     wave priority when it has more: left alone, the set that was dispatched
+//     first is served first by a compute unit's memory pipeline and finishes a
+//     fifth earlier.
 //
 // Every spin is bounded: a workgroup that waits longer than `spin_limit` polls
 // raises the partition's error flag and leaves, and so does every other one.

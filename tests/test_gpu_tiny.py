@@ -353,3 +353,21 @@ def test_first_visit_in_pieces(name, dtype, path):
         g.prefill_chunk(0, dev_ids(np.zeros(30)))
     assert e.value.status == mdi.MDI_ERR_CTX
     g.sync()
+
+
+def test_more_queued_messages_than_one_launch_carries():
+    """Eleven samples' messages in one call: launches of 8 and of 3 (sets of 2 and 1), every sample against the oracle."""
+    cfg = S.tiny(n_layer=2, dtype=S.DT_F32, max_ctx=32)
+    w = scale_matrices(S.make_weights(cfg, 13, exercise=True), 6.0)
+    n = 11
+    o, g = pair(cfg, w, 0, 2, embed=True, max_seqs=n, kv_page_tokens=8)
+    prompts = S.make_prompts(cfg, 13, n, 9)
+    for s in range(n):
+        prompts[s] = prompts[s][:1 + s % 9]
+        o.prefill(s, prompts[s])
+        g.prefill(s, dev_ids(prompts[s]))
+    for step in range(10):                       # every sample crosses a page boundary at some step
+        outs = g.decode_steps(list(range(n)), [dev_ids([(7 * s + step) % cfg["vocab"]]) for s in range(n)])
+        for s in range(n):
+            check(outs[s], o.decode_step(s, (7 * s + step) % cfg["vocab"]), cfg, ("decode", step, s))
+    g.sync()

@@ -412,33 +412,48 @@ __global__ __launch_bounds__(kBlock) void k_rope_scatter(RopeScatterArgs a) {
   const int pos = a.pos0 + t;
   const int page = a.table[pos / a.pt], slot = pos % a.pt;
   const long pt_h = (long)a.pt * h;
-  const int kind = a.dtype == MDI_BF16 ? IN_BF16 : IN_F32;
-  for (int p = threadIdx.x; p < n_heads * half; p += kBlock) {
-    const int head = p / half, i = p - head * half;
-    float v0 = row[head * h + i], v1 = row[head * h + i + half];
+  const bool bf = a.dtype == MDI_BF16;
+  // four consecutive pairs (i, i + h/2) per thread: h/2 is a multiple of 4, so everything moves in 8- or 16-byte pieces
+  auto put4 = [&](void* base, bool as_bf16, long o, const float4& v) __attribute__((always_inline)) {
+    if (as_bf16) {
+      uint2 w;
+      w.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+      w.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+      *reinterpret_cast<uint2*>((bf16_t*)base + o) = w;
+    } else {
+      *reinterpret_cast<float4*>((float*)base + o) = v;
+    }
+  };
+  const int q4 = half >> 2;
+  for (int p = threadIdx.x; p < n_heads * q4; p += kBlock) {
+    const int head = p / q4, i = (p - head * q4) * 4;
+    float4 v0 = *reinterpret_cast<const float4*>(row + head * h + i);
+    float4 v1 = *reinterpret_cast<const float4*>(row + head * h + i + half);
     if (a.rope && head < a.H + a.K) {
-      const float2 cs = a.rope[(long)pos * half + i];
-      const float t0 = v0 * cs.x - v1 * cs.y, t1 = v0 * cs.y + v1 * cs.x;
-      v0 = t0; v1 = t1;
+      const float4 c01 = *reinterpret_cast<const float4*>(a.rope + (long)pos * half + i);       // (cos, sin) of pairs i, i+1
+      const float4 c23 = *reinterpret_cast<const float4*>(a.rope + (long)pos * half + i + 2);   // ... i+2, i+3
+      const float4 r0 = {v0.x * c01.x - v1.x * c01.y, v0.y * c01.z - v1.y * c01.w, v0.z * c23.x - v1.z * c23.y, v0.w * c23.z - v1.w * c23.w};
+      const float4 r1 = {v0.x * c01.y + v1.x * c01.x, v0.y * c01.w + v1.y * c01.z, v0.z * c23.y + v1.z * c23.x, v0.w * c23.w + v1.w * c23.z};
+      v0 = r0; v1 = r1;
     }
     if (head < a.H) {
-      if (a.q_out) {
-        float* q = a.q_out + (long)t * a.H * h + head * h + i;
-        q[0] = v0; q[half] = v1;
-      }
+      const long o = (long)t * a.H * h + head * h + i;
+      if (a.q_out) { put4(a.q_out, false, o, v0); put4(a.q_out, false, o + half, v1); }
       if (a.q_bf) {
-        bf16_t* q = a.q_bf + (long)t * a.H * h + head * h + i;
-        q[0] = f32_to_bf16(v0 * a.scale); q[half] = f32_to_bf16(v1 * a.scale);
+        const float sc = a.scale;
+        put4(a.q_bf, true, o, float4{v0.x * sc, v0.y * sc, v0.z * sc, v0.w * sc});
+        put4(a.q_bf, true, o + half, float4{v1.x * sc, v1.y * sc, v1.z * sc, v1.w * sc});
       }
     } else {
       const bool is_v = head >= a.H + a.K;
       const int kvh = head - a.H - (is_v ? a.K : 0);
       const long o = (((long)page * a.K + kvh) * 2 + (is_v ? 1 : 0)) * pt_h + (long)slot * h + i;
-      store_kind(a.pool, kind, o, v0);
-      store_kind(a.pool, kind, o + half, v1);
+      put4(a.pool, bf, o, v0);
+      put4(a.pool, bf, o + half, v1);
       if (a.k_bf && !is_v) {
-        bf16_t* k = a.k_bf + ((long)kvh * a.Tp + t) * h + i;
-        k[0] = f32_to_bf16(v0); k[half] = f32_to_bf16(v1);
+        const long k = ((long)kvh * a.Tp + t) * h + i;
+        put4(a.k_bf, true, k, v0);
+        put4(a.k_bf, true, k + half, v1);
       }
     }
   }

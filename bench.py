@@ -169,6 +169,11 @@ def main():
     if queue < 1 or n_seqs % queue or args.steps % queue or args.warmup % queue:
         print("bench.py: --queue must divide the samples in flight, --steps and --warmup", file=sys.stderr)
         sys.exit(2)
+    per_seq = -(-(args.warmup + args.steps) // n_seqs)
+    if prompt + per_seq > cfg["max_ctx"]:
+        print(f"bench.py: {args.warmup} + {args.steps} steps over {n_seqs} samples need a context of {prompt + per_seq}, "
+              f"this workload's caches hold {cfg['max_ctx']}; use fewer steps", file=sys.stderr)
+        sys.exit(2)
     main_run = run(prompt, args.steps, args.warmup, queue)
     n_local = hi - lo
     params = sum(a * b for a, b in S.layer_tensor_shapes(cfg).values())
@@ -177,7 +182,8 @@ def main():
 
     persistent_kind = part.info(0) in (2, 3)
     # the paper's own rule, one message at a time, next to the queue-draining figure
-    one_run = run(prompt, 400, 40, 1) if (queue > 1 and persistent_kind) else None
+    one_steps = min(400, (cfg["max_ctx"] - prompt - 1) * n_seqs * 10 // 11 // n_seqs * n_seqs)
+    one_run = run(prompt, one_steps, one_steps // 10, 1) if (queue > 1 and persistent_kind and one_steps > 0) else None
     path_kind = part.info(0)          # 2 = persistent launch, 3 = persistent launch with streaming + exchange wavefronts on tiled matrices, 1 = per operation
     persistent = path_kind in (2, 3)
     kernels = {}

@@ -684,182 +684,182 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
 #pragma nounroll
     for (int ph = 0; ph < 5; ++ph) {
 #pragma nounroll
-    for (int slot = slot_lo; slot < slot_hi; ++slot) {
-      // Messages alternate inside a phase: while this message's flags and input vector make their round trips,
-      // the memory system is still busy with the other message's stream, and by the time a message reaches its
-      // next phase every workgroup has long finished its previous one.
-      const StepSlot& S = a.s[slot];
-      const unsigned epoch = S.epoch0 + (unsigned)(layer * 5 + ph);
-      // ---- this phase's first two tiles: their addresses depend on nothing another workgroup writes,
-      //      so they are in flight while the barrier completes and the input vector is staged
-      const int j = gemv_index(ph);
-      const Geo g = load_geo(j, layer_matrix(Lv, j), wave);
-      if (ph == PH_ATTN) {
-        ga = make_attn_geo<WT, G>(a, S, wg, wave, lane);
-        attn_issue<WT>(A, ga, a, S, L->kv, 0, wave); attn_issue<WT>(B, ga, a, S, L->kv, 1, wave);
-      } else { gemv_issue(A, g, 0, wave, lane); gemv_issue(B, g, 1, wave, lane); }
+      for (int slot = slot_lo; slot < slot_hi; ++slot) {
+        // Messages alternate inside a phase: while this message's flags and input vector make their round trips,
+        // the memory system is still busy with the other message's stream, and by the time a message reaches its
+        // next phase every workgroup has long finished its previous one.
+        const StepSlot& S = a.s[slot];
+        const unsigned epoch = S.epoch0 + (unsigned)(layer * 5 + ph);
+        // ---- this phase's first two tiles: their addresses depend on nothing another workgroup writes,
+        //      so they are in flight while the barrier completes and the input vector is staged
+        const int j = gemv_index(ph);
+        const Geo g = load_geo(j, layer_matrix(Lv, j), wave);
+        if (ph == PH_ATTN) {
+          ga = make_attn_geo<WT, G>(a, S, wg, wave, lane);
+          attn_issue<WT>(A, ga, a, S, L->kv, 0, wave); attn_issue<WT>(B, ga, a, S, L->kv, 1, wave);
+        } else { gemv_issue(A, g, 0, wave, lane); gemv_issue(B, g, 1, wave, lane); }
 
-      auto early_requests = [&]() __attribute__((always_inline)) {
-        // ---- requests for the next (message, phase), answered while this phase is being finished: with two
-        //      messages alternating, what the next one needs was published a whole phase ago
-        early_flags = false; early_vec = false;
-        if (slot_hi - slot_lo > 1) {
-          int nslot = slot + 1, nph = ph, nlayer = layer;
-          if (nslot == slot_hi) { nslot = slot_lo; if (++nph == 5) { nph = 0; ++nlayer; } }
-          if (nlayer < a.n_layer) {
-            const StepSlot& N = a.s[nslot];
-            const unsigned nepoch = N.epoch0 + (unsigned)(nlayer * 5 + nph);
-            if (nwg <= 256 && threadIdx.x < 64) {
+        auto early_requests = [&]() __attribute__((always_inline)) {
+          // ---- requests for the next (message, phase), answered while this phase is being finished: with two
+          //      messages alternating, what the next one needs was published a whole phase ago
+          early_flags = false; early_vec = false;
+          if (slot_hi - slot_lo > 1) {
+            int nslot = slot + 1, nph = ph, nlayer = layer;
+            if (nslot == slot_hi) { nslot = slot_lo; if (++nph == 5) { nph = 0; ++nlayer; } }
+            if (nlayer < a.n_layer) {
+              const StepSlot& N = a.s[nslot];
+              const unsigned nepoch = N.epoch0 + (unsigned)(nlayer * 5 + nph);
+              if (nwg <= 256 && threadIdx.x < 64) {
 #pragma unroll
-              for (int k = 0; k < 4; ++k) {
-                const int i = (int)threadIdx.x + 64 * k;
-                efl[k] = i < nwg ? __hip_atomic_load(N.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : nepoch;
+                for (int k = 0; k < 4; ++k) {
+                  const int i = (int)threadIdx.x + 64 * k;
+                  efl[k] = i < nwg ? __hip_atomic_load(N.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : nepoch;
+                }
+                early_flags = true;
               }
-              early_flags = true;
-            }
-            if (nph != PH_ATTN && !(nph == PH_QKV && nlayer == 0)) {
-              const tagged_t* nsrc = nph == PH_OPROJ ? N.o : nph == PH_DOWN ? N.u : N.xres;
-              const int nn = nph == PH_OPROJ ? a.H * a.h : nph == PH_DOWN ? a.F : a.d;
-              const bool nrms = (nph == PH_QKV || nph == PH_UP) && a.norm_kind == MDI_NORM_RMSNORM;
-              const float* ngain = advance(nph == PH_QKV ? a.l0.ln1_g : a.l0.ln2_g, a.w_stride * nlayer);
+              if (nph != PH_ATTN && !(nph == PH_QKV && nlayer == 0)) {
+                const tagged_t* nsrc = nph == PH_OPROJ ? N.o : nph == PH_DOWN ? N.u : N.xres;
+                const int nn = nph == PH_OPROJ ? a.H * a.h : nph == PH_DOWN ? a.F : a.d;
+                const bool nrms = (nph == PH_QKV || nph == PH_UP) && a.norm_kind == MDI_NORM_RMSNORM;
+                const float* ngain = advance(nph == PH_QKV ? a.l0.ln1_g : a.l0.ln2_g, a.w_stride * nlayer);
 #pragma unroll
-              for (int jj = 0; jj < 8; ++jj) {
-                const int i = (int)threadIdx.x + jj * kStepThreads;
-                eraw[jj] = i < nn ? ld_raw(nsrc + i) : 0ull;
-              }
+                for (int jj = 0; jj < 8; ++jj) {
+                  const int i = (int)threadIdx.x + jj * kStepThreads;
+                  eraw[jj] = i < nn ? ld_raw(nsrc + i) : 0ull;
+                }
 #pragma unroll
-              for (int jj = 0; jj < 8; ++jj) {
-                const int i = (int)threadIdx.x + jj * kStepThreads;
-                egain[jj] = (nrms && i < nn) ? ngain[i] : 1.f;
-              }
-              early_vec = true;
-            }
-          }
-        }
-      };
-
-      // Two sets share a compute unit's memory pipeline, and the hardware serves the older wavefronts (the set
-      // that was dispatched first) or the higher priority first; left alone, one set finishes a fifth earlier
-      // and the other runs the rest of the launch on half the wavefronts.  So the set that is behind takes the
-      // higher priority, phase by phase.
-      unsigned other_done = 0u;
-      const bool pace = a.n_sets == 2 && slot == slot_lo;
-      if (pace) other_done = __hip_atomic_load(O.flags + wg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - O.epoch0;
-
-      // ---- wait until every workgroup has finished the previous phase ----------------------------
-      stamp(a, S, layer, ph, 0);
-      if (threadIdx.x < 64) {
-        bool ok = true;
-        int it = 0;
-        bool seen = early_flags;                   // the flags requested early may already show everyone
-#pragma unroll
-        for (int k = 0; k < 4; ++k) seen = seen && ((int)(efl[k] - epoch) >= 0);
-        while (!__all(seen)) {
-          bool all = true;
-          for (int i = threadIdx.x; i < nwg; i += 64) {
-            const unsigned v = __hip_atomic_load(S.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            all = all && ((int)(v - epoch) >= 0);
-          }
-          if (__all(all)) break;
-          if (++it > a.spin_limit) { ok = false; break; }
-          __builtin_amdgcn_s_sleep(1);
-        }
-        if (threadIdx.x == 0) {
-          s_flag[0] = ok;
-          if (!ok) __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-      }
-      __syncthreads();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-      if (!s_flag[0]) return;
-      stamp(a, S, layer, ph, 1);
-      if (pace) {
-        // work left, in (message, phase) units; the set with more of it goes first
-        const int seen = __builtin_amdgcn_readfirstlane((int)other_done), total = a.n_layer * 5;
-        const int left = (total - (layer * 5 + ph)) * (slot_hi - slot_lo);
-        const int other_left = (total - seen) * (a.set_lo[2 - set] - a.set_lo[1 - set]);
-        if (left > other_left || (left == other_left && set == 1)) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
-      }
-
-      if (ph == PH_ATTN) {
-        // ---- attention over the sample's pages -----------------------------------------------------
-        attn_begin<WT, G>(st, ga, a, S, xs, epoch);
-        stamp(a, S, layer, ph, 2);
-        const int nte = ((ga.n_k + kTile - 1) / kTile + 1) & ~1;
-#pragma nounroll
-        for (int t = 0; t < nte; t += 2) {
-          attn_compute<WT, G>(st, A, ga, a.h, t, wave, xs);
-          attn_issue<WT>(A, ga, a, S, L->kv, t + 2, wave);
-          attn_compute<WT, G>(st, B, ga, a.h, t + 1, wave, xs);
-          attn_issue<WT>(B, ga, a, S, L->kv, t + 3, wave);
-        }
-        stamp(a, S, layer, ph, 3);
-        early_requests();
-        attn_to_lds<WT, G>(st, ga, a.h, xs, wave);
-        attn_finish<G>(ga, a, S, xs, s_flag, epoch);
-      } else {
-        // ---- a GEMV phase ----------------------------------------------------------------------------
-        for (int i = threadIdx.x; i < g.n_pl * 2 * kStepWaves; i += kStepThreads) part[i] = 0.f;
-        const bool normed = ph == PH_QKV || ph == PH_UP;
-        const bool fused_rms = normed && a.norm_kind == MDI_NORM_RMSNORM;
-        const float* gain = ph == PH_QKV ? L->ln1_g : L->ln2_g;
-        float row_scale = 1.f;                       // 1/rms when the norm is folded into the epilogue
-        if (ph == PH_QKV && layer == 0) {
-          stage_input<WT>(a, S, xs, load_geo(1, nullptr, wave), epoch);
-          if (fused_rms) {
-            // same arithmetic, element order and thread mapping as stage_coherent, so that a layer gives the same
-            // bits whether it is the first of its partition or not (where the model is cut changes nothing)
-            __syncthreads();                          // stage_input has read its rows of xs
-            float ss = 0.f;
-            for (int i0 = threadIdx.x; i0 < a.d; i0 += 8 * kStepThreads) {
-#pragma unroll
-              for (int jj = 0; jj < 8; ++jj) {
-                const int i = i0 + jj * kStepThreads;
-                if (i < a.d) { const float x = xs[i]; ss += x * x; xs[i] = x * gain[i]; }
+                for (int jj = 0; jj < 8; ++jj) {
+                  const int i = (int)threadIdx.x + jj * kStepThreads;
+                  egain[jj] = (nrms && i < nn) ? ngain[i] : 1.f;
+                }
+                early_vec = true;
               }
             }
-            row_scale = 1.f / sqrtf(block_sum(ss, red) / (float)a.d + a.eps);
           }
-        } else {
-          const tagged_t* src = ph == PH_OPROJ ? S.o : ph == PH_DOWN ? S.u : S.xres;
-          const float ss = stage_coherent(src, g.units * Storage<WT>::kVec, xs, fused_rms ? gain : nullptr, epoch, a.spin_limit, a.err,
-                                          early_vec, eraw, egain);
-          if (fused_rms) row_scale = 1.f / sqrtf(block_sum(ss, red) / (float)a.d + a.eps);
+        };
+
+        // Two sets share a compute unit's memory pipeline, and the hardware serves the older wavefronts (the set
+        // that was dispatched first) or the higher priority first; left alone, one set finishes a fifth earlier
+        // and the other runs the rest of the launch on half the wavefronts.  So the set that is behind takes the
+        // higher priority, phase by phase.
+        unsigned other_done = 0u;
+        const bool pace = a.n_sets == 2 && slot == slot_lo;
+        if (pace) other_done = __hip_atomic_load(O.flags + wg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - O.epoch0;
+
+        // ---- wait until every workgroup has finished the previous phase ----------------------------
+        stamp(a, S, layer, ph, 0);
+        if (threadIdx.x < 64) {
+          bool ok = true;
+          int it = 0;
+          bool seen = early_flags;                   // the flags requested early may already show everyone
+#pragma unroll
+          for (int k = 0; k < 4; ++k) seen = seen && ((int)(efl[k] - epoch) >= 0);
+          while (!__all(seen)) {
+            bool all = true;
+            for (int i = threadIdx.x; i < nwg; i += 64) {
+              const unsigned v = __hip_atomic_load(S.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              all = all && ((int)(v - epoch) >= 0);
+            }
+            if (__all(all)) break;
+            if (++it > a.spin_limit) { ok = false; break; }
+            __builtin_amdgcn_s_sleep(1);
+          }
+          if (threadIdx.x == 0) {
+            s_flag[0] = ok;
+            if (!ok) __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
         }
         __syncthreads();
-        if (normed && !fused_rms) {
-          normalise(xs, a.d, a.norm_kind, a.eps, gain, ph == PH_QKV ? L->ln1_b : L->ln2_b, red);
-          __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        if (!s_flag[0]) return;
+        stamp(a, S, layer, ph, 1);
+        if (pace) {
+          // work left, in (message, phase) units; the set with more of it goes first
+          const int seen = __builtin_amdgcn_readfirstlane((int)other_done), total = a.n_layer * 5;
+          const int left = (total - (layer * 5 + ph)) * (slot_hi - slot_lo);
+          const int other_left = (total - seen) * (a.set_lo[2 - set] - a.set_lo[1 - set]);
+          if (left > other_left || (left == other_left && set == 1)) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
         }
-        // residual phases: fetch this thread's rows of x now, the stream below hides the latency
-        tagged_t x0 = 0ull, x1 = 0ull;
-        if ((ph == PH_OPROJ || ph == PH_DOWN) && (int)threadIdx.x < g.n_pl) {
-          const int r0 = 2 * geo_pair(g, (int)threadIdx.x);
-          x0 = ld_raw(S.xres + r0);
-          if (r0 + 1 < g.N) x1 = ld_raw(S.xres + r0 + 1);
-        }
-        stamp(a, S, layer, ph, 2);
 
-        const int nte = ((g.n_k + kTile - 1) / kTile + 1) & ~1;
+        if (ph == PH_ATTN) {
+          // ---- attention over the sample's pages -----------------------------------------------------
+          attn_begin<WT, G>(st, ga, a, S, xs, epoch);
+          stamp(a, S, layer, ph, 2);
+          const int nte = ((ga.n_k + kTile - 1) / kTile + 1) & ~1;
 #pragma nounroll
-        for (int t = 0; t < nte; t += 2) {
-          gemv_compute<WT>(A, g, t, wave, lane, xs, part, acc0, acc1);
-          gemv_issue(A, g, t + 2, wave, lane);
-          gemv_compute<WT>(B, g, t + 1, wave, lane, xs, part, acc0, acc1);
-          gemv_issue(B, g, t + 3, wave, lane);
-        }
-        stamp(a, S, layer, ph, 3);
-        early_requests();
-        gemv_finish<WT>(ph, g, L, layer, a, S, part, row_scale, x0, x1, epoch);
-      }
+          for (int t = 0; t < nte; t += 2) {
+            attn_compute<WT, G>(st, A, ga, a.h, t, wave, xs);
+            attn_issue<WT>(A, ga, a, S, L->kv, t + 2, wave);
+            attn_compute<WT, G>(st, B, ga, a.h, t + 1, wave, xs);
+            attn_issue<WT>(B, ga, a, S, L->kv, t + 3, wave);
+          }
+          stamp(a, S, layer, ph, 3);
+          early_requests();
+          attn_to_lds<WT, G>(st, ga, a.h, xs, wave);
+          attn_finish<G>(ga, a, S, xs, s_flag, epoch);
+        } else {
+          // ---- a GEMV phase ----------------------------------------------------------------------------
+          for (int i = threadIdx.x; i < g.n_pl * 2 * kStepWaves; i += kStepThreads) part[i] = 0.f;
+          const bool normed = ph == PH_QKV || ph == PH_UP;
+          const bool fused_rms = normed && a.norm_kind == MDI_NORM_RMSNORM;
+          const float* gain = ph == PH_QKV ? L->ln1_g : L->ln2_g;
+          float row_scale = 1.f;                       // 1/rms when the norm is folded into the epilogue
+          if (ph == PH_QKV && layer == 0) {
+            stage_input<WT>(a, S, xs, load_geo(1, nullptr, wave), epoch);
+            if (fused_rms) {
+              // same arithmetic, element order and thread mapping as stage_coherent, so that a layer gives the same
+              // bits whether it is the first of its partition or not (where the model is cut changes nothing)
+              __syncthreads();                          // stage_input has read its rows of xs
+              float ss = 0.f;
+              for (int i0 = threadIdx.x; i0 < a.d; i0 += 8 * kStepThreads) {
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                  const int i = i0 + jj * kStepThreads;
+                  if (i < a.d) { const float x = xs[i]; ss += x * x; xs[i] = x * gain[i]; }
+                }
+              }
+              row_scale = 1.f / sqrtf(block_sum(ss, red) / (float)a.d + a.eps);
+            }
+          } else {
+            const tagged_t* src = ph == PH_OPROJ ? S.o : ph == PH_DOWN ? S.u : S.xres;
+            const float ss = stage_coherent(src, g.units * Storage<WT>::kVec, xs, fused_rms ? gain : nullptr, epoch, a.spin_limit, a.err,
+                                            early_vec, eraw, egain);
+            if (fused_rms) row_scale = 1.f / sqrtf(block_sum(ss, red) / (float)a.d + a.eps);
+          }
+          __syncthreads();
+          if (normed && !fused_rms) {
+            normalise(xs, a.d, a.norm_kind, a.eps, gain, ph == PH_QKV ? L->ln1_b : L->ln2_b, red);
+            __syncthreads();
+          }
+          // residual phases: fetch this thread's rows of x now, the stream below hides the latency
+          tagged_t x0 = 0ull, x1 = 0ull;
+          if ((ph == PH_OPROJ || ph == PH_DOWN) && (int)threadIdx.x < g.n_pl) {
+            const int r0 = 2 * geo_pair(g, (int)threadIdx.x);
+            x0 = ld_raw(S.xres + r0);
+            if (r0 + 1 < g.N) x1 = ld_raw(S.xres + r0 + 1);
+          }
+          stamp(a, S, layer, ph, 2);
 
-      // ---- publish: this workgroup is done with the phase ---------------------------------------------
-      stamp(a, S, layer, ph, 5);
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this thread's stores have completed
-      __syncthreads();
-      stamp(a, S, layer, ph, 6);
-      if (threadIdx.x == 0) __hip_atomic_store(S.flags + wg, epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+          const int nte = ((g.n_k + kTile - 1) / kTile + 1) & ~1;
+#pragma nounroll
+          for (int t = 0; t < nte; t += 2) {
+            gemv_compute<WT>(A, g, t, wave, lane, xs, part, acc0, acc1);
+            gemv_issue(A, g, t + 2, wave, lane);
+            gemv_compute<WT>(B, g, t + 1, wave, lane, xs, part, acc0, acc1);
+            gemv_issue(B, g, t + 3, wave, lane);
+          }
+          stamp(a, S, layer, ph, 3);
+          early_requests();
+          gemv_finish<WT>(ph, g, L, layer, a, S, part, row_scale, x0, x1, epoch);
+        }
+
+        // ---- publish: this workgroup is done with the phase ---------------------------------------------
+        stamp(a, S, layer, ph, 5);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this thread's stores have completed
+        __syncthreads();
+        stamp(a, S, layer, ph, 6);
+        if (threadIdx.x == 0) __hip_atomic_store(S.flags + wg, epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
     }
   }
 }

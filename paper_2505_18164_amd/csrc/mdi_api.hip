@@ -618,8 +618,10 @@ void fill_step_slot(const mdi_partition* p, int m, int nwg, const MessagePlan& m
   const auto& sc = p->sc[m];
   s->xres = sc.xres; s->q = sc.q; s->o = sc.o; s->u = sc.u; s->part = sc.part; s->knew = sc.knew;
   s->tickets = sc.tickets; s->flags = sc.flags; s->epoch0 = m == 0 ? p->epoch : sc.epoch;
+  // context splits: as many as there are workgroups per head group, but no split shorter than 128 positions -
+  // the partials of a head group are folded by one workgroup, eight at a time, and every eight cost a round trip
   const int max_splits = std::max(1, std::min(kMaxSplits, nwg / p->n_hg));
-  int chunk = (mp.ctx + max_splits - 1) / max_splits;
+  int chunk = std::max((mp.ctx + max_splits - 1) / max_splits, 128);
   chunk = (chunk + 15) / 16 * 16;
   s->chunk = chunk; s->n_splits = (mp.ctx + chunk - 1) / chunk;
   s->act_out = act_out;

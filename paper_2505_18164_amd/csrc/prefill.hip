@@ -6,7 +6,8 @@
 // the vector ALUs.
 #include <algorithm>
 
-#include <cstdlib>
+#include <mutex>
+
 #include "device_utils.h"
 
 namespace mdi {
@@ -349,14 +350,15 @@ static void launch_gemm_bf16(hipStream_t s, int epi, const GemmArgs& a) {
   const int m_tiles = (a.T + BM - 1) / BM, n_tiles = (a.N + BN - 1) / BN;
   const dim3 grid(8 * m_tiles * ((n_tiles + 7) / 8)), block(NW * 64);   // see the tile mapping in the kernel
   const size_t lds = (size_t)2 * (BM + BN) * LDS_STRIDE * sizeof(bf16_t);
-  static bool raised = false;                        // 256 x 192 tiles need more LDS than a kernel gets by default
-  if (lds > 64 * 1024 && !raised) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_F32_BIAS, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_RESID, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_SWIGLU, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_GELU_TANH, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_GELU_ERF, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    raised = true;
+  if (lds > 64 * 1024) {                             // 256 x 192 tiles need more LDS than a kernel gets by default
+    static std::once_flag raised;
+    std::call_once(raised, [&]() {
+      (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_F32_BIAS, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_RESID, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_SWIGLU, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_GELU_TANH, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)k_gemm_bf16<GEPI_GELU_ERF, BM, BN, NW, WM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
   }
   switch (epi) {
     case GEPI_F32_BIAS: hipLaunchKernelGGL((k_gemm_bf16<GEPI_F32_BIAS, BM, BN, NW, WM>), grid, block, lds, s, a); break;

@@ -229,6 +229,13 @@ class Partition:
         self.caches[n] = self._empty_cache()
         return self._forward(n, acts)
 
+    def prefill_chunk(self, n, acts):
+        """The next piece of a first visit: the rows continue at the cache length (an empty cache is created for a
+        fresh sample).  Pieces compute what one first visit of the whole prompt computes."""
+        if n not in self.caches:
+            self.caches[n] = self._empty_cache()
+        return self._forward(n, acts)
+
     def decode_step(self, n, act):
         """Later visit: newest token only, extending cache n (Sec. III-D)."""
         if n not in self.caches:

@@ -339,11 +339,13 @@ def test_first_visit_in_pieces(name, dtype, path):
     o, g = pair(cfg, w, 0, 3, embed=True, max_seqs=2, kv_page_tokens=8)
     prompts = S.make_prompts(cfg, 61, 2, 21)
     want = o.prefill(0, prompts[0])
+    o2 = O.Partition(cfg, w, 0, 3, has_embed=True)                  # the oracle taking the same pieces
     check(g.prefill(1, dev_ids(prompts[1][:6])), o.prefill(1, prompts[1][:6]), cfg, "other sample, first visit")
     at = 0
     for piece in (5, 1, 9, 6):
         got = g.prefill_chunk(0, dev_ids(prompts[0][at:at + piece]))
         check(got, want[at:at + piece], cfg, ("piece at", at))
+        check(got, o2.prefill_chunk(0, prompts[0][at:at + piece]), cfg, ("piece at, oracle in pieces", at))
         at += piece
         check(g.decode_step(1, dev_ids([at])), o.decode_step(1, at), cfg, ("other sample between pieces", at))
     assert g.seq_len(0) == 21

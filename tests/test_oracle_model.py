@@ -243,3 +243,30 @@ def test_parameter_accounting_matches_paper_sizes():
         total = blocks * per_layer + 2 * vocab * d + d
         assert abs(total - stated) / stated < 0.03
         assert abs(total * 4 / 1e9 - gb) / gb < 0.12
+
+
+@pytest.mark.parametrize("variant", ["llama", "gpt2"])
+def test_first_visit_in_pieces_equals_the_whole_first_visit(variant):
+    """Causal attention over the cache plus the new rows: forwarding a prompt in pieces (of any sizes, one of them a
+    single row, which is exactly a later visit) gives the rows of one first visit of the whole prompt, and the later
+    visits that follow do not see a difference."""
+    kw = dict(norm_kind=S.NORM_LAYERNORM, mlp_kind=S.MLP_GELU_TANH, pos_kind=S.POS_LEARNED, has_bias=1, tie_embed=1, n_kv_head=4) if variant == "gpt2" else {}
+    cfg = S.tiny(n_layer=3, max_ctx=40, **kw)
+    w = S.make_weights(cfg, 19, exercise=True)
+    ids = S.make_prompts(cfg, 19, 1, 23)[0]
+    whole, pieces = O.Partition(cfg, w, 0, 3, has_embed=True), O.Partition(cfg, w, 0, 3, has_embed=True)
+    want = whole.prefill(0, ids)
+    at, rows = 0, []
+    for n in (7, 1, 11, 4):
+        rows.append(pieces.prefill_chunk(0, ids[at:at + n]))
+        at += n
+    got = np.concatenate(rows)
+    assert got.shape == want.shape and np.abs(got - want).max() <= 1e-11 * np.abs(want).max()
+    assert pieces.seq_len(0) == whole.seq_len(0) == 23
+    for t in (3, 9):
+        a, b = whole.decode_step(0, t), pieces.decode_step(0, t)
+        assert np.abs(a - b).max() <= 1e-11 * np.abs(a).max()
+    # a piece of one row IS a later visit: same code path, same bits
+    one, other = O.Partition(cfg, w, 0, 3, has_embed=True), O.Partition(cfg, w, 0, 3, has_embed=True)
+    one.prefill(0, ids[:5]); other.prefill(0, ids[:5])
+    assert np.array_equal(one.prefill_chunk(0, ids[5:6])[0], other.decode_step(0, int(ids[5])))

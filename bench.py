@@ -211,7 +211,7 @@ def main():
     sweep = None
     if args.ctx_sweep:
         sweep = []
-        for T in (prompt + wl["n_new"] // 2, prompt + wl["n_new"] - 8 - 400 // n_seqs):
+        for T in (prompt + wl["n_new"] // 2, prompt + wl["n_new"] - 8 - -(-440 // n_seqs)):   # 440 = timed + warm-up steps
             r = run(T, 400, 40, queue)
             sweep.append({k: r[k] for k in ("ctx", "ms_per_step", "tokens_per_s", "gbs")})
 

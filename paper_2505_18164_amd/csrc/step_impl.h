@@ -399,21 +399,36 @@ __device__ __forceinline__ AttnGeo make_attn_geo(const StepArgs& a, const StepSl
   return g;
 }
 
-// Issues exactly 2 * kTile loads (see gemv_issue); slots without a token re-read token 0.
-template <typename WT>
-__device__ __forceinline__ void attn_issue(Tile& t, const AttnGeo& g, const StepArgs& a, const StepSlot& S, const void* pool_, int ti, int wave) {
-  const MDI_GLOBAL WT* pool = (const MDI_GLOBAL WT*)pool_;
+// Page numbers of the tokens of tile ti (slots without a token take token 0's).  The table entries of every position
+// before the newest were written by earlier launches, so they are fetched a tile pair ahead of the rows they locate:
+// a row's address then never waits for a table look-up.
+__device__ __forceinline__ void attn_pages(int (&pg)[kTile], const AttnGeo& g, const StepArgs& a, const StepSlot& S, int ti, int wave) {
   const MDI_GLOBAL int32_t* table = (const MDI_GLOBAL int32_t*)S.table;
 #pragma unroll
   for (int s = 0; s < kTile; ++s) {
     const int k = ti * kTile + s;
     int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
     if (!(k < g.n_k && tok < g.s1p)) tok = 0;
-    const int page = __hip_atomic_load(table + tok / a.pt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const MDI_GLOBAL WT* kp = pool + ((long)page * a.K + g.kvh) * 2 * a.pt_h + (long)(tok % a.pt) * a.h + g.hoff;
+    pg[s] = __hip_atomic_load(table + tok / a.pt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+// Issues exactly 2 * kTile row loads (see gemv_issue) for tile ti, whose page numbers are in pg, then asks for the
+// page numbers of the tile that goes into the same registers next; slots without a token re-read token 0.
+template <typename WT>
+__device__ __forceinline__ void attn_issue(Tile& t, int (&pg)[kTile], const AttnGeo& g, const StepArgs& a, const StepSlot& S, const void* pool_,
+                                           int ti, int wave) {
+  const MDI_GLOBAL WT* pool = (const MDI_GLOBAL WT*)pool_;
+#pragma unroll
+  for (int s = 0; s < kTile; ++s) {
+    const int k = ti * kTile + s;
+    int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
+    if (!(k < g.n_k && tok < g.s1p)) tok = 0;
+    const MDI_GLOBAL WT* kp = pool + ((long)pg[s] * a.K + g.kvh) * 2 * a.pt_h + (long)(tok % a.pt) * a.h + g.hoff;
     t.r[2 * s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp);
     t.r[2 * s + 1] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp + a.pt_h);
   }
+  attn_pages(pg, g, a, S, ti + 2, wave);
 }
 
 template <typename WT, int G>
@@ -671,6 +686,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
   AttnState<WT, G> st;
   AttnGeo ga{};
   Tile A, B;
+  int pgA[kTile], pgB[kTile];               // page numbers of the attention tiles that go into A and B next
   // requested while finishing the previous (message, phase): the next one's flags and the head of its input vector
   bool early_flags = false, early_vec = false;
   unsigned efl[4] = {0u, 0u, 0u, 0u};
@@ -696,13 +712,20 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
         const Geo g = load_geo(j, layer_matrix(Lv, j), wave);
         if (ph == PH_ATTN) {
           ga = make_attn_geo<WT, G>(a, S, wg, wave, lane);
-          attn_issue<WT>(A, ga, a, S, L->kv, 0, wave); attn_issue<WT>(B, ga, a, S, L->kv, 1, wave);
+          attn_pages(pgA, ga, a, S, 0, wave); attn_pages(pgB, ga, a, S, 1, wave);
+          attn_issue<WT>(A, pgA, ga, a, S, L->kv, 0, wave); attn_issue<WT>(B, pgB, ga, a, S, L->kv, 1, wave);
         } else { gemv_issue(A, g, 0, wave, lane); gemv_issue(B, g, 1, wave, lane); }
 
         auto early_requests = [&]() __attribute__((always_inline)) {
           // ---- requests for the next (message, phase), answered while this phase is being finished: with two
           //      messages alternating, what the next one needs was published a whole phase ago
           early_flags = false; early_vec = false;
+          // whatever was requested a phase ago has been used: giving every register a value here, on every path,
+          // tells the compiler that none of them is live across the streaming loops above
+#pragma unroll
+          for (int k = 0; k < 4; ++k) efl[k] = 0u;
+#pragma unroll
+          for (int jj = 0; jj < 8; ++jj) { eraw[jj] = 0ull; egain[jj] = 1.f; }
           if (slot_hi - slot_lo > 1) {
             int nslot = slot + 1, nph = ph, nlayer = layer;
             if (nslot == slot_hi) { nslot = slot_lo; if (++nph == 5) { nph = 0; ++nlayer; } }
@@ -789,9 +812,9 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
 #pragma nounroll
           for (int t = 0; t < nte; t += 2) {
             attn_compute<WT, G>(st, A, ga, a.h, t, wave, xs);
-            attn_issue<WT>(A, ga, a, S, L->kv, t + 2, wave);
+            attn_issue<WT>(A, pgA, ga, a, S, L->kv, t + 2, wave);
             attn_compute<WT, G>(st, B, ga, a.h, t + 1, wave, xs);
-            attn_issue<WT>(B, ga, a, S, L->kv, t + 3, wave);
+            attn_issue<WT>(B, pgB, ga, a, S, L->kv, t + 3, wave);
           }
           stamp(a, S, layer, ph, 3);
           early_requests();

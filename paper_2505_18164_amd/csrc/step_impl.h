@@ -188,7 +188,18 @@ struct Geo {
                          // reads one contiguous window of the matrix, and a workgroup stays >= 64 KiB in place.
   int n_k;               // this wavefront's items: item k is flat index wave + 8k, flat = pair * cpp + chunk
   int dq, dr;            // 8 / cpp and 8 % cpp: how (pair, chunk) moves from one item to the next
+  int rsh, rmask, rmul, rstep;   // first row of pair p = (p >> rsh) * rmul + (p & rmask); its partner rstep rows on
 };
+// The two pairings as one branch-free formula (head sizes are powers of two): rows (2p, 2p + 1), or RoPE partners
+// (i, i + h/2) inside heads of h rows.
+__device__ __forceinline__ void geo_rows(Geo& g) {
+  if (g.rope_h) {
+    const int half = g.rope_h >> 1;
+    g.rsh = 31 - __builtin_clz(half); g.rmask = half - 1; g.rmul = g.rope_h; g.rstep = half;
+  } else {
+    g.rsh = 0; g.rmask = 0; g.rmul = 2; g.rstep = 1;
+  }
+}
 
 template <typename WT>
 __device__ __forceinline__ Geo make_geo(const void* W, int N, int Kd, int rope_h, int wg, int nwg, int wave) {
@@ -208,6 +219,7 @@ __device__ __forceinline__ Geo make_geo(const void* W, int N, int Kd, int rope_h
   const int flat = g.n_pl * g.cpp;
   g.n_k = flat > wave ? (flat - wave + kStepWaves - 1) / kStepWaves : 0;
   g.dq = kStepWaves / g.cpp; g.dr = kStepWaves - g.dq * g.cpp;
+  geo_rows(g);
   return g;
 }
 __device__ __forceinline__ void geo_next(const Geo& g, int& pl, int& c) {
@@ -218,12 +230,7 @@ __device__ __forceinline__ int geo_pair(const Geo& g, int pl) {     // local pai
   return ((((pl >> g.bshift) * g.nwg) + g.p_lo) << g.bshift) + (pl & ((1 << g.bshift) - 1));
 }
 __device__ __forceinline__ int geo_row(const Geo& g, int p, int j) {
-  if (g.rope_h) {                                   // head sizes are powers of two
-    const int half = g.rope_h >> 1, sh = 31 - __builtin_clz(half);
-    const int head = p >> sh, i = p & (half - 1);
-    return head * g.rope_h + i + j * half;
-  }
-  return 2 * p + j;
+  return (p >> g.rsh) * g.rmul + (p & g.rmask) + j * g.rstep;
 }
 
 // the step's own input (token embedding + learned position, or the previous stage's activation)
@@ -249,35 +256,41 @@ __device__ __forceinline__ void stage_input(const StepArgs& a, const StepSlot& S
   }
 }
 
-// Every call issues exactly 2 * kTile loads, whatever the geometry: items past the end of the
-// wavefront's share (and lanes past the end of a row) read the first bytes of the matrix instead
-// and are ignored by gemv_compute.  A fixed number of loads per tile is what lets the compiler
-// wait for one tile while the next stays in flight (its counters cannot follow conditional loads).
-__device__ __forceinline__ void gemv_issue(Tile& t, const Geo& g, int ti, int wave, int lane) {
+// Where a wavefront stands in its items (local pair, chunk of the row): tiles are issued, and multiplied, in order, so
+// each side keeps a cursor and moves it item by item instead of dividing the item index again for every tile.
+struct Cursor { int pl, c; };
+__device__ __forceinline__ Cursor cursor_start(const Geo& g, int wave) {
+  Cursor cur;
+  cur.pl = wave / g.cpp; cur.c = wave - cur.pl * g.cpp;
+  return cur;
+}
+
+// Every call issues exactly 2 * kTile loads, whatever the geometry: a fixed number of loads per tile is what lets
+// the compiler wait for one tile while the next stays in flight (its counters cannot follow conditional loads).
+// Items past the end of the wavefront's share need no case of their own: their pair index lies past the matrix and
+// is clamped to its last row, lanes past the end of a row read the row's first bytes; gemv_compute ignores both.
+// All of this is scalar arithmetic on the critical path of a phase's start, so it is kept short.
+__device__ __forceinline__ void gemv_issue(Tile& t, const Geo& g, Cursor& cur, int lane) {
   const MDI_GLOBAL u32x4* W = (const MDI_GLOBAL u32x4*)g.W;
-  const int i0 = wave + kStepWaves * kTile * ti;
-  int pl = i0 / g.cpp, c = i0 - pl * g.cpp;
+  int pl = cur.pl, c = cur.c;
 #pragma unroll
   for (int s = 0; s < kTile; ++s) {
-    const bool item = ti * kTile + s < g.n_k;                 // uniform
-    const int p = geo_pair(g, item ? pl : 0);
-    const int r0 = item ? min(geo_row(g, p, 0), g.N - 1) : 0, r1 = item ? min(geo_row(g, p, 1), g.N - 1) : 0;
-    const int cc = item ? c : 0;
-    const MDI_GLOBAL u32x4* b0 = W + (long)r0 * g.units + cc * 64;
-    const MDI_GLOBAL u32x4* b1 = W + (long)r1 * g.units + cc * 64;
-    const int off = cc * 64 + lane < g.units ? lane : 0;      // unit 0 of the chunk always exists
+    const int r0 = min(geo_row(g, geo_pair(g, pl), 0), g.N - 1), r1 = min(r0 + g.rstep, g.N - 1);
+    const MDI_GLOBAL u32x4* b0 = W + (long)r0 * g.units + c * 64;
+    const MDI_GLOBAL u32x4* b1 = W + (long)r1 * g.units + c * 64;
+    const int off = c * 64 + lane < g.units ? lane : 0;       // unit 0 of the chunk always exists
     t.r[2 * s] = b0[off];
     t.r[2 * s + 1] = b1[off];
     geo_next(g, pl, c);
   }
+  cur.pl = pl; cur.c = c;
 }
 
 template <typename WT>
-__device__ __forceinline__ void gemv_compute(const Tile& t, const Geo& g, int ti, int wave, int lane, const float* xs,
+__device__ __forceinline__ void gemv_compute(const Tile& t, const Geo& g, int ti, Cursor& cur, int wave, int lane, const float* xs,
                                              float* part, float& acc0, float& acc1) {
   constexpr int V = Storage<WT>::kVec;
-  const int i0 = wave + kStepWaves * kTile * ti;
-  int pl = i0 / g.cpp, c = i0 - pl * g.cpp;
+  int pl = cur.pl, c = cur.c;
 #pragma unroll
   for (int s = 0; s < kTile; ++s) {
     int npl = pl, nc = c;
@@ -305,6 +318,7 @@ __device__ __forceinline__ void gemv_compute(const Tile& t, const Geo& g, int ti
     }
     pl = npl; c = nc;
   }
+  cur.pl = pl; cur.c = c;
 }
 
 // Sums the wavefront slots of every pair and applies the phase's epilogue.
@@ -380,6 +394,7 @@ struct AttnGeo {
   int hg, split, kvh, s0, s1, s1p;
   int L, tpw, sub, hoff;
   int n_k;                // this wavefront's steps: step k covers tokens s0 + (8k + wave) * tpw ..
+  int pt_sh;              // log2(tokens per page) when that is a power of two, else -1
 };
 
 template <typename WT, int G>
@@ -396,12 +411,14 @@ __device__ __forceinline__ AttnGeo make_attn_geo(const StepArgs& a, const StepSl
   g.s1p = min(g.s1, S.ctx - 1);                               // the newest row is written in this launch
   const int steps = g.active && g.s1p > g.s0 ? (g.s1p - g.s0 + g.tpw - 1) / g.tpw : 0;
   g.n_k = steps > wave ? (steps - wave + kStepWaves - 1) / kStepWaves : 0;
+  g.pt_sh = (a.pt & (a.pt - 1)) == 0 ? __builtin_ctz(a.pt) : -1;
   return g;
 }
 
 // Page numbers of the tokens of tile ti (slots without a token take token 0's).  The table entries of every position
 // before the newest were written by earlier launches, so they are fetched a tile pair ahead of the rows they locate:
 // a row's address then never waits for a table look-up.
+template <bool kPow2>
 __device__ __forceinline__ void attn_pages(int (&pg)[kTile], const AttnGeo& g, const StepArgs& a, const StepSlot& S, int ti, int wave) {
   const MDI_GLOBAL int32_t* table = (const MDI_GLOBAL int32_t*)S.table;
 #pragma unroll
@@ -409,13 +426,13 @@ __device__ __forceinline__ void attn_pages(int (&pg)[kTile], const AttnGeo& g, c
     const int k = ti * kTile + s;
     int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
     if (!(k < g.n_k && tok < g.s1p)) tok = 0;
-    pg[s] = __hip_atomic_load(table + tok / a.pt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    pg[s] = __hip_atomic_load(table + (kPow2 ? tok >> g.pt_sh : tok / a.pt), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
 // Issues exactly 2 * kTile row loads (see gemv_issue) for tile ti, whose page numbers are in pg, then asks for the
 // page numbers of the tile that goes into the same registers next; slots without a token re-read token 0.
-template <typename WT>
+template <typename WT, bool kPow2>
 __device__ __forceinline__ void attn_issue(Tile& t, int (&pg)[kTile], const AttnGeo& g, const StepArgs& a, const StepSlot& S, const void* pool_,
                                            int ti, int wave) {
   const MDI_GLOBAL WT* pool = (const MDI_GLOBAL WT*)pool_;
@@ -424,11 +441,12 @@ __device__ __forceinline__ void attn_issue(Tile& t, int (&pg)[kTile], const Attn
     const int k = ti * kTile + s;
     int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
     if (!(k < g.n_k && tok < g.s1p)) tok = 0;
-    const MDI_GLOBAL WT* kp = pool + ((long)pg[s] * a.K + g.kvh) * 2 * a.pt_h + (long)(tok % a.pt) * a.h + g.hoff;
+    const int in_page = kPow2 ? tok & (a.pt - 1) : tok % a.pt;
+    const MDI_GLOBAL WT* kp = pool + ((long)pg[s] * a.K + g.kvh) * 2 * a.pt_h + (long)in_page * a.h + g.hoff;
     t.r[2 * s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp);
     t.r[2 * s + 1] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp + a.pt_h);
   }
-  attn_pages(pg, g, a, S, ti + 2, wave);
+  attn_pages<kPow2>(pg, g, a, S, ti + 2, wave);
 }
 
 template <typename WT, int G>
@@ -635,6 +653,7 @@ __device__ __forceinline__ Geo load_geo(int j, const void* W, int wave) {
   g.bshift = __builtin_amdgcn_readfirstlane(o[8]); g.nwg = __builtin_amdgcn_readfirstlane(o[9]);
   const int flat = g.n_pl * g.cpp;
   g.n_k = flat > wave ? (flat - wave + kStepWaves - 1) / kStepWaves : 0;
+  geo_rows(g);
   return g;
 }
 // GEMV phases in order: 0 = QKV, 1 = output projection, 2 = MLP up, 3 = MLP down
@@ -686,6 +705,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
   AttnState<WT, G> st;
   AttnGeo ga{};
   Tile A, B;
+  Cursor ci, cc;                             // the GEMV phases' issue and multiply cursors
   int pgA[kTile], pgB[kTile];               // page numbers of the attention tiles that go into A and B next
   // requested while finishing the previous (message, phase): the next one's flags and the head of its input vector
   bool early_flags = false, early_vec = false;
@@ -712,9 +732,15 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
         const Geo g = load_geo(j, layer_matrix(Lv, j), wave);
         if (ph == PH_ATTN) {
           ga = make_attn_geo<WT, G>(a, S, wg, wave, lane);
-          attn_pages(pgA, ga, a, S, 0, wave); attn_pages(pgB, ga, a, S, 1, wave);
-          attn_issue<WT>(A, pgA, ga, a, S, L->kv, 0, wave); attn_issue<WT>(B, pgB, ga, a, S, L->kv, 1, wave);
-        } else { gemv_issue(A, g, 0, wave, lane); gemv_issue(B, g, 1, wave, lane); }
+          // a division per token is most of the address arithmetic; page sizes are powers of two as a rule
+          if (ga.pt_sh >= 0) {
+            attn_pages<true>(pgA, ga, a, S, 0, wave); attn_pages<true>(pgB, ga, a, S, 1, wave);
+            attn_issue<WT, true>(A, pgA, ga, a, S, L->kv, 0, wave); attn_issue<WT, true>(B, pgB, ga, a, S, L->kv, 1, wave);
+          } else {
+            attn_pages<false>(pgA, ga, a, S, 0, wave); attn_pages<false>(pgB, ga, a, S, 1, wave);
+            attn_issue<WT, false>(A, pgA, ga, a, S, L->kv, 0, wave); attn_issue<WT, false>(B, pgB, ga, a, S, L->kv, 1, wave);
+          }
+        } else { ci = cc = cursor_start(g, wave); gemv_issue(A, g, ci, lane); gemv_issue(B, g, ci, lane); }
 
         auto early_requests = [&]() __attribute__((always_inline)) {
           // ---- requests for the next (message, phase), answered while this phase is being finished: with two
@@ -812,9 +838,11 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
 #pragma nounroll
           for (int t = 0; t < nte; t += 2) {
             attn_compute<WT, G>(st, A, ga, a.h, t, wave, xs);
-            attn_issue<WT>(A, pgA, ga, a, S, L->kv, t + 2, wave);
+            if (ga.pt_sh >= 0) attn_issue<WT, true>(A, pgA, ga, a, S, L->kv, t + 2, wave);
+            else attn_issue<WT, false>(A, pgA, ga, a, S, L->kv, t + 2, wave);
             attn_compute<WT, G>(st, B, ga, a.h, t + 1, wave, xs);
-            attn_issue<WT>(B, pgB, ga, a, S, L->kv, t + 3, wave);
+            if (ga.pt_sh >= 0) attn_issue<WT, true>(B, pgB, ga, a, S, L->kv, t + 3, wave);
+            else attn_issue<WT, false>(B, pgB, ga, a, S, L->kv, t + 3, wave);
           }
           stamp(a, S, layer, ph, 3);
           early_requests();
@@ -866,10 +894,10 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
           const int nte = ((g.n_k + kTile - 1) / kTile + 1) & ~1;
 #pragma nounroll
           for (int t = 0; t < nte; t += 2) {
-            gemv_compute<WT>(A, g, t, wave, lane, xs, part, acc0, acc1);
-            gemv_issue(A, g, t + 2, wave, lane);
-            gemv_compute<WT>(B, g, t + 1, wave, lane, xs, part, acc0, acc1);
-            gemv_issue(B, g, t + 3, wave, lane);
+            gemv_compute<WT>(A, g, t, cc, wave, lane, xs, part, acc0, acc1);
+            gemv_issue(A, g, ci, lane);
+            gemv_compute<WT>(B, g, t + 1, cc, wave, lane, xs, part, acc0, acc1);
+            gemv_issue(B, g, ci, lane);
           }
           stamp(a, S, layer, ph, 3);
           early_requests();
@@ -917,8 +945,9 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
   float* red = lds_red();
   const Geo g = make_geo<WT>(a.W, a.N, a.Kd, 0, wg, nwg, wave);
   Tile A, B;
-  gemv_issue(A, g, 0, wave, lane);
-  gemv_issue(B, g, 1, wave, lane);
+  Cursor ci = cursor_start(g, wave), cc = ci;
+  gemv_issue(A, g, ci, lane);
+  gemv_issue(B, g, ci, lane);
   for (int i = threadIdx.x; i < a.Kd; i += kStepThreads) xs[i] = load_kind(a.x, a.x_kind, i);
   for (int i = threadIdx.x; i < g.n_pl * 2 * kStepWaves; i += kStepThreads) part[i] = 0.f;
   __syncthreads();
@@ -928,10 +957,10 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
   const int nte = ((g.n_k + kTile - 1) / kTile + 1) & ~1;
 #pragma nounroll
   for (int t = 0; t < nte; t += 2) {
-    gemv_compute<WT>(A, g, t, wave, lane, xs, part, acc0, acc1);
-    gemv_issue(A, g, t + 2, wave, lane);
-    gemv_compute<WT>(B, g, t + 1, wave, lane, xs, part, acc0, acc1);
-    gemv_issue(B, g, t + 3, wave, lane);
+    gemv_compute<WT>(A, g, t, cc, wave, lane, xs, part, acc0, acc1);
+    gemv_issue(A, g, ci, lane);
+    gemv_compute<WT>(B, g, t + 1, cc, wave, lane, xs, part, acc0, acc1);
+    gemv_issue(B, g, ci, lane);
   }
   __syncthreads();                                           // all wavefronts' partials are in LDS
   float bv = -INFINITY; int bi = 0x7FFFFFFF;

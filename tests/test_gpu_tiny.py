@@ -70,6 +70,31 @@ def test_mid_partition_activations_in_and_out(dtype, path):
         check(g.decode_step(0, dev_acts(x, cfg)), o.decode_step(0, x), cfg, ("decode", step))
 
 
+@pytest.mark.parametrize("path", [0, 1, 3], ids=["persistent", "per_op", "persistent_tiles"])
+@pytest.mark.parametrize("page_tokens", [5, 12])
+def test_page_sizes_that_are_not_powers_of_two(page_tokens, path):
+    # the attention kernels locate a cached row by position / page size and position % page size: shifts for the
+    # usual page sizes, a division otherwise
+    cfg = S.tiny(n_layer=2, dtype=S.DT_F32, max_ctx=64)
+    w = scale_matrices(S.make_weights(cfg, 44, exercise=True), 6.0)
+    o, g = pair(cfg, w, 0, 2, embed=True, max_seqs=2, kv_page_tokens=page_tokens, decode_path=path)
+    prompts = [S.make_prompts(cfg, 44, 1, 17)[0], S.make_prompts(cfg, 45, 1, 6)[0]]
+    for s in (0, 1):
+        check(g.prefill(s, dev_ids(prompts[s])), o.prefill(s, prompts[s]), cfg, ("prefill", s))
+    rng = np.random.default_rng(9)
+    for step in range(14):                      # every sample crosses several page boundaries
+        toks = [int(rng.integers(0, cfg["vocab"])) for _ in range(2)]
+        if step % 2:
+            outs = g.decode_steps([1, 0], [dev_ids([toks[1]]), dev_ids([toks[0]])])
+            check(outs[0], o.decode_step(1, toks[1]), cfg, ("queued", step, 1))
+            check(outs[1], o.decode_step(0, toks[0]), cfg, ("queued", step, 0))
+        else:
+            for s in (0, 1):
+                check(g.decode_step(s, dev_ids([toks[s]])), o.decode_step(s, toks[s]), cfg, ("decode", step, s))
+    assert g.seq_len(0) == 17 + 14 and g.seq_len(1) == 6 + 14
+    g.sync()
+
+
 def test_prefill_of_one_token_and_argmax_ties():
     cfg = S.tiny(n_layer=1, dtype=S.DT_F32)
     w = S.make_weights(cfg, 2)

@@ -72,7 +72,7 @@ typedef struct mdi_config {
   uint32_t vocab;          /* V                                                         */
   uint32_t max_ctx;        /* longest sequence (prompt + generated) a cache may hold     */
   uint32_t max_seqs;       /* number of samples in flight = number of KV caches          */
-  uint32_t kv_page_tokens; /* tokens per KV page; 0 = 16                                */
+  uint32_t kv_page_tokens; /* tokens per KV page; 0 = 16; max_ctx * this < 2^32         */
   uint32_t kv_pages;       /* pages in the pool; 0 = max_seqs * ceil(max_ctx / page)     */
   uint32_t max_prefill;    /* longest first visit T; 0 = max_ctx (sizes prefill scratch) */
   uint32_t norm_kind;      /* MDI_NORM_*                                                */

@@ -110,6 +110,8 @@ mdi_status check_config(const mdi_config* c, uint32_t lo, uint32_t hi, uint32_t 
   if (!(c->norm_eps >= 0.f)) return MDI_ERR_ARG;
   if (c->pos_kind == MDI_POS_ROPE && !(c->rope_base > 0.f)) return MDI_ERR_ARG;
   if (c->max_prefill > c->max_ctx) return MDI_ERR_ARG;
+  // the decode kernel divides a position by the page size with one multiplication, exact below this bound
+  if ((uint64_t)c->max_ctx * (c->kv_page_tokens ? c->kv_page_tokens : 16) >= (1ull << 32)) return MDI_ERR_ARG;
   if (flags & ~(uint32_t)(MDI_HAS_EMBED | MDI_HAS_HEAD)) return MDI_ERR_ARG;
   if (hi > c->n_layer || lo > hi) return MDI_ERR_ARG;
   if (lo == hi && ((flags & MDI_HAS_EMBED) || !(flags & MDI_HAS_HEAD))) return MDI_ERR_ARG;

@@ -394,8 +394,31 @@ struct AttnGeo {
   int hg, split, kvh, s0, s1, s1p;
   int L, tpw, sub, hoff;
   int n_k;                // this wavefront's steps: step k covers tokens s0 + (8k + wave) * tpw ..
-  int pt_sh;              // log2(tokens per page) when that is a power of two, else -1
+  float f2, f4, f8, f16;  // 1 when a position's values are spread over at least that many lanes, else 0
+  int pt_sh;              // log2(tokens per page) when that is a power of two, else -1 ...
+  unsigned pt_magic;      // ... and then position / page size = high word of position * pt_magic (exact while
+                          // position * page size < 2^32, which creating the partition checks)
 };
+// Sum over the g.L lanes that share a position, in every one of them.  Inside a row of 16 lanes every step is taken,
+// multiplied by the step's flag: no branch on the (run-time) lane count in the streaming loop.  Same order of
+// additions as group_sum.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add_if(float v, float flag) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false);
+  return fmaf(__int_as_float(moved), flag, v);
+}
+__device__ __forceinline__ float group_sum_lanes(float v, const AttnGeo& g) {
+  v = dpp_add_if<kDppXor1>(v, g.f2);
+  v = dpp_add_if<kDppXor2>(v, g.f4);
+  v = dpp_add_if<kDppHalfMirror>(v, g.f8);
+  v = dpp_add_if<kDppMirror>(v, g.f16);
+  if (g.L >= 32) v += __shfl_xor(v, 16, 64);
+  if (g.L >= 64) v += __shfl_xor(v, 32, 64);
+  return v;
+}
+__device__ __forceinline__ int page_of(const AttnGeo& g, int tok) {
+  return g.pt_sh >= 0 ? tok >> g.pt_sh : (int)__umulhi((unsigned)tok, g.pt_magic);
+}
 
 template <typename WT, int G>
 __device__ __forceinline__ AttnGeo make_attn_geo(const StepArgs& a, const StepSlot& S, int wg, int wave, int lane) {
@@ -411,14 +434,15 @@ __device__ __forceinline__ AttnGeo make_attn_geo(const StepArgs& a, const StepSl
   g.s1p = min(g.s1, S.ctx - 1);                               // the newest row is written in this launch
   const int steps = g.active && g.s1p > g.s0 ? (g.s1p - g.s0 + g.tpw - 1) / g.tpw : 0;
   g.n_k = steps > wave ? (steps - wave + kStepWaves - 1) / kStepWaves : 0;
+  g.f2 = g.L >= 2 ? 1.f : 0.f; g.f4 = g.L >= 4 ? 1.f : 0.f; g.f8 = g.L >= 8 ? 1.f : 0.f; g.f16 = g.L >= 16 ? 1.f : 0.f;
   g.pt_sh = (a.pt & (a.pt - 1)) == 0 ? __builtin_ctz(a.pt) : -1;
+  g.pt_magic = g.pt_sh >= 0 ? 0u : 0xFFFFFFFFu / (unsigned)a.pt + 1u;
   return g;
 }
 
 // Page numbers of the tokens of tile ti (slots without a token take token 0's).  The table entries of every position
 // before the newest were written by earlier launches, so they are fetched a tile pair ahead of the rows they locate:
 // a row's address then never waits for a table look-up.
-template <bool kPow2>
 __device__ __forceinline__ void attn_pages(int (&pg)[kTile], const AttnGeo& g, const StepArgs& a, const StepSlot& S, int ti, int wave) {
   const MDI_GLOBAL int32_t* table = (const MDI_GLOBAL int32_t*)S.table;
 #pragma unroll
@@ -426,13 +450,13 @@ __device__ __forceinline__ void attn_pages(int (&pg)[kTile], const AttnGeo& g, c
     const int k = ti * kTile + s;
     int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
     if (!(k < g.n_k && tok < g.s1p)) tok = 0;
-    pg[s] = __hip_atomic_load(table + (kPow2 ? tok >> g.pt_sh : tok / a.pt), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    pg[s] = __hip_atomic_load(table + page_of(g, tok), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
 // Issues exactly 2 * kTile row loads (see gemv_issue) for tile ti, whose page numbers are in pg, then asks for the
 // page numbers of the tile that goes into the same registers next; slots without a token re-read token 0.
-template <typename WT, bool kPow2>
+template <typename WT>
 __device__ __forceinline__ void attn_issue(Tile& t, int (&pg)[kTile], const AttnGeo& g, const StepArgs& a, const StepSlot& S, const void* pool_,
                                            int ti, int wave) {
   const MDI_GLOBAL WT* pool = (const MDI_GLOBAL WT*)pool_;
@@ -441,12 +465,12 @@ __device__ __forceinline__ void attn_issue(Tile& t, int (&pg)[kTile], const Attn
     const int k = ti * kTile + s;
     int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
     if (!(k < g.n_k && tok < g.s1p)) tok = 0;
-    const int in_page = kPow2 ? tok & (a.pt - 1) : tok % a.pt;
+    const int in_page = tok - page_of(g, tok) * a.pt;
     const MDI_GLOBAL WT* kp = pool + ((long)pg[s] * a.K + g.kvh) * 2 * a.pt_h + (long)in_page * a.h + g.hoff;
     t.r[2 * s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp);
     t.r[2 * s + 1] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(kp + a.pt_h);
   }
-  attn_pages<kPow2>(pg, g, a, S, ti + 2, wave);
+  attn_pages(pg, g, a, S, ti + 2, wave);
 }
 
 template <typename WT, int G>
@@ -466,7 +490,7 @@ __device__ __forceinline__ void attn_update_f(AttnState<WT, G>& st, const AttnGe
       const float4 q4 = *reinterpret_cast<const float4*>(qs + gi * h + g.hoff + e);
       s = fmaf(q4.x, kf[e], s); s = fmaf(q4.y, kf[e + 1], s); s = fmaf(q4.z, kf[e + 2], s); s = fmaf(q4.w, kf[e + 3], s);
     }
-    s = group_sum(s, g.L);
+    s = group_sum_lanes(s, g);
     if (valid) {
       const float mn = fmaxf(st.m[gi], s);
       const float alpha = __expf(st.m[gi] - mn), p = __expf(s - mn);
@@ -497,6 +521,19 @@ __device__ __forceinline__ void attn_compute(AttnState<WT, G>& st, const Tile& t
       const int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
       attn_update<WT, G>(st, g, h, t.r[2 * s], t.r[2 * s + 1], tok < g.s1p, qs);
     }
+  }
+}
+
+// The streaming loop of the attention phase: two tiles in flight, each multiplied while the other's rows arrive.
+template <typename WT, int G>
+__device__ __forceinline__ void attn_stream(AttnState<WT, G>& st, Tile& A, Tile& B, int (&pgA)[kTile], int (&pgB)[kTile], const AttnGeo& ga,
+                                            const StepArgs& a, const StepSlot& S, const void* kv, int nte, int wave, const float* xs) {
+#pragma nounroll
+  for (int t = 0; t < nte; t += 2) {
+    attn_compute<WT, G>(st, A, ga, a.h, t, wave, xs);
+    attn_issue<WT>(A, pgA, ga, a, S, kv, t + 2, wave);
+    attn_compute<WT, G>(st, B, ga, a.h, t + 1, wave, xs);
+    attn_issue<WT>(B, pgB, ga, a, S, kv, t + 3, wave);
   }
 }
 
@@ -732,14 +769,8 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
         const Geo g = load_geo(j, layer_matrix(Lv, j), wave);
         if (ph == PH_ATTN) {
           ga = make_attn_geo<WT, G>(a, S, wg, wave, lane);
-          // a division per token is most of the address arithmetic; page sizes are powers of two as a rule
-          if (ga.pt_sh >= 0) {
-            attn_pages<true>(pgA, ga, a, S, 0, wave); attn_pages<true>(pgB, ga, a, S, 1, wave);
-            attn_issue<WT, true>(A, pgA, ga, a, S, L->kv, 0, wave); attn_issue<WT, true>(B, pgB, ga, a, S, L->kv, 1, wave);
-          } else {
-            attn_pages<false>(pgA, ga, a, S, 0, wave); attn_pages<false>(pgB, ga, a, S, 1, wave);
-            attn_issue<WT, false>(A, pgA, ga, a, S, L->kv, 0, wave); attn_issue<WT, false>(B, pgB, ga, a, S, L->kv, 1, wave);
-          }
+          attn_pages(pgA, ga, a, S, 0, wave); attn_pages(pgB, ga, a, S, 1, wave);
+          attn_issue<WT>(A, pgA, ga, a, S, L->kv, 0, wave); attn_issue<WT>(B, pgB, ga, a, S, L->kv, 1, wave);
         } else { ci = cc = cursor_start(g, wave); gemv_issue(A, g, ci, lane); gemv_issue(B, g, ci, lane); }
 
         auto early_requests = [&]() __attribute__((always_inline)) {
@@ -835,15 +866,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
           attn_begin<WT, G>(st, ga, a, S, xs, epoch);
           stamp(a, S, layer, ph, 2);
           const int nte = ((ga.n_k + kTile - 1) / kTile + 1) & ~1;
-#pragma nounroll
-          for (int t = 0; t < nte; t += 2) {
-            attn_compute<WT, G>(st, A, ga, a.h, t, wave, xs);
-            if (ga.pt_sh >= 0) attn_issue<WT, true>(A, pgA, ga, a, S, L->kv, t + 2, wave);
-            else attn_issue<WT, false>(A, pgA, ga, a, S, L->kv, t + 2, wave);
-            attn_compute<WT, G>(st, B, ga, a.h, t + 1, wave, xs);
-            if (ga.pt_sh >= 0) attn_issue<WT, true>(B, pgB, ga, a, S, L->kv, t + 3, wave);
-            else attn_issue<WT, false>(B, pgB, ga, a, S, L->kv, t + 3, wave);
-          }
+          attn_stream<WT, G>(st, A, B, pgA, pgB, ga, a, S, L->kv, nte, wave, xs);
           stamp(a, S, layer, ph, 3);
           early_requests();
           attn_to_lds<WT, G>(st, ga, a.h, xs, wave);

@@ -21,6 +21,12 @@
  *
  * Thread-safety: calls on one partition must be serialised by the caller;
  * different partitions share no mutable state and may be driven concurrently.
+ *
+ * One tuning knob is read from the environment when a partition is created:
+ * MDI_GROUP_CTX = context length from which, in models whose query heads share
+ * kv heads in even groups, the decode kernel lets two query heads take one pass
+ * over the cache together (default 4096; below it every head takes its own).
+ * Results are within the parity bar either way; the order of additions differs.
  */
 #ifndef MDI_H
 #define MDI_H

@@ -69,6 +69,7 @@ struct mdi_partition {
   // persistent single-launch decode step
   bool use_step = false;
   int nwg = 0, G = 1, n_hg = 0, part_floats = 0;
+  int group_ctx = 4096;   // context length from which a launch lets G query heads share a pass over the cache
   size_t step_lds = 0;
   std::vector<StepLayer> h_step_layers;
   StepLayer* d_step_layers = nullptr;
@@ -228,8 +229,14 @@ void plan_step(mdi_partition* p, int n_cu) {
   if (c.decode_path == 1 || !p->n_local || n_cu <= 0) return;
   const int H = c.n_head, K = c.n_kv_head, h = c.head_dim, d = c.d_model, F = c.d_ff;
   const int group = H / K;
-  p->G = (group == 8 || group == 4 || group == 2) ? group : 1;
-  p->n_hg = H / p->G;
+  // Query heads that take one pass over their kv head's cache together.  Measured (heads of 128, groups of 4 and 8):
+  // sharing the pass among a whole group leaves few, long work items (one per kv head and context split) with many
+  // partials to fold, and loses to one head per item, whose repeated cache reads hit in L2 / the memory-side cache;
+  // pairs of heads win once the cache is long (step_group picks per launch).  LDS is sized for pairs.
+  p->G = group % 2 == 0 ? 2 : 1;
+  p->group_ctx = 4096;
+  if (const char* e = getenv("MDI_GROUP_CTX")) p->group_ctx = std::max(0, atoi(e));   // tuning / test knob, see mdi.h
+  p->n_hg = H;                           // the most head groups a launch has (one head each)
   p->nwg = std::min(n_cu, 1024);
   if (p->n_hg > p->nwg) return;
   const int nup = c.mlp_kind == MDI_MLP_SWIGLU ? 2 * F : F;
@@ -589,8 +596,11 @@ mdi_status plan_message(mdi_partition* p, uint32_t seq, MessagePlan* m) {
   return MDI_OK;
 }
 
-// Arguments of the persistent step kernel that do not depend on the message.
-void fill_step_shared(const mdi_partition* p, StepArgs* a) {
+// Query heads per attention work item for a launch whose longest context is ctx (see plan_step).
+int step_group(const mdi_partition* p, int ctx) { return ctx >= p->group_ctx ? p->G : 1; }
+
+// Arguments of the persistent step kernel that do not depend on the message; G = query heads per attention work item.
+void fill_step_shared(const mdi_partition* p, int G, StepArgs* a) {
   const mdi_config& c = p->cfg;
   a->l0 = p->h_step_layers[0];
   a->w_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].wqkv - (const char*)p->h_step_layers[0].wqkv : 0;
@@ -601,14 +611,14 @@ void fill_step_shared(const mdi_partition* p, StepArgs* a) {
   a->norm_kind = c.norm_kind; a->mlp_kind = c.mlp_kind; a->eps = c.norm_eps;
   a->wte = p->wte; a->wpe = p->wpe; a->vocab = (int)c.vocab;
   a->err = p->err; a->spin_limit = 1 << 21;
-  a->n_hg = p->n_hg;
+  a->n_hg = (int)c.n_head / G;
   a->scale = 1.f / sqrtf((float)c.head_dim);
   a->act_kind = act_kind(c);
   a->part_floats = p->part_floats;
 }
 
 // One message's part of the arguments: message m of a launch whose sets have nwg workgroups each.
-void fill_step_slot(const mdi_partition* p, int m, int nwg, const MessagePlan& mp, const void* act_in, void* act_out, StepSlot* s) {
+void fill_step_slot(const mdi_partition* p, int m, int nwg, int n_hg, const MessagePlan& mp, const void* act_in, void* act_out, StepSlot* s) {
   const mdi_config& c = p->cfg;
   const int h = c.head_dim, K = c.n_kv_head;
   const long pt_h = (long)p->pt * h;
@@ -622,7 +632,7 @@ void fill_step_slot(const mdi_partition* p, int m, int nwg, const MessagePlan& m
   s->tickets = sc.tickets; s->flags = sc.flags; s->epoch0 = m == 0 ? p->epoch : sc.epoch;
   // context splits: as many as there are workgroups per head group, but no split shorter than 128 positions -
   // the partials of a head group are folded by one workgroup, eight at a time, and every eight cost a round trip
-  const int max_splits = std::max(1, std::min(kMaxSplits, nwg / p->n_hg));
+  const int max_splits = std::max(1, std::min(kMaxSplits, nwg / n_hg));
   int chunk = std::max((mp.ctx + max_splits - 1) / max_splits, 128);
   chunk = (chunk + 15) / 16 * 16;
   s->chunk = chunk; s->n_splits = (mp.ctx + chunk - 1) / chunk;
@@ -633,20 +643,23 @@ void fill_step_slot(const mdi_partition* p, int m, int nwg, const MessagePlan& m
 // Launches the persistent kernel for n <= kMaxSlots planned messages.
 mdi_status launch_messages(mdi_partition* p, int n, const uint32_t* seqs, const MessagePlan* mp, const void* const* ins, void* const* outs) {
   StepArgs a{};
-  fill_step_shared(p, &a);
+  int ctx = 0;
+  for (int m = 0; m < n; ++m) ctx = std::max(ctx, mp[m].ctx);
+  const int G = step_group(p, ctx);
+  fill_step_shared(p, G, &a);
   a.n_slots = n;
   a.n_sets = n >= 2 ? 2 : 1;             // two sets of 4-wavefront workgroups share the compute units
   a.nwg = p->nwg;
   a.set_lo[0] = 0; a.set_lo[1] = a.n_sets == 2 ? (n + 1) / 2 : n; a.set_lo[2] = n;
-  for (int m = 0; m < n; ++m) fill_step_slot(p, m, a.nwg, mp[m], ins[m], outs[m], &a.s[m]);
+  for (int m = 0; m < n; ++m) fill_step_slot(p, m, a.nwg, a.n_hg, mp[m], ins[m], outs[m], &a.s[m]);
   if (p->trace) {                      // timeline of the first message of each set (of the first two messages with one set)
     const int second = a.n_sets == 2 ? a.set_lo[1] : 1;
     a.s[0].trace = p->trace;
     if (second < n) a.s[second].trace = p->trace + (size_t)a.nwg * p->n_local * 40;
   }
   const mdi_status st = launch_step_serialised(p, [&]() {
-    if (n == 1) launch_step_w8(p->stream, p->cfg.dtype, p->G, a.nwg, p->step_lds, a);
-    else launch_step_w4(p->stream, p->cfg.dtype, p->G, a.nwg, p->step_lds, a);
+    if (n == 1) launch_step_w8(p->stream, p->cfg.dtype, G, a.nwg, p->step_lds, a);
+    else launch_step_w4(p->stream, p->cfg.dtype, G, a.nwg, p->step_lds, a);
   });
   if (st != MDI_OK) return st;
   p->epoch += 5u * (unsigned)p->n_local;

@@ -941,12 +941,9 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
 template <typename WT>
 static void launch_step_t(hipStream_t s, int G, int nwg, size_t lds, const StepArgs& a) {
   const dim3 grid(nwg * a.n_sets), block(kStepThreads);
-  switch (G) {
-    case 8: hipLaunchKernelGGL((k_step<WT, 8>), grid, block, lds, s, a); break;
-    case 4: hipLaunchKernelGGL((k_step<WT, 4>), grid, block, lds, s, a); break;
-    case 2: hipLaunchKernelGGL((k_step<WT, 2>), grid, block, lds, s, a); break;
-    default: hipLaunchKernelGGL((k_step<WT, 1>), grid, block, lds, s, a); break;
-  }
+  // G = query heads per attention work item: the host asks for 1 or 2 (larger groups were measured slower)
+  if (G == 2) hipLaunchKernelGGL((k_step<WT, 2>), grid, block, lds, s, a);
+  else hipLaunchKernelGGL((k_step<WT, 1>), grid, block, lds, s, a);
 }
 
 #if MDI_STEP_WAVES == 8

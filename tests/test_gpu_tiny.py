@@ -95,6 +95,31 @@ def test_page_sizes_that_are_not_powers_of_two(page_tokens, path):
     g.sync()
 
 
+@pytest.mark.parametrize("dtype", [S.DT_F32, S.DT_BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("name", ["llama_gqa", "llama_gqa8"])
+def test_pairs_of_query_heads_share_a_pass_over_the_cache(name, dtype, monkeypatch):
+    # long contexts switch the decode kernel to two query heads per pass over their kv head's cache; the switch-over
+    # length is lowered here so that small shapes take that path, alone and with queued messages
+    monkeypatch.setenv("MDI_GROUP_CTX", "12")
+    cfg = S.tiny(n_layer=2, dtype=dtype, max_ctx=48, **VARIANTS[name])
+    w = scale_matrices(S.make_weights(cfg, 52, exercise=True), 6.0 if dtype == S.DT_F32 else 3.0)
+    o, g = pair(cfg, w, 0, 2, embed=True, max_seqs=2, kv_page_tokens=8)
+    prompts = [S.make_prompts(cfg, 52, 1, 9)[0], S.make_prompts(cfg, 53, 1, 4)[0]]
+    for s in (0, 1):
+        check(g.prefill(s, dev_ids(prompts[s])), o.prefill(s, prompts[s]), cfg, ("prefill", s))
+    rng = np.random.default_rng(3)
+    for step in range(16):                      # contexts 5..25: both sides of the switch-over
+        toks = [int(rng.integers(0, cfg["vocab"])) for _ in range(2)]
+        if step % 2:
+            outs = g.decode_steps([0, 1], [dev_ids([toks[0]]), dev_ids([toks[1]])])
+            for s in (0, 1):
+                check(outs[s], o.decode_step(s, toks[s]), cfg, ("queued", step, s))
+        else:
+            for s in (0, 1):
+                check(g.decode_step(s, dev_ids([toks[s]])), o.decode_step(s, toks[s]), cfg, ("decode", step, s))
+    g.sync()
+
+
 def test_prefill_of_one_token_and_argmax_ties():
     cfg = S.tiny(n_layer=1, dtype=S.DT_F32)
     w = S.make_weights(cfg, 2)

@@ -72,6 +72,12 @@ def test_argument_validation(L):
     assert status(0, 2, 0, dtype=7) == libmdi.MDI_ERR_ARG
     c = libmdi.make_config(cfg, max_seqs=0)
     assert L.mdi_partition_bytes(C.byref(c), 0, 2, 0, C.byref(n)) == libmdi.MDI_ERR_ARG
+    # position / page size is one multiplication in the decode kernel, exact while max_ctx * page size < 2^32
+    c = libmdi.make_config(dict(cfg, max_ctx=1 << 20), max_seqs=1)
+    c.kv_page_tokens = 1 << 11
+    assert L.mdi_partition_bytes(C.byref(c), 0, 2, 0, C.byref(n)) == libmdi.MDI_OK
+    c.kv_page_tokens = 1 << 12
+    assert L.mdi_partition_bytes(C.byref(c), 0, 2, 0, C.byref(n)) == libmdi.MDI_ERR_ARG
     c = libmdi.make_config(cfg, max_seqs=1)
     c.abi_version = 99
     assert L.mdi_partition_bytes(C.byref(c), 0, 2, 0, C.byref(n)) == libmdi.MDI_ERR_ARG
@@ -82,3 +88,17 @@ def test_argument_validation(L):
     assert L.mdi_sample_greedy(None, 0, None, None, None) == libmdi.MDI_ERR_ARG
     assert L.mdi_seq_reset(None, 0) == libmdi.MDI_ERR_ARG
     L.mdi_partition_destroy(None)
+
+
+def test_reciprocal_page_division_is_exact_below_the_checked_bound():
+    # the decode kernel computes position // page_size as the high word of position * (0xFFFFFFFF // page_size + 1)
+    # for page sizes that are not powers of two; exhaustive near the boundaries, random elsewhere
+    import numpy as np
+    rng = np.random.default_rng(0)
+    for pt in [3, 5, 6, 7, 12, 24, 48, 100, 255, 1000, 4097]:
+        magic = np.uint64(0xFFFFFFFF // pt + 1)
+        top = (1 << 32) // pt                                   # positions with position * pt < 2^32
+        pos = np.unique(np.concatenate([np.arange(0, min(top, 5000)), np.arange(max(0, top - 5000), top),
+                                        rng.integers(0, top, 20000), (np.arange(1, 3000) * pt - 1) % top,
+                                        (np.arange(1, 3000) * pt) % top])).astype(np.uint64)
+        assert np.array_equal((pos * magic) >> np.uint64(32), pos // np.uint64(pt)), pt

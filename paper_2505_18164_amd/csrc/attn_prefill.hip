@@ -10,6 +10,8 @@
 // keys), and P^T leaves the first product in exactly the register layout the second one wants as
 // its B operand, without any data movement.  The price is that the values are needed with the key
 // index contiguous (A operand of V^T P^T), so a small kernel writes V transposed beforehand.
+#include <mutex>
+
 #include "device_utils.h"
 
 namespace mdi {
@@ -39,16 +41,24 @@ __global__ __launch_bounds__(256) void k_v_transpose(const float* qkv, int T, in
   }
 }
 
+// Two groups of four wavefronts work on the same 128 queries: group g takes the key blocks 2 i + g, so the longest
+// workgroup (the last queries, which see every key) has half as many steps in a row, and a SIMD holds two wavefronts
+// whose matrix and softmax arithmetic overlap.  The groups' running (maximum, sum, output) are folded through LDS at
+// the end, group 0 first: the result does not depend on timing.
 template <int HD>
-__global__ __launch_bounds__(256) void k_flash_prefill(FlashArgs a) {
+__global__ __launch_bounds__(512) void k_flash_prefill(FlashArgs a) {
   constexpr int KS = HD + 8;            // LDS row stride of a key (elements): 16 bytes of padding spread the rows over the banks
   constexpr int VS = BK + 4;            // LDS row stride of a value channel: an odd number of 8-byte units
   constexpr int HT = HD / 32;           // 32-channel tiles of the output
-  constexpr int KP = BK * HD / 8 / 256; // 16-byte pieces of a key block per thread
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[BK * KS];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[HD * VS];
+  constexpr int KP = BK * HD / 8 / 256; // 16-byte pieces of a key block per thread of a group
+  extern __shared__ __attribute__((aligned(16))) unsigned char flash_smem[];
+  bf16_t* Ks_all = (bf16_t*)flash_smem;                 // [2][BK * KS]
+  bf16_t* Vs_all = Ks_all + 2 * BK * KS;                // [2][HD * VS]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;   // position inside the group
+  const int grp = threadIdx.x >> 8;
+  bf16_t* Ks = Ks_all + grp * BK * KS;
+  bf16_t* Vs = Vs_all + grp * HD * VS;
   const int qb = gridDim.x - 1 - blockIdx.x;                     // the longest rows first
   const int head = blockIdx.y, kvh = head / (a.H / a.K);
   const int q0 = qb * BQ, qw0 = q0 + 32 * wave;
@@ -74,10 +84,13 @@ __global__ __launch_bounds__(256) void k_flash_prefill(FlashArgs a) {
   const bf16_t* kbase = a.k + (long)kvh * a.Tp * HD;
   const bf16_t* vbase = a.vt + (long)kvh * HD * a.Tp;
   const int n_kb = min((q0 + BQ + BK - 1) / BK, a.Tp / BK);      // key blocks any query of this workgroup may see
+  const int n_it = (n_kb + 1) / 2;                               // steps: block 2 it + grp each
 
   // staging registers: the next block's keys and values travel global -> registers during the arithmetic
+  // (a group whose last step has no block re-reads block 0 and skips the arithmetic)
   u32x4 kreg[KP], vreg[KP];
   auto fetch = [&](int kb) {
+    if (kb >= n_kb) kb = 0;
 #pragma unroll
     for (int i = 0; i < KP; ++i) {
       const int p = tid + i * 256;                               // piece p: key p / (HD/8), elements 8 (p % (HD/8))
@@ -98,14 +111,15 @@ __global__ __launch_bounds__(256) void k_flash_prefill(FlashArgs a) {
     }
   };
 
-  fetch(0);
-  for (int kb = 0; kb < n_kb; ++kb) {
-    __syncthreads();                                             // everybody is done with the previous block
+  fetch(grp);
+  for (int it = 0; it < n_it; ++it) {
+    const int kb = 2 * it + grp;
+    __syncthreads();                                             // everybody is done with the previous blocks
     stash();
     __syncthreads();
-    if (kb + 1 < n_kb) fetch(kb + 1);
+    if (it + 1 < n_it) fetch(kb + 2);
     const int k0 = kb * BK;
-    if (k0 > qw0 + 31) continue;                                 // this wavefront's queries see none of these keys
+    if (kb >= n_kb || k0 > qw0 + 31) continue;                   // no block, or this wavefront's queries see none of these keys
 
     // ---- S^T = K Q^T: two tiles of 32 keys x 32 queries
     f32x16 s[2];
@@ -164,6 +178,31 @@ __global__ __launch_bounds__(256) void k_flash_prefill(FlashArgs a) {
       }
   }
 
+  // ---- fold the two groups: group 1 hands its state over through LDS (the K/V area, no longer needed);
+  //      element j of thread t at [j][t], so that a wavefront's accesses are consecutive
+  float* fold = (float*)flash_smem;
+  __syncthreads();
+  if (grp == 1) {
+#pragma unroll
+    for (int i = 0; i < HT; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) fold[(i * 16 + r) * 256 + tid] = o[i][r];
+    fold[(HT * 16) * 256 + tid] = m;
+    fold[(HT * 16 + 1) * 256 + tid] = l;
+  }
+  __syncthreads();
+  if (grp == 1) return;
+  {
+    const float m1 = fold[(HT * 16) * 256 + tid], l1 = fold[(HT * 16 + 1) * 256 + tid];
+    const float mn = fmaxf(m, m1);
+    const float a0 = __expf(m - mn), a1 = __expf(m1 - mn);       // a group that saw no key has m = -1e30, l = 0, o = 0
+    l = l * a0 + l1 * a1;
+#pragma unroll
+    for (int i = 0; i < HT; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[i][r] = o[i][r] * a0 + fold[(i * 16 + r) * 256 + tid] * a1;
+  }
+
   l += __shfl_xor(l, 32, 64);
   if (query < a.T) {
     const float inv = 1.f / l;
@@ -179,6 +218,14 @@ __global__ __launch_bounds__(256) void k_flash_prefill(FlashArgs a) {
   }
 }
 
+template <int HD>
+constexpr size_t flash_lds_bytes() {
+  // two key blocks and two value blocks; the fold at the end needs HD / 2 + 2 floats per thread of one group
+  const size_t kv = (size_t)2 * (BK * (HD + 8) + HD * (BK + 4)) * sizeof(bf16_t);
+  const size_t fold = (size_t)(HD / 2 + 2) * 256 * sizeof(float);
+  return kv > fold ? kv : fold;
+}
+
 }  // namespace
 
 bool flash_supported(int dtype, int h) { return dtype == MDI_BF16 && (h == 64 || h == 128); }
@@ -190,8 +237,16 @@ void launch_v_transpose(hipStream_t s, const float* qkv, int T, int Tp, int H, i
 
 void launch_flash_prefill(hipStream_t s, const FlashArgs& a) {
   const dim3 grid(a.Tp / BQ, a.H);
-  if (a.h == 128) hipLaunchKernelGGL(k_flash_prefill<128>, grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(k_flash_prefill<64>, grid, dim3(256), 0, s, a);
+  if (a.h == 128) {
+    constexpr size_t lds = flash_lds_bytes<128>();               // above the 64 KiB a kernel gets by default
+    static std::once_flag raised;
+    std::call_once(raised, []() {
+      (void)hipFuncSetAttribute((const void*)k_flash_prefill<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
+    hipLaunchKernelGGL(k_flash_prefill<128>, grid, dim3(512), lds, s, a);
+  } else {
+    hipLaunchKernelGGL(k_flash_prefill<64>, grid, dim3(512), flash_lds_bytes<64>(), s, a);
+  }
 }
 
 }  // namespace mdi

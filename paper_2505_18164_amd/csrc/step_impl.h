@@ -258,10 +258,15 @@ __device__ __forceinline__ void stage_input(const StepArgs& a, const StepSlot& S
 
 // Where a wavefront stands in its items (local pair, chunk of the row): tiles are issued, and multiplied, in order, so
 // each side keeps a cursor and moves it item by item instead of dividing the item index again for every tile.
-struct Cursor { int pl, c; };
+struct Cursor {
+  int pl, c;
+  int row_pl;                          // the local pair whose row addresses b0, b1 hold (-1: none yet)
+  const MDI_GLOBAL u32x4 *b0, *b1;     // (issue side only) a pair's rows stay the same over its chunks
+};
 __device__ __forceinline__ Cursor cursor_start(const Geo& g, int wave) {
   Cursor cur;
   cur.pl = wave / g.cpp; cur.c = wave - cur.pl * g.cpp;
+  cur.row_pl = -1; cur.b0 = nullptr; cur.b1 = nullptr;
   return cur;
 }
 
@@ -275,12 +280,15 @@ __device__ __forceinline__ void gemv_issue(Tile& t, const Geo& g, Cursor& cur, i
   int pl = cur.pl, c = cur.c;
 #pragma unroll
   for (int s = 0; s < kTile; ++s) {
-    const int r0 = min(geo_row(g, geo_pair(g, pl), 0), g.N - 1), r1 = min(r0 + g.rstep, g.N - 1);
-    const MDI_GLOBAL u32x4* b0 = W + (long)r0 * g.units + c * 64;
-    const MDI_GLOBAL u32x4* b1 = W + (long)r1 * g.units + c * 64;
-    const int off = c * 64 + lane < g.units ? lane : 0;       // unit 0 of the chunk always exists
-    t.r[2 * s] = b0[off];
-    t.r[2 * s + 1] = b1[off];
+    if (pl != cur.row_pl) {                                     // uniform; long rows keep a pair for several items
+      const int r0 = min(geo_row(g, geo_pair(g, pl), 0), g.N - 1), r1 = min(r0 + g.rstep, g.N - 1);
+      cur.b0 = W + (long)r0 * g.units;
+      cur.b1 = W + (long)r1 * g.units;
+      cur.row_pl = pl;
+    }
+    const int off = c * 64 + (c * 64 + lane < g.units ? lane : 0);   // unit 0 of the chunk always exists
+    t.r[2 * s] = cur.b0[off];
+    t.r[2 * s + 1] = cur.b1[off];
     geo_next(g, pl, c);
   }
   cur.pl = pl; cur.c = c;

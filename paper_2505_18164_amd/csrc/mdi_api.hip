@@ -244,6 +244,7 @@ void plan_step(mdi_partition* p, int n_cu) {
   const int max_pairs = ((max_rows + 1) / 2 + p->nwg - 1) / p->nwg + 1;
   p->part_floats = (max_pairs * 2 * kStepWavesMax + 3) & ~3;
   int xs = std::max(std::max(d, H * h), F);
+  xs = (xs + 511) / 512 * 512;         // the kernel keeps zeros behind a vector up to a whole 64-lane chunk (64 x 8 values)
   xs = std::max(xs, kStepWavesMax * p->G * (h + 2));
   xs = (xs + 3) & ~3;
   p->step_lds = (size_t)(128 + p->part_floats + xs) * sizeof(float);

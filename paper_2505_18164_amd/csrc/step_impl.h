@@ -294,7 +294,9 @@ __device__ __forceinline__ void gemv_issue(Tile& t, const Geo& g, Cursor& cur, i
   cur.pl = pl; cur.c = c;
 }
 
-template <typename WT>
+// kPadded: the caller has zeros in xs behind the vector, up to a whole number of 64-lane chunks, so the lanes past the
+// end of a row (which hold the row's first bytes) multiply by zero and need no case of their own.
+template <typename WT, bool kPadded>
 __device__ __forceinline__ void gemv_compute(const Tile& t, const Geo& g, int ti, Cursor& cur, int wave, int lane, const float* xs,
                                              float* part, float& acc0, float& acc1) {
   constexpr int V = Storage<WT>::kVec;
@@ -306,7 +308,7 @@ __device__ __forceinline__ void gemv_compute(const Tile& t, const Geo& g, int ti
     const int k = ti * kTile + s;
     if (k < g.n_k) {                                         // uniform
       const int unit = c * 64 + lane;
-      if (unit < g.units) {
+      if (kPadded || unit < g.units) {
         float w0[V], w1[V], xv[V];
         Unpack<WT>::go(t.r[2 * s], w0);
         Unpack<WT>::go(t.r[2 * s + 1], w1);
@@ -908,6 +910,8 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
                                             early_vec, eraw, egain);
             if (fused_rms) row_scale = 1.f / sqrtf(block_sum(ss, red) / (float)a.d + a.eps);
           }
+          // zeros behind the vector up to a whole 64-lane chunk (the host sizes the LDS for it): see gemv_compute
+          for (int i = g.units * Storage<WT>::kVec + (int)threadIdx.x; i < g.cpp * 64 * Storage<WT>::kVec; i += kStepThreads) xs[i] = 0.f;
           __syncthreads();
           if (normed && !fused_rms) {
             normalise(xs, a.d, a.norm_kind, a.eps, gain, ph == PH_QKV ? L->ln1_b : L->ln2_b, red);
@@ -925,9 +929,9 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
           const int nte = ((g.n_k + kTile - 1) / kTile + 1) & ~1;
 #pragma nounroll
           for (int t = 0; t < nte; t += 2) {
-            gemv_compute<WT>(A, g, t, cc, wave, lane, xs, part, acc0, acc1);
+            gemv_compute<WT, true>(A, g, t, cc, wave, lane, xs, part, acc0, acc1);
             gemv_issue(A, g, ci, lane);
-            gemv_compute<WT>(B, g, t + 1, cc, wave, lane, xs, part, acc0, acc1);
+            gemv_compute<WT, true>(B, g, t + 1, cc, wave, lane, xs, part, acc0, acc1);
             gemv_issue(B, g, ci, lane);
           }
           stamp(a, S, layer, ph, 3);
@@ -985,9 +989,9 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
   const int nte = ((g.n_k + kTile - 1) / kTile + 1) & ~1;
 #pragma nounroll
   for (int t = 0; t < nte; t += 2) {
-    gemv_compute<WT>(A, g, t, cc, wave, lane, xs, part, acc0, acc1);
+    gemv_compute<WT, false>(A, g, t, cc, wave, lane, xs, part, acc0, acc1);
     gemv_issue(A, g, ci, lane);
-    gemv_compute<WT>(B, g, t + 1, cc, wave, lane, xs, part, acc0, acc1);
+    gemv_compute<WT, false>(B, g, t + 1, cc, wave, lane, xs, part, acc0, acc1);
     gemv_issue(B, g, ci, lane);
   }
   __syncthreads();                                           // all wavefronts' partials are in LDS

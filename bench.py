@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 # HBM bytes per k_step launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this script
 # ((workload, messages per launch) -> bytes);
 # the numbers and the commands are in profiles/k_step_c4_decode_hbm_counters.md
-MEASURED_TRAFFIC = {(4, 8): 2.4115e10, (4, 1): 3.4074e9}
+MEASURED_TRAFFIC = {(4, 8): 2.3804e10, (4, 1): 3.4074e9}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 

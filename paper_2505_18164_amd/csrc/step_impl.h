@@ -273,8 +273,9 @@ __device__ __forceinline__ Cursor cursor_start(const Geo& g, int wave) {
 // Every call issues exactly 2 * kTile loads, whatever the geometry: a fixed number of loads per tile is what lets
 // the compiler wait for one tile while the next stays in flight (its counters cannot follow conditional loads).
 // Items past the end of the wavefront's share need no case of their own: their pair index lies past the matrix and
-// is clamped to its last row, lanes past the end of a row read the row's first bytes; gemv_compute ignores both.
-// All of this is scalar arithmetic on the critical path of a phase's start, so it is kept short.
+// is clamped to its last row, lanes past the end of a row read the row's first bytes; gemv_compute skips the former
+// and masks the latter or multiplies them by zeros.  All of this is scalar arithmetic, which the wavefronts of a
+// compute unit share one unit for, on the critical path of a phase's start: it is kept short.
 __device__ __forceinline__ void gemv_issue(Tile& t, const Geo& g, Cursor& cur, int lane) {
   const MDI_GLOBAL u32x4* W = (const MDI_GLOBAL u32x4*)g.W;
   int pl = cur.pl, c = cur.c;

@@ -381,6 +381,10 @@ void launch_gemm(hipStream_t s, int dtype, int epi, const GemmArgs& a) {
     const long big = (long)((a.N + 191) / 192) * ((a.T + 255) / 256);
     const long rounds = (big + n_cu - 1) / n_cu;
     if (a.T >= 256 && big * 10 >= rounds * n_cu * 7) { launch_gemm_bf16<256, 192, 8, 4>(s, epi, a); return; }
+    // 256 x 128 tiles when they give one round that keeps at least 70 % of the compute units busy (2048 rows x 4096
+    // outputs: exactly one tile each): a quarter less operand traffic per product than 128 x 128 tiles
+    const long mid = (long)((a.N + 127) / 128) * ((a.T + 255) / 256);
+    if (a.T >= 256 && mid <= n_cu && mid * 10 >= n_cu * 7) { launch_gemm_bf16<256, 128, 8, 4>(s, epi, a); return; }
     // a grid of 128 x 128 tiles that cannot give every compute unit two 4-wavefront workgroups: one 8-wavefront
     // workgroup each (a third less operand traffic than two 128 x 64 tiles), or narrower tiles when even that
     // leaves compute units idle

@@ -1,21 +1,29 @@
 """Benchmark of the partition decode hot path on one MI355X.
 
-One step = one later visit of one sample (Sec. III-D) to the partition (all
+One step = one later visit of one sample (Sec. III-D) to a partition (all its
 layers: norm, fused QKV + RoPE + KV append, paged attention, output projection,
-MLP), every message forwarded on its own with its own pass over the weights.
-The N samples in flight are visited round-robin, so consecutive steps read
-different KV caches (the rotating-cache access pattern).  By default the
+MLP).  The N samples in flight are visited round-robin, so consecutive steps
+read different KV caches (the rotating-cache access pattern).  By default the
 messages of all N samples are handed over per call (mdi_decode_steps: the
-node's input queue, Sec. III-A, drained in one launch); `--queue 1` hands them
-over one at a time (mdi_decode_step), and the default run reports that rate
-too.  Inputs, weights and caches are resident in HBM before the timed region;
-prompts are prefilled (first visit) before it and timed separately.
+node's input queue, Sec. III-A, drained in one call); `--queue 1` hands them
+over one at a time (mdi_decode_step, the paper's own rule), and the default run
+reports that rate too.  Inputs, weights and caches are resident in HBM before
+the timed region; prompts are prefilled (first visit) before it and timed
+separately.
+
+Any --steps / --warmup is accepted: exactly --steps steps are timed (the last
+call of a window carries fewer messages when the count does not divide), and a
+workload whose caches cannot hold them in one go (C1, C2) times them in several
+windows, each after fresh first visits, with only the decode calls inside the
+timed regions.  Workloads with several partitions (C2, C5) put all of them on
+the one GPU and report every partition alone and all of them driven round-robin.
 
 Prints ONE JSON line (see the keys below).
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -26,14 +34,33 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
-# HBM bytes per k_step launch from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this script
-# ((workload, messages per launch) -> bytes);
-# the numbers and the commands are in profiles/k_step_c4_decode_hbm_counters.md
-MEASURED_TRAFFIC = {(4, 8): 2.3804e10, (4, 1): 3.4074e9}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+# HBM bytes per launch of the decode kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this script, keyed by
+# (workload, messages per launch, batched arithmetic).  A figure is only reported while the kernel sources still
+# hash to what they were when it was measured; otherwise `roofline.traffic` is null.
+KERNEL_SOURCES = ("step_impl.h", "step_w4.hip", "step_w8.hip", "device_utils.h", "mdi_internal.h")
+MEASURED_TRAFFIC = {}
 
 
-def parse():
+def kernel_rev():
+    h = hashlib.sha1()
+    for name in KERNEL_SOURCES:
+        path = os.path.join(ROOT, "paper_2505_18164_amd", "csrc", name)
+        if os.path.exists(path):
+            h.update(open(path, "rb").read())
+    return h.hexdigest()[:12]
+
+
+def measured_traffic(workload, in_launch, batched):
+    rec = MEASURED_TRAFFIC.get((workload, in_launch, bool(batched)))
+    if rec and rec["kernel_rev"] == kernel_rev():
+        return rec["bytes"], rec["source"]
+    return None, None
+
+
+def parse(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1600)
@@ -41,40 +68,75 @@ def parse():
     ap.add_argument("--workload", type=int, default=4, help="index into the five benchmark configs (1-5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-output-layers", action="store_true", help="skip timing the output layers of the same model")
+    ap.add_argument("--no-side-runs", action="store_true", help="only the main timed region (no one-at-a-time run, no other partitions)")
     ap.add_argument("--ctx-sweep", action="store_true", help="also time decode at the middle and end context")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
-    ap.add_argument("--decode-path", type=int, default=0, help="0 = automatic (persistent single-launch step), 1 = one kernel per operation, 3 = persistent launch with streaming/exchange wavefronts on tiled matrices")
+    ap.add_argument("--decode-path", type=int, default=0, help="0 = automatic (persistent single-launch step), 1 = one kernel per operation")
     ap.add_argument("--queue", type=int, default=0,
                     help="messages of different samples handed to the partition per call: 0 = all samples in flight "
-                         "(mdi_decode_steps drains the queue), 1 = one at a time (mdi_decode_step); must divide the "
-                         "number of samples in flight")
-    return ap.parse_args()
+                         "(mdi_decode_steps drains the queue), 1 = one at a time (mdi_decode_step)")
+    return ap.parse_args(argv)
 
 
-def cpu_baseline(cfg, w, lo, hi, seed, S):
-    """The oracle as it stands, timed on this host: a short first visit plus a few decode steps."""
-    import numpy as np
+def plan_windows(n_seqs, prompt, max_ctx, steps, warmup, queue):
+    """How `steps` timed decode steps (after `warmup` untimed ones) fit a workload whose caches hold max_ctx
+    positions: a list of windows (warmup_steps, timed_steps); every window starts from fresh first visits of
+    `prompt` tokens.  Never refuses: the queue is clamped to [1, n_seqs], a warm-up that alone would fill the
+    caches is cut (the count actually run is in the result), and the timed steps are spread over as many windows
+    as the context needs.  Returns (queue, windows)."""
+    queue = n_seqs if queue <= 0 else max(1, min(queue, n_seqs))
+    steps = max(1, int(steps))
+    warmup = max(0, int(warmup))
+    cap = n_seqs * (max_ctx - prompt)               # decode steps the caches hold after the first visits
+    if cap < 2:
+        raise ValueError("workload leaves no room for decode steps")
+    warm0 = min(warmup, cap // 4)
+    rewarm = min(warm0, n_seqs)                     # later windows only re-warm after their first visits
+    windows, left = [], steps
+    while left > 0:
+        w = warm0 if not windows else rewarm
+        t = min(left, cap - w)
+        windows.append((w, t))
+        left -= t
+    return queue, windows
+
+
+def calls_of(first, count, queue, n_seqs):
+    """Round-robin message ids of `count` steps starting at step index `first`, cut into calls of <= queue."""
+    out, k = [], first
+    end = first + count
+    while k < end:
+        m = min(queue, end - k)
+        out.append([(k + i) % n_seqs for i in range(m)])
+        k += m
+    return out
+
+
+def cpu_baseline(cfg, w, lo, hi, seed, S, prompt, embed):
+    """The oracle as it stands, timed on this host: one sample's first visit of the workload's prompt length, then
+    decode steps at that context for about 12 s."""
     from oracle import mdi_oracle as O
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = len(os.sched_getaffinity(0))
-    op = O.Partition(cfg, w, lo, hi)
-    T, budget_s, max_dec = 128, 12.0, 600
-    a = S.make_activations(cfg, seed, 0, T)
+    op = O.Partition(cfg, w, lo, hi, has_embed=embed)
+    T, budget_s, max_dec = prompt, 12.0, 600
+    a = S.make_prompts(cfg, seed, 1, T)[0] if embed else S.make_activations(cfg, seed, 0, T)
     t0 = time.perf_counter()
     op.prefill(0, a)
     t1 = time.perf_counter()
     n_dec = 0
-    while n_dec < max_dec and time.perf_counter() - t1 < budget_s:      # about 12 s of decode steps
-        op.decode_step(0, S.make_activations(cfg, seed, 0, 1, step=n_dec + 1)[0])
+    toks = S.make_prompts(cfg, seed + 3, 1, max_dec)[0] if embed else None
+    while n_dec < max_dec and time.perf_counter() - t1 < budget_s and T + n_dec < cfg["max_ctx"]:
+        op.decode_step(0, toks[n_dec] if embed else S.make_activations(cfg, seed, 0, 1, step=n_dec + 1)[0])
         n_dec += 1
     t2 = time.perf_counter()
     return {"value": n_dec / (t2 - t1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"float64 numpy oracle, same partition and weights, 1 sample: first visit of {T} tokens "
-                      f"({t1 - t0:.1f} s, not counted) then {n_dec} decode steps at context {T}+ ({t2 - t1:.1f} s)",
+                      f"({t1 - t0:.1f} s, {T / (t1 - t0):.1f} tokens/s, not counted) then {n_dec} decode steps at context {T}+ ({t2 - t1:.1f} s)",
             "host_cores_available": len(os.sched_getaffinity(0))}
 
 
@@ -90,73 +152,96 @@ def main():
 
     wl = S.WORKLOADS[args.workload]
     cfg, seed = wl["cfg"](), S.workload_seed(args.workload)
-    lo, hi = wl["parts"][0]
     n_seqs, prompt = wl["n_seqs"], wl["prompt"]
-    embed = lo == 0
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-
-    t0 = time.perf_counter()
-    w = S.make_weights(cfg, seed, lo, hi, embed=embed, head=False)
-    part = mdi.Partition(cfg, w, lo, hi, has_embed=embed, max_seqs=n_seqs, kv_page_tokens=64, decode_path=args.decode_path,
-                         max_prefill=max(prompt, cfg["max_ctx"] - 8 if args.ctx_sweep else prompt))
-    setup_s = time.perf_counter() - t0
     d = cfg["d_model"]
+    queue, windows = plan_windows(n_seqs, prompt, cfg["max_ctx"], args.steps, args.warmup, args.queue)
+    steps_run = sum(t for _, t in windows)
+    warmup_run = windows[0][0]
+
+    # ---- partitions: the first one is the benchmarked one; the others of a several-partition workload are built
+    #      for the side runs (same shapes; their weight VALUES repeat the first partition's, each in its own arena)
+    t0 = time.perf_counter()
+    lo, hi = wl["parts"][0]
+    embed = lo == 0
+    w = S.make_weights(cfg, seed, lo, hi, embed=embed, head=False)
+    max_prefill = max(prompt, cfg["max_ctx"] - 8 if args.ctx_sweep else prompt)
+
+    def build_part(plo, phi, weights, has_embed):
+        return mdi.Partition(cfg, weights, plo, phi, has_embed=has_embed, max_seqs=n_seqs, kv_page_tokens=64,
+                             decode_path=args.decode_path, max_prefill=max_prefill)
+
+    part = build_part(lo, hi, w, embed)
+    setup_s = time.perf_counter() - t0
     tdt = part.tdtype
 
-    def first_inputs(T):
-        if embed:
+    def first_inputs(p_embed, T):
+        if p_embed:
             return [torch.from_numpy(p).to(dev) for p in S.make_prompts(cfg, seed, n_seqs, T)]
         g = torch.Generator(device=dev).manual_seed(seed + 2)
         return [torch.randn((T, d), generator=g, device=dev, dtype=torch.float32).to(tdt) for _ in range(n_seqs)]
 
-    def step_inputs():
-        if embed:
-            return [torch.randint(0, cfg["vocab"], (1,), device=dev, dtype=torch.int32) for _ in range(n_seqs)]
+    def step_inputs(p_embed):
+        if p_embed:
+            g = torch.Generator(device=dev).manual_seed(seed + 3)
+            return [torch.randint(0, cfg["vocab"], (1,), generator=g, device=dev, dtype=torch.int32) for _ in range(n_seqs)]
         g = torch.Generator(device=dev).manual_seed(seed + 3)
         return [torch.randn((d,), generator=g, device=dev, dtype=torch.float32).to(tdt) for _ in range(n_seqs)]
 
-    def run(T, steps, warmup, q):
-        """Prefill all samples at T tokens, then warm up and time `steps` decode steps, q messages per call."""
-        for s in range(n_seqs):
-            part.seq_reset(s)
-        ins = first_inputs(T)
+    def run(p, p_embed, T, wins, q):
+        """Per window: first visits of all samples at T tokens (timed separately), warm-up steps, then the timed
+        steps, q messages per call.  Returns rates over all windows."""
+        ins = first_inputs(p_embed, T)
         outs = [torch.empty((T, d), dtype=tdt, device=dev) for _ in range(n_seqs)]
-        part.prefill(0, ins[0], outs[0])          # untimed: loads the first-visit kernels
-        part.seq_reset(0)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for s in range(n_seqs):
-            part.prefill(s, ins[s], outs[s])
-        e1.record()
-        torch.cuda.synchronize()
-        prefill_ms = e0.elapsed_time(e1) / n_seqs
-        xs = step_inputs()
+        xs = step_inputs(p_embed)
         douts = [torch.empty((d,), dtype=tdt, device=dev) for _ in range(q)]
-
-        def visit(k):                      # messages k .. k + q - 1 of the round-robin order
-            if q == 1:
-                part.decode_step(k % n_seqs, xs[k % n_seqs], douts[0])
-            else:
-                ids = [(k + i) % n_seqs for i in range(q)]
-                part.decode_steps(ids, [xs[i] for i in ids], douts)
-
-        for k in range(0, warmup, q):
-            visit(k)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for s in range(n_seqs):
+            p.seq_reset(s)
+        p.prefill(0, ins[0], outs[0])          # untimed: loads the first-visit kernels
+        p.seq_reset(0)
         torch.cuda.synchronize()
-        ctx_first = part.seq_len(0) + 1
-        e0.record()
-        for k in range(0, steps, q):
-            visit(warmup + k)
-        e1.record()
-        part.sync()
-        ms = e0.elapsed_time(e1) / steps
-        ctx_last = max(part.seq_len(s) for s in range(n_seqs))
-        ctx_mean = (ctx_first + ctx_last) // 2
-        nbytes = part.step_bytes(ctx_mean)
+
+        def visit(ids):
+            if len(ids) == 1:
+                p.decode_step(ids[0], xs[ids[0]], douts[0])
+            else:
+                p.decode_steps(ids, [xs[i] for i in ids], douts[:len(ids)])
+
+        total_ms, total_steps, launches, prefill_ms, ctx_sum = 0.0, 0, 0, None, 0.0
+        for wi, (wu, timed) in enumerate(wins):
+            for s in range(n_seqs):
+                p.seq_reset(s)
+            torch.cuda.synchronize()
+            e0.record()
+            for s in range(n_seqs):
+                p.prefill(s, ins[s], outs[s])
+            e1.record()
+            torch.cuda.synchronize()
+            if prefill_ms is None:
+                prefill_ms = e0.elapsed_time(e1) / n_seqs
+            for ids in calls_of(0, wu, q, n_seqs):
+                visit(ids)
+            torch.cuda.synchronize()
+            ctx_first = p.seq_len(wu % n_seqs) + 1
+            calls = calls_of(wu, timed, q, n_seqs)
+            e0.record()
+            for ids in calls:
+                visit(ids)
+            e1.record()
+            p.sync()
+            total_ms += e0.elapsed_time(e1)
+            total_steps += timed
+            launches += len(calls)
+            ctx_last = max(p.seq_len(s) for s in range(n_seqs))
+            ctx_sum += 0.5 * (ctx_first + ctx_last) * timed
+        ms = total_ms / total_steps
+        ctx_mean = int(round(ctx_sum / total_steps))
+        nbytes = p.step_bytes(ctx_mean)
         return dict(ctx=ctx_mean, ms_per_step=ms, tokens_per_s=1000.0 / ms, bytes_per_step=nbytes,
-                    gbs=nbytes / ms / 1e6, prefill_ms=prefill_ms)
+                    gbs=nbytes / ms / 1e6, prefill_ms=prefill_ms, launches=launches, steps=total_steps,
+                    avg_launch_us=total_ms * 1e3 / launches)
 
     if args.calib_copy_mib:
         src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev).zero_()
@@ -165,39 +250,36 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    queue = args.queue if args.queue else n_seqs
-    if queue < 1 or n_seqs % queue or args.steps % queue or args.warmup % queue:
-        print("bench.py: --queue must divide the samples in flight, --steps and --warmup", file=sys.stderr)
-        sys.exit(2)
-    per_seq = -(-(args.warmup + args.steps) // n_seqs)
-    if prompt + per_seq > cfg["max_ctx"]:
-        print(f"bench.py: {args.warmup} + {args.steps} steps over {n_seqs} samples need a context of {prompt + per_seq}, "
-              f"this workload's caches hold {cfg['max_ctx']}; use fewer steps", file=sys.stderr)
-        sys.exit(2)
-    main_run = run(prompt, args.steps, args.warmup, queue)
+
+    main_run = run(part, embed, prompt, windows, queue)
     n_local = hi - lo
     params = sum(a * b for a, b in S.layer_tensor_shapes(cfg).values())
     prefill_flops = n_local * (2.0 * prompt * params + 2.0 * prompt * prompt * cfg["n_head"] * cfg["head_dim"])
     prefill_tflops = prefill_flops / (main_run["prefill_ms"] * 1e-3) / 1e12
+    bf16 = cfg["dtype"] == S.DT_BF16
 
-    persistent_kind = part.info(0) in (2, 3)
+    path_kind = part.info(0)          # 2 = persistent launch, 1 = one kernel per operation
+    persistent = path_kind == 2
+    side = not args.no_side_runs
     # the paper's own rule, one message at a time, next to the queue-draining figure
-    one_steps = min(400, (cfg["max_ctx"] - prompt - 1) * n_seqs * 10 // 11 // n_seqs * n_seqs)
-    one_run = run(prompt, one_steps, one_steps // 10, 1) if (queue > 1 and persistent_kind and one_steps > 0) else None
-    path_kind = part.info(0)          # 2 = persistent launch, 3 = persistent launch with streaming + exchange wavefronts on tiled matrices, 1 = per operation
-    persistent = path_kind in (2, 3)
+    one_run = None
+    if side and queue > 1:
+        _, one_w = plan_windows(n_seqs, prompt, cfg["max_ctx"], min(400, steps_run), min(40, warmup_run), 1)
+        one_run = run(part, embed, prompt, one_w, 1)
     kernels = {}
     if persistent:
         # the whole step is one kernel launch; its mean duration over the timed region (HIP events on the
-        # partition's stream, launches back to back) against the bytes a step must move
-        in_launch = queue if path_kind == 2 else 1          # messages one launch carries
-        roofline = {"bound": "hbm", "kernel": ("k_step2" if path_kind == 3 else "k_step") +
-                    f" (persistent decode launch, all layers, {in_launch} message(s) per launch)",
+        # partition's stream, launches back to back) against the bytes the launch must move
+        in_launch = main_run["steps"] / main_run["launches"]          # messages a launch carried on average
+        traffic, traffic_src = measured_traffic(args.workload, queue, False)
+        roofline = {"bound": "hbm", "kernel": f"k_step (persistent decode launch, all layers, {queue} message(s) per launch)",
                     "achieved": main_run["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": main_run["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.workload, in_launch)),
-                    "avg_launch_us": main_run["ms_per_step"] * 1e3 * in_launch,
+                    "frac": main_run["gbs"] / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
+                    "avg_launch_us": main_run["avg_launch_us"],
                     "bytes_per_launch": main_run["bytes_per_step"] * in_launch, "messages_per_launch": in_launch,
-                    "workgroups": part.info(1) * (2 if in_launch > 1 else 1), "lds_bytes": part.info(2)}
+                    "launches_timed": main_run["launches"],
+                    "workgroups": part.info(1) * (2 if queue > 1 else 1), "lds_bytes": part.info(2),
+                    "kernel_rev": kernel_rev()}
     else:
         # dominant kernel: the MLP up(+gate) projection GEMV, timed with HIP events inside the library
         us, kbytes = part.time_kernel(2, 50)
@@ -212,31 +294,96 @@ def main():
     if args.ctx_sweep:
         sweep = []
         for T in (prompt + wl["n_new"] // 2, prompt + wl["n_new"] - 8 - -(-440 // n_seqs)):   # 440 = timed + warm-up steps
-            r = run(T, 400, 40, queue)
+            r = run(part, embed, T, [(40, 400)], queue)
             sweep.append({k: r[k] for k in ("ctx", "ms_per_step", "tokens_per_s", "gbs")})
 
     result = {
         "metric": f"decode tokens/s per partition ({n_seqs} seqs in flight)",
-        "value": main_run["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": main_run["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps_run, "warmup": warmup_run,
         "ms_per_step": main_run["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg["dtype"] == S.DT_BF16 else "f32", "data": "synthetic",
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": wl["name"], "layers": [lo, hi], "seqs_in_flight": n_seqs, "prompt": prompt,
                    "context_during_timing": main_run["ctx"], "kv_page_tokens": 64, "messages_per_call": queue,
-                   "decode_path": {3: "persistent_tiles", 2: "persistent", 1: "per_op"}[path_kind]},
+                   "timed_windows": len(windows), "requested": {"steps": args.steps, "warmup": args.warmup},
+                   "decode_path": {2: "persistent", 1: "per_op"}[path_kind]},
         "step_bytes": main_run["bytes_per_step"], "step_GBps": main_run["gbs"],
         "step_frac_of_hbm_peak": main_run["gbs"] / HBM_PEAK_GBS,
         "roofline": roofline, "kernels": kernels,
         "prefill": {"tokens": prompt, "ms_per_sample": main_run["prefill_ms"], "TFLOP/s": prefill_tflops,
-                    "frac_of_bf16_mfma_peak": prefill_tflops / MFMA_BF16_PEAK_TFLOPS},
+                    "frac_of_bf16_mfma_peak": prefill_tflops / MFMA_BF16_PEAK_TFLOPS if bf16 else None,
+                    "frac_of_fp32_vector_peak": None if bf16 else prefill_tflops / FP32_VECTOR_PEAK_TFLOPS},
         "setup_s": setup_s,
     }
+    if one_run:
+        result["one_message_per_launch"] = {"ms_per_step": one_run["ms_per_step"], "tokens_per_s": one_run["tokens_per_s"],
+                                            "step_GBps": one_run["gbs"], "frac_of_hbm_peak": one_run["gbs"] / HBM_PEAK_GBS,
+                                            "steps": one_run["steps"]}
+    if sweep:
+        result["ctx_sweep"] = sweep
+
+    # ---- workloads of several partitions: each partition alone, then all of them driven round-robin -----------
+    if side and len(wl["parts"]) > 1:
+        others = []
+        for (plo, phi) in wl["parts"][1:]:
+            # same shapes as the first partition; blocks only (a secondary node), fed activations
+            w2 = {"layers": {plo + i: w["layers"][lo + i] for i in range(phi - plo)}}
+            others.append(build_part(plo, phi, w2, False))
+        all_parts = [(part, embed)] + [(p, False) for p in others]
+        sw = plan_windows(n_seqs, prompt, cfg["max_ctx"], min(400, steps_run), min(40, warmup_run), queue)[1]
+        alone = [{"layers": list(wl["parts"][0]), "tokens_per_s": main_run["tokens_per_s"], "step_GBps": main_run["gbs"]}]
+        for (p, pe), (plo, phi) in zip(all_parts[1:], wl["parts"][1:]):
+            r = run(p, pe, prompt, sw, queue)
+            alone.append({"layers": [plo, phi], "tokens_per_s": r["tokens_per_s"], "step_GBps": r["gbs"]})
+        # all partitions, each on a stream of its own in the library's eyes (here: one stream; persistent launches
+        # of different partitions are ordered one after the other anyway), visited in ring order per round
+        wu, timed = sw[0]
+        ins = {id(p): (first_inputs(pe, prompt), step_inputs(pe)) for p, pe in all_parts}
+        buf = torch.empty((prompt, d), dtype=tdt, device=dev)
+        douts = [torch.empty((d,), dtype=tdt, device=dev) for _ in range(queue)]
+        for p, pe in all_parts:
+            for s in range(n_seqs):
+                p.seq_reset(s)
+                p.prefill(s, ins[id(p)][0][s], buf)
+
+        def ring_visit(ids):
+            for p, pe in all_parts:
+                xs = ins[id(p)][1]
+                if len(ids) == 1:
+                    p.decode_step(ids[0], xs[ids[0]], douts[0])
+                else:
+                    p.decode_steps(ids, [xs[i] for i in ids], douts[:len(ids)])
+
+        for ids in calls_of(0, wu, queue, n_seqs):
+            ring_visit(ids)
+        torch.cuda.synchronize()
+        ctx0 = part.seq_len(wu % n_seqs) + 1
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for ids in calls_of(wu, timed, queue, n_seqs):
+            ring_visit(ids)
+        e1.record()
+        for p, _ in all_parts:
+            p.sync()
+        ms = e0.elapsed_time(e1)
+        ctx_mean = (ctx0 + max(part.seq_len(s) for s in range(n_seqs))) // 2
+        agg_bytes = sum(p.step_bytes(ctx_mean) for p, _ in all_parts) * timed
+        result["all_partitions"] = {
+            "partitions": len(all_parts), "alone": alone,
+            "round_robin": {"partition_steps_per_s": len(all_parts) * timed / ms * 1e3,
+                            "model_tokens_per_s": timed / ms * 1e3, "GBps": agg_bytes / ms / 1e6,
+                            "frac_of_hbm_peak": agg_bytes / ms / 1e6 / HBM_PEAK_GBS, "steps_per_partition": timed,
+                            "context": ctx_mean},
+            "note": "partitions 2.. reuse the first partition's weight values in arenas of their own"}
+        del others, all_parts, ins
+
     if not args.no_output_layers:
         # the starter's output layers (final norm, vocabulary projection, argmax) of the same model, on a partition
         # of their own as in the paper's layout; one call per generated token
         L = cfg["n_layer"]
         hw = S.make_weights(cfg, seed, L, L, embed=False, head=True)
         hp = mdi.Partition(cfg, hw, L, L, has_head=True, max_seqs=1)
-        x = torch.randn((d,), device=dev, dtype=torch.float32).to(tdt)
+        g = torch.Generator(device=dev).manual_seed(seed + 4)
+        x = torch.randn((d,), generator=g, device=dev, dtype=torch.float32).to(tdt)
         tok = torch.empty((1,), dtype=torch.int32, device=dev)
         for _ in range(10):
             hp.sample_greedy(0, x, tok)
@@ -252,13 +399,8 @@ def main():
         result["output_layers"] = {"vocab": cfg["vocab"], "us_per_call": us, "bytes": hb, "GB/s": hb / us / 1e3,
                                    "frac_of_hbm_peak": hb / us / 1e3 / HBM_PEAK_GBS}
         del hp, hw
-    if one_run:
-        result["one_message_per_launch"] = {"ms_per_step": one_run["ms_per_step"], "tokens_per_s": one_run["tokens_per_s"],
-                                            "step_GBps": one_run["gbs"], "frac_of_hbm_peak": one_run["gbs"] / HBM_PEAK_GBS}
-    if sweep:
-        result["ctx_sweep"] = sweep
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, w, lo, hi, seed, S)
+        result["cpu_baseline"] = cpu_baseline(cfg, w, lo, hi, seed, S, prompt, embed)
     print(json.dumps(result))
 
 

@@ -20,7 +20,27 @@
  * state errors are detected on the host before anything is enqueued.
  *
  * Thread-safety: calls on one partition must be serialised by the caller;
- * different partitions share no mutable state and may be driven concurrently.
+ * different partitions may be driven concurrently from different threads and
+ * streams.
+ *
+ * Process-wide state.  Partitions share no data, with one exception that the
+ * persistent decode launch forces: that launch (one kernel for a whole decode
+ * step, used whenever the shape allows it, see decode_path) keeps one
+ * workgroup per compute unit resident (two of half the size when it carries
+ * several messages) and its workgroups wait for each other, so two such
+ * launches must never be dispatched side by side, or each could hold a part
+ * of the compute units and wait for the rest.  The library therefore keeps, per
+ * HIP device, a mutex-guarded event that orders every persistent launch after
+ * the previous one of any other partition on that device: decode steps of
+ * different partitions run one after the other even when their streams differ
+ * (first visits, output layers and the one-kernel-per-operation path are
+ * ordinary launches and do overlap).  The launch also assumes that nothing
+ * else occupies the compute units for good (another process's persistent
+ * kernel, say).  Every wait inside it is bounded: if the workgroups cannot all
+ * become resident, or an exchange never completes, the kernel gives up, the
+ * step's outputs are invalid and mdi_partition_sync reports MDI_ERR_HIP; the
+ * partition must then be destroyed (its exchange counters are no longer
+ * consistent), other partitions are unaffected.
  *
  * One tuning knob is read from the environment when a partition is created:
  * MDI_GROUP_CTX = context length from which, in models whose query heads share
@@ -92,9 +112,7 @@ typedef struct mdi_config {
   uint32_t dtype;          /* MDI_F32 | MDI_BF16                                        */
   uint32_t decode_path;    /* how a decode step is launched.  0 = automatic: one persistent kernel launch
                               when the shape allows it, else one kernel per operation; 1 = always one
-                              kernel per operation; 2 = same as 0; 3 = the persistent launch with
-                              streaming and exchange wavefronts on matrix-core tiles (keeps a second,
-                              tiled copy of the layer matrices in the arena; currently the slower one) */
+                              kernel per operation; other values = 0                               */
 } mdi_config;
 
 /*
@@ -102,6 +120,8 @@ typedef struct mdi_config {
  * in_features]` row-major, contiguous, in cfg.dtype; vectors in binary32.
  * Pointers that do not apply (biases when has_bias == 0, ln*_b for RMSNorm,
  * w_gate for GELU MLPs) are NULL.  A NULL bias with has_bias == 1 means zero.
+ * has_bias covers the attention projections and the GELU MLP; a SwiGLU MLP
+ * carries no biases: b_up / b_down must be NULL there (MDI_ERR_ARG otherwise).
  */
 typedef struct mdi_layer_weights {
   const void *ln1_g, *ln1_b; /* [d] pre-attention norm                                  */
@@ -124,8 +144,11 @@ typedef struct mdi_weights {
 } mdi_weights;
 
 /*
- * Size in bytes of the device arena a partition needs (packed weights, KV page
- * pool, page tables, scratch).  arena_bytes: host pointer, written on MDI_OK.
+ * Size in bytes of the device arena a partition needs: the node's model chunk
+ * (Sec. III-B: the layers it was assigned, plus embedding / output layers on
+ * the starter), one KV cache per sample in flight (Sec. III-D; the paper's
+ * memory tables, Sec. IV-C, count exactly these per node), page tables and
+ * scratch.  arena_bytes: host pointer, written on MDI_OK.
  */
 MDI_API mdi_status mdi_partition_bytes(const mdi_config *cfg, uint32_t layer_lo, uint32_t layer_hi,
                                uint32_t flags, size_t *arena_bytes);
@@ -248,10 +271,19 @@ MDI_API mdi_status mdi_sample_topk(mdi_partition *part, uint32_t seq_id, const v
  */
 MDI_API mdi_status mdi_partition_sync(mdi_partition *part);
 
-/* Drop sample seq_id's cache (its pages return to the pool); it may be prefilled again. */
+/*
+ * Back to "the n-th KV cache is None" (Alg. 2): drop sample seq_id's cache, its
+ * pages return to the pool, and its next message must be a first visit again.
+ * The caller orders this after the work that still reads the cache (same stream
+ * or a wait); nothing is enqueued.
+ */
 MDI_API mdi_status mdi_seq_reset(mdi_partition *part, uint32_t seq_id);
 
-/* Tokens currently cached for seq_id (0 = no cache yet).  len: host pointer. */
+/*
+ * Tokens currently cached for seq_id, i.e. the position the next message of
+ * that sample takes (Sec. III-E: a message carries only the sample id, the node
+ * keeps count); 0 = no cache yet (Alg. 2).  len: host pointer.
+ */
 MDI_API mdi_status mdi_seq_len(const mdi_partition *part, uint32_t seq_id, uint32_t *len);
 
 /*
@@ -277,9 +309,10 @@ MDI_API mdi_status mdi_time_kernel(mdi_partition *part, int which, uint32_t reps
                                    uint64_t *bytes_per_launch);
 
 /*
- * Introspection.  what: 0 = decode path in use (0 persistent single launch,
- * 1 one kernel per operation), 1 = workgroups of the persistent kernel,
- * 2 = its LDS bytes per workgroup, 3 = arena bytes in use.  value: host pointer.
+ * Introspection.  what: 0 = decode path in use (2 = persistent single launch,
+ * 1 = one kernel per operation), 1 = workgroups in one set of the persistent
+ * launch (0 on the other path), 2 = its LDS bytes per workgroup (0 likewise),
+ * 3 = arena bytes in use.  value: host pointer.
  */
 MDI_API mdi_status mdi_partition_info(const mdi_partition *part, uint32_t what, uint64_t *value);
 
@@ -297,7 +330,12 @@ MDI_API mdi_status mdi_partition_info(const mdi_partition *part, uint32_t what, 
  */
 MDI_API mdi_status mdi_partition_trace(mdi_partition *part, void *trace);
 
-/* Frees the host object; the arena stays with the caller. */
+/*
+ * The node leaves the ring (the starter's stop message of Sec. III-A ends a
+ * secondary's loop, Alg. 2): frees the host object.  Nothing is enqueued and
+ * nothing waited for: the caller drains the partition's stream first
+ * (mdi_partition_sync) and keeps the arena, which stays its own.
+ */
 MDI_API void mdi_partition_destroy(mdi_partition *part);
 
 MDI_API const char *mdi_strerror(mdi_status st);

@@ -22,8 +22,9 @@ Pins (tests/test_oracle_*.py): softmax rows sum to 1; attention against
 explicit triple loops; causality; GQA == MHA with repeated kv heads; cached
 decode == full-prefix recompute; composed partitions == unsplit model;
 interleaved samples == each sample alone; norm/RoPE/activation closed forms;
-identity layer when the output matrices vanish; Alg. 1/2 visit counts; the
-counter-based generator against its published known answers; the sampler
+identity layer when the output matrices vanish; the output layers (final norm,
+then the vocabulary projection, tied and untied) against scalar loops;
+Alg. 1/2 visit counts; the counter-based generator against its published known answers; the sampler
 against the distribution it is defined to draw from.
 Whole-model numeric values are "parity unpinned" by the paper: it prints no
 logits or tokens and its trained weights are not available.

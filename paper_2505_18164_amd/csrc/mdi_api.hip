@@ -16,7 +16,6 @@ namespace {
 struct LayerPacked {
   const float *ln1_g = nullptr, *ln1_b = nullptr, *ln2_g = nullptr, *ln2_b = nullptr;
   const void *wqkv = nullptr, *wo = nullptr, *wup = nullptr, *wdown = nullptr;
-  const void *wqkv_t = nullptr, *wo_t = nullptr, *wup_t = nullptr, *wdown_t = nullptr;   // the same in 16-row tiles (decode)
   const float *bqkv = nullptr, *bo = nullptr, *bup = nullptr, *bdown = nullptr;
   char* kv = nullptr;  // this layer's pages: [page][K][2][pt][h]
 };
@@ -85,13 +84,7 @@ struct mdi_partition {
     unsigned epoch = 0;
   } sc[kMaxSlots];
   int n_cu = 0;
-  // persistent decode step with specialised wavefronts
-  bool use_step2 = false;
-  bool tiled = false;                  // the arena holds tiled copies of the layer matrices
-  StepLayer s2_l0{};                   // first layer's pointers for step2.hip (tiled matrices)
-  int s2_S = 0, s2_E = 0;
-  size_t s2_lds = 0;
-  int s2_tab = 0, s2_own = 0, s2_part = 0, s2_xs = 0, s2_xraw = 0, s2_rec = 0, s2_gain = 0, s2_part_floats = 0;
+  int device = 0;         // HIP device the partition was created on (index into the per-device launch chain)
 };
 
 namespace {
@@ -141,12 +134,6 @@ size_t carve(mdi_partition* p, void* arena) {
     if (c.has_bias && !swiglu) L.bup = (float*)cv.take(F * 4);
     L.wdown = cv.take(d * F * B);
     if (c.has_bias && !swiglu) L.bdown = (float*)cv.take(d * 4);
-    if (p->tiled) {
-      L.wqkv_t = cv.take(tiled_bytes(c.dtype, nqkv, d));
-      L.wo_t = cv.take(tiled_bytes(c.dtype, d, H * h));
-      L.wup_t = cv.take(tiled_bytes(c.dtype, nup, d));
-      L.wdown_t = cv.take(tiled_bytes(c.dtype, d, F));
-    }
   }
   const bool embed = p->flags & MDI_HAS_EMBED, head = p->flags & MDI_HAS_HEAD;
   if (embed || (head && c.tie_embed)) p->wte = cv.take(V * d * B);
@@ -219,7 +206,6 @@ void init_geometry(mdi_partition* p, const mdi_config* cfg, uint32_t lo, uint32_
   p->pages_per_seq = ((int)cfg->max_ctx + p->pt - 1) / p->pt;
   p->n_pages = cfg->kv_pages ? (int)cfg->kv_pages : (int)cfg->max_seqs * p->pages_per_seq;
   p->Tm = cfg->max_prefill ? (int)cfg->max_prefill : (int)cfg->max_ctx;
-  p->tiled = p->n_local > 0 && cfg->decode_path == 3;
 }
 
 // Decides whether a decode step runs as one persistent launch and sizes its LDS.
@@ -252,63 +238,31 @@ void plan_step(mdi_partition* p, int n_cu) {
   p->use_step = true;
 }
 
-// Same decision for the kernel with streaming and exchange wavefronts (step2.hip); lays out its LDS.
-void plan_step2(mdi_partition* p, int n_cu) {
-  const mdi_config& c = p->cfg;
-  p->use_step2 = false;
-  if (!p->tiled || n_cu <= 0) return;
-  const int H = c.n_head, K = c.n_kv_head, h = c.head_dim, d = c.d_model, F = c.d_ff;
-  const int group = H / K;
-  p->G = group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;      // query heads that share one pass over their kv head's cache
-  step2_shape(p->G, &p->s2_S, &p->s2_E);
-  const int S = p->s2_S;
-  p->n_hg = H / p->G;
-  p->nwg = std::min(n_cu, 1024);
-  if (p->n_hg > p->nwg) return;
-  const int nup = c.mlp_kind == MDI_MLP_SWIGLU ? 2 * F : F;
-  const long rows[4] = {(long)(H + 2 * K) * h, d, nup, d};
-  const long cols[4] = {d, (long)H * h, d, F};
-  const int KT = c.dtype == MDI_BF16 ? 32 : 16;                      // columns per tile
-  long nb_max = 0, kpad_max = 0;
-  for (int j = 0; j < 4; ++j) {
-    const long nblk = (rows[j] + 15) / 16;
-    nb_max = std::max(nb_max, (nblk + p->nwg - 1) / p->nwg);
-    kpad_max = std::max(kpad_max, (cols[j] + KT - 1) / KT * KT);
-  }
-  const long nb_d = ((d + 15) / 16 + p->nwg - 1) / p->nwg;
-  auto up4 = [](long v) { return (int)((v + 3) & ~3L); };
-  p->s2_tab = kStep2HeaderWords;
-  p->s2_own = up4(p->s2_tab + p->pages_per_seq);
-  p->s2_part = up4(p->s2_own + 16 * nb_d);
-  p->s2_part_floats = up4(nb_max * S * 16);
-  p->s2_xs = p->s2_part + p->s2_part_floats;
-  const int xs_words = up4(std::max<long>(kpad_max * p->esz / 4, (long)p->G * h + 2 * h));
-  p->s2_xraw = p->s2_xs + xs_words;
-  p->s2_rec = p->s2_xraw + up4(d);
-  p->s2_gain = p->s2_rec + up4((long)(S + 1) * p->G * (h + 2));
-  p->s2_lds = (size_t)(p->s2_gain + up4(d) * (c.norm_kind == MDI_NORM_LAYERNORM ? 2 : 1)) * sizeof(float);
-  if (p->s2_lds > 160 * 1024) return;
-  if (p->s2_lds > 64 * 1024 && !step2_allow_lds(c.dtype, p->G, p->s2_lds)) return;
-  p->use_step2 = true;
-}
-
-// Persistent kernels of different partitions must not be co-scheduled (each wants every
-// compute unit for its barriers), so their launches are chained with an event per process.
-std::mutex g_step_mutex;
-hipEvent_t g_step_event = nullptr;
-hipStream_t g_step_stream = nullptr;
+// The one piece of state that partitions share (see mdi.h, "Process-wide state").  A persistent launch needs
+// every one of its workgroups resident at once; two such launches dispatched side by side from different
+// streams could each be given a part of the compute units and wait for the rest for ever (their bounded
+// waits would turn that into MDI_ERR_HIP).  So, per device, an event orders a partition's persistent launch
+// after the previous one of any other partition.
+constexpr int kMaxDevices = 64;
+struct LaunchChain {
+  std::mutex mutex;
+  hipEvent_t event = nullptr;
+  hipStream_t stream = nullptr;       // the stream of the launch `event` was recorded after
+};
+LaunchChain g_chain[kMaxDevices];
 
 template <typename Launch>
 mdi_status launch_step_serialised(mdi_partition* p, Launch&& launch) {
-  std::lock_guard<std::mutex> lock(g_step_mutex);
-  if (!g_step_event) {
-    if (hipEventCreateWithFlags(&g_step_event, hipEventDisableTiming) != hipSuccess) return MDI_ERR_HIP;
-  } else if (g_step_stream != p->stream) {
-    if (hipStreamWaitEvent(p->stream, g_step_event, 0) != hipSuccess) return MDI_ERR_HIP;
+  LaunchChain& ch = g_chain[p->device];
+  std::lock_guard<std::mutex> lock(ch.mutex);
+  if (!ch.event) {
+    if (hipEventCreateWithFlags(&ch.event, hipEventDisableTiming) != hipSuccess) return MDI_ERR_HIP;
+  } else if (ch.stream != p->stream) {
+    if (hipStreamWaitEvent(p->stream, ch.event, 0) != hipSuccess) return MDI_ERR_HIP;
   }
   launch();
-  if (hipEventRecord(g_step_event, p->stream) != hipSuccess) return MDI_ERR_HIP;
-  g_step_stream = p->stream;
+  if (hipEventRecord(ch.event, p->stream) != hipSuccess) return MDI_ERR_HIP;
+  ch.stream = p->stream;
   return MDI_OK;
 }
 
@@ -351,6 +305,7 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
     const mdi_layer_weights& s = w->layers[i];
     if (!s.ln1_g || !s.ln2_g || !s.wq || !s.wk || !s.wv || !s.wo || !s.w_up || !s.w_down) return MDI_ERR_ARG;
     if (swiglu && !s.w_gate) return MDI_ERR_ARG;
+    if (swiglu && (s.b_up || s.b_down)) return MDI_ERR_ARG;   // a SwiGLU MLP carries no biases here: refuse rather than drop them
   }
   mdi_partition* p = new (std::nothrow) mdi_partition();
   if (!p) return MDI_ERR_NOMEM;
@@ -385,12 +340,6 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
       put_rows(p, s.w_up, L.wup, F, d, B);
     }
     put_rows(p, s.w_down, L.wdown, d, F, B);
-    if (p->tiled) {
-      launch_pack_tiles(p->stream, c.dtype, L.wqkv, const_cast<void*>(L.wqkv_t), (int)((H + 2 * K) * h), (int)d, (int)h);
-      launch_pack_tiles(p->stream, c.dtype, L.wo, const_cast<void*>(L.wo_t), (int)d, (int)(H * h), 0);
-      launch_pack_tiles(p->stream, c.dtype, L.wup, const_cast<void*>(L.wup_t), (int)(swiglu ? 2 * F : F), (int)d, 0);
-      launch_pack_tiles(p->stream, c.dtype, L.wdown, const_cast<void*>(L.wdown_t), (int)d, (int)F, 0);
-    }
     if (c.has_bias) {
       float* bq = (float*)L.bqkv;
       launch_fill_f32(p->stream, bq, (H + 2 * K) * h, 0.f);
@@ -420,9 +369,10 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
   if (p->n_local) {
     int dev = 0, n_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n_cu = 0;
+    if (dev < 0 || dev >= kMaxDevices) { delete p; return MDI_ERR_ARG; }
     p->n_cu = n_cu;
-    plan_step2(p, n_cu);
-    if (!p->use_step2) plan_step(p, n_cu);
+    p->device = dev;
+    plan_step(p, n_cu);
     launch_fill_u32(p->stream, p->bar_flags, 1024, 1u);     // phase counters start at 1: tag 0 marks "never written"
     p->epoch = 1;
     launch_fill_u32(p->stream, (uint32_t*)p->t_xres, 2 * d, 0u);
@@ -450,10 +400,6 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
       const LayerPacked& L = p->layers[i];
       p->h_step_layers[i] = StepLayer{L.wqkv, L.wo, L.wup, L.wdown, L.bqkv, L.bo, L.bup, L.bdown,
                                       L.ln1_g, L.ln1_b, L.ln2_g, L.ln2_b, L.kv};
-    }
-    {
-      const LayerPacked& L = p->layers[0];
-      p->s2_l0 = StepLayer{L.wqkv_t, L.wo_t, L.wup_t, L.wdown_t, L.bqkv, L.bo, L.bup, L.bdown, L.ln1_g, L.ln1_b, L.ln2_g, L.ln2_b, L.kv};
     }
     if (hipMemcpyAsync(p->d_step_layers, p->h_step_layers.data(), p->n_local * sizeof(StepLayer), hipMemcpyHostToDevice, p->stream) != hipSuccess) {
       delete p;
@@ -685,36 +631,6 @@ mdi_status mdi_decode_step(mdi_partition* p, uint32_t seq, const void* act_in, v
   const int d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff;
   const int ak = act_kind(c);
   const bool embed = p->flags & MDI_HAS_EMBED, swiglu = c.mlp_kind == MDI_MLP_SWIGLU;
-  if (p->use_step2) {
-    Step2Args a{};
-    a.l0 = p->s2_l0;
-    a.w_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].wqkv - (const char*)p->h_step_layers[0].wqkv : 0;
-    a.kv_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].kv - (const char*)p->h_step_layers[0].kv : 0;
-    a.n_layer = p->n_local;
-    a.d = d; a.H = H; a.K = K; a.h = h; a.F = F; a.pt = p->pt; a.pt_h = (long)p->pt * h;
-    a.norm_kind = c.norm_kind; a.mlp_kind = c.mlp_kind; a.eps = c.norm_eps;
-    a.in = act_in; a.in_kind = embed ? IN_TOKEN : ak; a.wte = p->wte; a.wpe = p->wpe; a.vocab = (int)c.vocab;
-    a.pos = len; a.ctx = ctx;
-    a.rope = p->rope ? p->rope + (size_t)len * (h / 2) : nullptr;
-    a.table = drow; a.n_tab = (len + p->pt - 1) / p->pt; a.table_entry = new_entry; a.new_page = page;
-    a.kv_tok_off = (long)page * K * 2 * a.pt_h + (long)slot * h;
-    a.xres = p->t_xres; a.q = p->t_q; a.o = p->t_o; a.u = p->t_u; a.part = p->t_part; a.knew = p->t_knew;
-    a.tickets = p->tickets; a.flags = p->bar_flags; a.epoch0 = p->epoch; a.err = p->err; a.spin_limit = 1 << 21;
-    a.n_hg = p->n_hg;
-    const int max_splits = std::max(1, std::min(kMaxSplits, p->nwg / p->n_hg));
-    int chunk = (ctx + max_splits - 1) / max_splits;
-    chunk = (chunk + 15) / 16 * 16;
-    a.chunk = chunk; a.n_splits = (ctx + chunk - 1) / chunk;
-    a.scale = 1.f / sqrtf((float)h);
-    a.act_out = act_out; a.act_kind = ak;
-    a.lds_tab = p->s2_tab; a.lds_own = p->s2_own; a.lds_part = p->s2_part; a.lds_xs = p->s2_xs; a.lds_xraw = p->s2_xraw;
-    a.lds_rec = p->s2_rec; a.lds_gain = p->s2_gain; a.part_floats = p->s2_part_floats; a.trace = p->trace;
-    const mdi_status st = launch_step_serialised(p, [&]() { launch_step2(p->stream, p->cfg.dtype, p->G, p->nwg, p->s2_lds, a); });
-    if (st != MDI_OK) return st;
-    p->epoch += 5u * (unsigned)p->n_local;
-    p->seq_len[seq] = (uint32_t)ctx;
-    return hip_status();
-  }
   if (p->use_step) {
     const mdi_status st = launch_messages(p, 1, &seq, &mp, &act_in, &act_out);
     return st != MDI_OK ? st : hip_status();
@@ -808,22 +724,26 @@ mdi_status mdi_decode_steps(mdi_partition* p, uint32_t n, const uint32_t* seqs, 
 }
 
 namespace {
+// Scratch of the output layers' kernels: per-workgroup argmax candidates and the arrival counter.
+struct HeadScratch { float* amax_val; int* amax_idx; unsigned* counter; };
+
 // final norm + vocabulary projection + greedy argmax; logits (optional) go to `logits`
-void launch_head(mdi_partition* p, const void* act_in, int32_t* token_out, float* logits) {
+void launch_head(mdi_partition* p, const void* act_in, int32_t* token_out, float* logits, const HeadScratch& hs) {
   const mdi_config& c = p->cfg;
   if (p->head_nwg) {
     LogitsArgs a{p->lm_head, (int)c.vocab, (int)c.d_model, act_in, act_kind(c), (int)c.norm_kind, p->lnf_g, p->lnf_b, c.norm_eps,
-                 logits, p->amax_val, p->amax_idx, p->counters + c.n_head, token_out, p->head_part_floats};
+                 logits, hs.amax_val, hs.amax_idx, hs.counter, token_out, p->head_part_floats};
     launch_logits(p->stream, c.dtype, p->head_nwg, p->head_lds, a);
     return;
   }
   GemvArgs a{};
   a.W = p->lm_head; a.N = (int)c.vocab; a.Kd = (int)c.d_model;
   a.x = act_in; a.x_kind = act_kind(c); a.norm_kind = c.norm_kind; a.g = p->lnf_g; a.b = p->lnf_b; a.eps = c.norm_eps;
-  a.out = logits; a.amax_val = p->amax_val; a.amax_idx = p->amax_idx;
-  a.counter = p->counters + c.n_head; a.token_out = token_out;
+  a.out = logits; a.amax_val = hs.amax_val; a.amax_idx = hs.amax_idx;
+  a.counter = hs.counter; a.token_out = token_out;
   launch_gemv(p->stream, c.dtype, PRO_NORM, EPI_LOGITS, a);
 }
+HeadScratch arena_head_scratch(const mdi_partition* p) { return HeadScratch{p->amax_val, p->amax_idx, p->counters + p->cfg.n_head}; }
 }  // namespace
 
 mdi_status mdi_sample_greedy(mdi_partition* p, uint32_t seq, const void* act_in, int32_t* token_out, float* logits_out) {
@@ -831,7 +751,7 @@ mdi_status mdi_sample_greedy(mdi_partition* p, uint32_t seq, const void* act_in,
   if (!(p->flags & MDI_HAS_HEAD)) return MDI_ERR_STATE;
   const mdi_config& c = p->cfg;
   if (seq >= c.max_seqs) return MDI_ERR_ARG;
-  launch_head(p, act_in, token_out, logits_out);
+  launch_head(p, act_in, token_out, logits_out, arena_head_scratch(p));
   return hip_status();
 }
 
@@ -841,7 +761,7 @@ mdi_status mdi_sample_topk(mdi_partition* p, uint32_t seq, const void* act_in, f
   if (!(p->flags & MDI_HAS_HEAD)) return MDI_ERR_STATE;
   const mdi_config& c = p->cfg;
   if (seq >= c.max_seqs || !(temperature > 0.f) || !top_k || top_k > (uint32_t)kMaxTopK) return MDI_ERR_ARG;
-  launch_head(p, act_in, token_out, p->logits);
+  launch_head(p, act_in, token_out, p->logits, arena_head_scratch(p));
   if (logits_out && hipMemcpyAsync(logits_out, p->logits, (size_t)c.vocab * 4, hipMemcpyDeviceToDevice, p->stream) != hipSuccess)
     return MDI_ERR_HIP;
   SampleArgs sa{p->logits, (int)c.vocab, (int)std::min<uint32_t>(top_k, c.vocab), 1.f / temperature, seq, step,
@@ -938,9 +858,9 @@ mdi_status mdi_time_kernel(mdi_partition* p, int which, uint32_t reps, float* av
 mdi_status mdi_partition_info(const mdi_partition* p, uint32_t what, uint64_t* value) {
   if (!p || !value) return MDI_ERR_ARG;
   switch (what) {
-    case 0: *value = p->use_step2 ? 3 : p->use_step ? 2 : 1; return MDI_OK;
-    case 1: *value = p->use_step2 || p->use_step ? (uint64_t)p->nwg : 0; return MDI_OK;
-    case 2: *value = p->use_step2 ? (uint64_t)p->s2_lds : p->use_step ? (uint64_t)p->step_lds : 0; return MDI_OK;
+    case 0: *value = p->use_step ? 2 : 1; return MDI_OK;
+    case 1: *value = p->use_step ? (uint64_t)p->nwg : 0; return MDI_OK;
+    case 2: *value = p->use_step ? (uint64_t)p->step_lds : 0; return MDI_OK;
     case 3: *value = p->arena_bytes; return MDI_OK;
     default: return MDI_ERR_ARG;
   }

@@ -211,38 +211,6 @@ struct LogitsArgs {
 };
 void launch_logits(hipStream_t s, int dtype, int nwg, size_t lds_bytes, const LogitsArgs& a);
 
-// ---- whole decode step as one persistent launch, specialised wavefronts (step2.hip) ----------
-struct Step2Args {
-  StepLayer l0;                      // first local layer; layer i's pointers are these advanced by i strides
-  long w_stride, kv_stride;          // bytes between consecutive layers' packed weights / page pools
-  int n_layer;
-  int d, H, K, h, F, pt; long pt_h;
-  int norm_kind, mlp_kind; float eps;
-  const void* in; int in_kind; const void* wte; const void* wpe;
-  int pos, ctx;                      // position of the new token, context length including it
-  const float2* rope;                // (cos, sin)[h/2] of `pos`, or nullptr
-  int vocab;
-  const int32_t* table; int n_tab;   // the sample's page ids; entries [0, n_tab) cover positions < pos
-  int32_t* table_entry; int new_page;
-  long kv_tok_off;                   // element offset of K[kv head 0][slot] of the new token inside a layer's pool
-  // vectors exchanged between workgroups inside the launch: every element is (float bits, phase counter) in 8 bytes
-  tagged_t *xres, *q, *o, *u, *part, *knew;   // [d], [H*h], [H*h], [F], [H][kMaxSplits][h+2], [2][K*h]
-  unsigned *tickets, *flags; unsigned epoch0; int* err; int spin_limit;
-  int n_hg, n_splits, chunk; float scale;
-  void* act_out; int act_kind;
-  int lds_tab, lds_own, lds_part, lds_xs, lds_xraw, lds_rec, lds_gain;   // LDS layout, in 4-byte words
-  int part_floats;
-  unsigned long long* trace;         // optional [workgroup][n_layer][5][8] timestamps (100 MHz ticks), or nullptr
-};
-constexpr int kStep2HeaderWords = 96 + 240;
-// Matrices in the layout step2.hip streams: tiles of 16 rows x 1 KiB in matrix-core operand order, rows in
-// pair order (pairs (i, i + rope_h/2) inside heads of rope_h rows when rope_h > 0, else (2p, 2p + 1)).
-size_t tiled_bytes(int dtype, long N, long Kd);
-void launch_pack_tiles(hipStream_t s, int dtype, const void* src, void* dst, int N, int Kd, int rope_h);
-void step2_shape(int G, int* S, int* E);                  // streaming / exchange wavefronts per workgroup for GQA group size G
-bool step2_allow_lds(int dtype, int G, size_t lds_bytes);
-void launch_step2(hipStream_t s, int dtype, int G, int nwg, size_t lds_bytes, const Step2Args& a);
-
 // ---- set-up ---------------------------------------------------------------
 void launch_rope_table(hipStream_t s, float2* table, int max_ctx, int h, double base);
 // dst[r*dst_stride_rows + ...]: copy `rows` rows of `cols` elements, dst row = r*row_mul + row_off

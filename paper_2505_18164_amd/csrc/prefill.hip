@@ -500,44 +500,6 @@ void launch_copy_rows(hipStream_t s, int elem_bytes, const void* src, void* dst,
     hipLaunchKernelGGL(k_copy_rows<uint32_t>, dim3(blocks), dim3(256), 0, s, (const uint32_t*)src, (uint32_t*)dst, rows, cols, row_mul, row_off);
 }
 
-// Row-major [N, Kd] -> tiles of 16 rows x 1 KiB for the persistent decode kernel: piece `lane` (16 bytes)
-// of tile (block, kt) holds row 16 * block + lane % 16 of the pair-ordered matrix, elements
-// [kt * 4V + V * (lane / 16), + V).  Rows and columns beyond the matrix are zero.
-template <typename T, int V>
-__global__ void k_pack_tiles(const T* src, T* dst, int N, int Kd, int n_kt, int rope_h, long pieces) {
-  for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < pieces; idx += (long)gridDim.x * blockDim.x) {
-    const int lane = (int)(idx & 63);
-    const long tile = idx >> 6;
-    const int kt = (int)(tile % n_kt);
-    const long blk = tile / n_kt;
-    const long pr = blk * 16 + (lane & 15);
-    long row = pr;
-    if (rope_h) {
-      const long p = pr >> 1, half = rope_h >> 1;
-      row = (p / half) * rope_h + (p % half) + (pr & 1) * half;
-    }
-    const int k0 = kt * 4 * V + (lane >> 4) * V;
-#pragma unroll
-    for (int e = 0; e < V; ++e)
-      dst[idx * V + e] = (row < N && k0 + e < Kd) ? src[row * Kd + k0 + e] : (T)0;
-  }
-}
-size_t tiled_bytes(int dtype, long N, long Kd) {
-  const long V = dtype == MDI_BF16 ? 8 : 4;
-  const long n_kt = (Kd + 4 * V - 1) / (4 * V), nblk = (N + 15) / 16;
-  return (size_t)(nblk * n_kt) * 1024;
-}
-void launch_pack_tiles(hipStream_t s, int dtype, const void* src, void* dst, int N, int Kd, int rope_h) {
-  const int V = dtype == MDI_BF16 ? 8 : 4;
-  const int n_kt = (Kd + 4 * V - 1) / (4 * V);
-  const long pieces = (long)((N + 15) / 16) * n_kt * 64;
-  const int blocks = (int)std::min<long>((pieces + 255) / 256, 8192);
-  if (dtype == MDI_BF16)
-    hipLaunchKernelGGL((k_pack_tiles<uint16_t, 8>), dim3(blocks), dim3(256), 0, s, (const uint16_t*)src, (uint16_t*)dst, N, Kd, n_kt, rope_h, pieces);
-  else
-    hipLaunchKernelGGL((k_pack_tiles<uint32_t, 4>), dim3(blocks), dim3(256), 0, s, (const uint32_t*)src, (uint32_t*)dst, N, Kd, n_kt, rope_h, pieces);
-}
-
 __global__ void k_fill_u32(uint32_t* dst, long n, uint32_t v) {
   for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (long)gridDim.x * blockDim.x) dst[idx] = v;
 }

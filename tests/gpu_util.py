@@ -44,12 +44,28 @@ def pair(cfg, w, lo, hi, embed=False, head=False, max_seqs=1, **kw):
     return o, g
 
 
+def rel_l2_rows(got, want):
+    """Relative L2 error of every row (position) of a [T, d] result."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    return np.linalg.norm(got - want, axis=-1) / np.linalg.norm(want, axis=-1)
+
+
 def check(got, want, cfg, what, bar=None):
-    """Assert the parity bar with a short message (no array dumps)."""
-    err = rel_l2(host(got) if isinstance(got, torch.Tensor) else got, want)
+    """Assert the parity bar with a short message (no array dumps).  A [T, d] result must meet the bar in EVERY
+    row as well as over the whole tensor: one wrong row among thousands would vanish in the overall norm."""
+    got = host(got) if isinstance(got, torch.Tensor) else np.asarray(got)
+    want = np.asarray(want)
+    err = rel_l2(got, want)
     bar = tol(cfg) if bar is None else bar
     if not err < bar:
         raise AssertionError(f"{what}: rel-L2 {err:.3e} exceeds {bar:.1e}")
+    if want.ndim == 2 and want.shape[0] > 1:
+        rows = rel_l2_rows(got.reshape(want.shape), want)
+        worst = int(np.argmax(rows))
+        if not rows[worst] < bar:
+            raise AssertionError(f"{what}: row {worst} of {want.shape[0]} has rel-L2 {rows[worst]:.3e}, exceeds {bar:.1e}")
+        err = max(err, float(rows[worst]))
     return err
 
 

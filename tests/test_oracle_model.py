@@ -270,3 +270,65 @@ def test_first_visit_in_pieces_equals_the_whole_first_visit(variant):
     one, other = O.Partition(cfg, w, 0, 3, has_embed=True), O.Partition(cfg, w, 0, 3, has_embed=True)
     one.prefill(0, ids[:5]); other.prefill(0, ids[:5])
     assert np.array_equal(one.prefill_chunk(0, ids[5:6])[0], other.decode_step(0, int(ids[5])))
+
+
+# ------------------------------------------------------------ output layers
+@pytest.mark.parametrize("tie", [0, 1], ids=["untied", "tied"])
+@pytest.mark.parametrize("norm_kind", [S.NORM_LAYERNORM, S.NORM_RMSNORM], ids=["layernorm", "rmsnorm"])
+def test_output_layers_against_scalar_loops(norm_kind, tie):
+    """The starter's output portion (Sec. III-B "final layers", Alg. 1 "process output layers"): final norm of the
+    last block's output, THEN the vocabulary projection, with the matrix taken row per token ([V, d]; the
+    embedding matrix itself when tied).  Written out with Python floats; gains and biases are non-trivial and the
+    matrix is not square, so a missing norm, the block norm's gain in place of the final one, a dropped bias or a
+    transposed matrix all change the numbers."""
+    cfg = S.tiny(n_layer=1, norm_kind=norm_kind, tie_embed=tie, d_model=8, n_head=2, n_kv_head=1, head_dim=4, d_ff=16,
+                 vocab=13, pos_kind=S.POS_LEARNED if norm_kind == S.NORM_LAYERNORM else S.POS_ROPE)
+    w = S.make_weights(cfg, 41, exercise=True)
+    w["wte"] = w["wte"] * 20.0
+    if tie:
+        w["lm_head"] = w["wte"]
+    else:
+        w["lm_head"] = w["lm_head"] * 20.0
+    d, V, eps = cfg["d_model"], cfg["vocab"], cfg["norm_eps"]
+    rng = np.random.default_rng(3)
+    xs = rng.normal(size=(3, d)) * 2.0 + 0.7                 # non-zero mean: LayerNorm's centring matters
+    g = [float(v) for v in w["lnf_g"]]
+    b = [float(v) for v in w["lnf_b"]] if norm_kind == S.NORM_LAYERNORM else None
+    M = [[float(v) for v in row] for row in (w["wte"] if tie else w["lm_head"])]
+    want = []
+    for x in xs:
+        x = [float(v) for v in x]
+        if norm_kind == S.NORM_LAYERNORM:
+            mu = sum(x) / d
+            var = sum((v - mu) ** 2 for v in x) / d
+            xn = [(x[i] - mu) / math.sqrt(var + eps) * g[i] + b[i] for i in range(d)]
+        else:
+            ms = sum(v * v for v in x) / d
+            xn = [x[i] / math.sqrt(ms + eps) * g[i] for i in range(d)]
+        want.append([sum(M[t][i] * xn[i] for i in range(d)) for t in range(V)])
+    want = np.array(want)
+    got = O.head_logits(cfg, O._cast_tree({k: v for k, v in w.items() if k != "layers"}, np.float64), xs)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    # the same through a partition, row by row, and the token it yields
+    p = O.Partition(cfg, w, 1, 1, has_head=True)
+    for x, row in zip(xs, want):
+        np.testing.assert_allclose(p.logits(x), row, rtol=1e-12, atol=1e-12)
+        assert p.sample_greedy(x)[0] == max(range(V), key=lambda t: (row[t], -t))
+    # what the plausible mistakes would give is far from it (the pin can tell them apart)
+    no_norm = np.array([[sum(M[t][i] * float(x[i]) for i in range(d)) for t in range(V)] for x in xs])
+    assert np.abs(no_norm - want).max() > 1e-2
+    if norm_kind == S.NORM_LAYERNORM:
+        no_bias = want - np.array([[sum(M[t][i] * b[i] for i in range(d)) for t in range(V)]] * 3)
+        assert np.abs(no_bias - want).max() > 1e-3
+
+
+def test_output_layers_use_the_final_norm_not_a_block_norm():
+    """A wrong gain vector (a block's pre-MLP gain instead of the final one) must change the logits."""
+    cfg = S.tiny(n_layer=1, d_model=8, n_head=2, n_kv_head=1, head_dim=4, d_ff=16, vocab=13)
+    w = S.make_weights(cfg, 43, exercise=True)
+    x = np.linspace(-1.0, 2.0, cfg["d_model"])
+    p = O.Partition(cfg, w, 1, 1, has_head=True)
+    ms = float((x * x).mean())
+    xn = x / math.sqrt(ms + cfg["norm_eps"]) * w["lnf_g"].astype(np.float64)
+    np.testing.assert_allclose(p.logits(x), w["lm_head"].astype(np.float64) @ xn, rtol=1e-12, atol=1e-14)
+    assert not np.allclose(w["lnf_g"], w["layers"][0]["ln2_g"])

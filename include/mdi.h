@@ -69,7 +69,8 @@ typedef enum {
   MDI_ERR_STATE = -2, /* decode before the first visit, prefill of a live sequence     */
   MDI_ERR_CTX = -3,   /* the call would grow a sequence beyond max_ctx                 */
   MDI_ERR_NOMEM = -4, /* arena too small, or the KV page pool is exhausted             */
-  MDI_ERR_HIP = -5    /* a HIP runtime call or kernel launch reported an error         */
+  MDI_ERR_HIP = -5,   /* a HIP runtime call or kernel launch reported an error         */
+  MDI_ERR_LIMIT = -6  /* mdi_sample_topk_static: vocabulary beyond its fixed scratch   */
 } mdi_status;
 
 enum { MDI_NORM_LAYERNORM = 0, MDI_NORM_RMSNORM = 1 };
@@ -258,6 +259,26 @@ MDI_API mdi_status mdi_sample_greedy(mdi_partition *part, uint32_t seq_id, const
 MDI_API mdi_status mdi_sample_topk(mdi_partition *part, uint32_t seq_id, const void *act_in,
                            float temperature, uint32_t top_k, uint64_t seed, uint32_t step,
                            int32_t *token_out, float *logits_out);
+
+/*
+ * mdi_sample_topk for callers that cannot allocate device memory or hand the
+ * library any: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  Same arguments, same result (token and logits are
+ * bit-identical to mdi_sample_topk's; top_k = 1 gives the greedy token), but
+ * the kernels' scratch - the [V] float logits the sampler works on, the
+ * per-workgroup argmax candidates and the arrival counter - is not taken from
+ * the partition's arena: it lives in a fixed array inside the library
+ * (1 MiB + 8.25 KiB of device memory per GPU, held until the process ends).
+ * The call allocates and frees nothing and records no memset (the counter is
+ * cleared by a small fill kernel).  Limit: vocab <= 262144, else MDI_ERR_LIMIT.
+ * All calls on one GPU share the array: calls that overlap on a GPU (different
+ * streams, different partitions, different threads) race; the caller orders
+ * them.  Other errors as mdi_sample_topk; MDI_ERR_STATE also when the
+ * partition's device is not the current one on the array's first use.
+ */
+MDI_API mdi_status mdi_sample_topk_static(mdi_partition *part, uint32_t seq_id, const void *act_in,
+                                  float temperature, uint32_t top_k, uint64_t seed, uint32_t step,
+                                  int32_t *token_out, float *logits_out);
 
 /*
  * Wait for everything enqueued on the partition's stream and report errors that

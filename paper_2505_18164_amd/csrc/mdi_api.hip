@@ -266,6 +266,35 @@ mdi_status launch_step_serialised(mdi_partition* p, Launch&& launch) {
   return MDI_OK;
 }
 
+// Scratch of mdi_sample_topk_static, the entry point for callers that cannot allocate: a [V] float logits buffer
+// for vocabularies up to kStaticVocabMax, the per-workgroup argmax candidates and the arrival counter.  One copy
+// per GPU, held until the process ends; its device address is taken once per device and kept.
+constexpr size_t kStaticVocabMax = 262144;
+constexpr size_t kStaticCand = 1024;                       // workgroups of the output-layer launch, at most
+constexpr size_t kStaticLogitsOff = 0;
+constexpr size_t kStaticValOff = kStaticVocabMax * 4;
+constexpr size_t kStaticIdxOff = kStaticValOff + kStaticCand * 4;
+constexpr size_t kStaticCounterOff = kStaticIdxOff + kStaticCand * 4;
+constexpr size_t kStaticScratchBytes = kStaticCounterOff + 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices];                 // device address of `scratch` on each GPU (nullptr: not taken yet)
+
+// `device` must be the current device: the symbol's address is that of the current device's copy.
+mdi_status static_scratch(int device, unsigned char** out) {
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess) return MDI_ERR_HIP;
+    if (cur != device) return MDI_ERR_STATE;
+    unsigned char* ptr = nullptr;
+    if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MDI_ERR_HIP;
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return MDI_OK;
+}
+
 // device-to-device copy of a [rows, cols] matrix into rows r*mul + off of dst
 void put_rows(mdi_partition* p, const void* src, const void* dst, size_t rows, size_t cols, int esz, long mul = 1, long off = 0) {
   if (!src || !dst) return;
@@ -405,6 +434,16 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
       delete p;
       return MDI_ERR_HIP;
     }
+  }
+  if (head) {
+    // the static scratch of mdi_sample_topk_static: its address on this device is taken here, once, so that the
+    // entry point itself only reads it
+    int dev = 0;
+    unsigned char* unused = nullptr;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { delete p; return MDI_ERR_HIP; }
+    p->device = dev;
+    const mdi_status sst = static_scratch(dev, &unused);
+    if (sst != MDI_OK) { delete p; return sst; }
   }
   if (head && c.decode_path != 1) {
     // the output layers as one streaming launch when the activation and the pair partials fit in LDS
@@ -770,6 +809,31 @@ mdi_status mdi_sample_topk(mdi_partition* p, uint32_t seq, const void* act_in, f
   return hip_status();
 }
 
+mdi_status mdi_sample_topk_static(mdi_partition* p, uint32_t seq, const void* act_in, float temperature, uint32_t top_k,
+                                  uint64_t seed, uint32_t step, int32_t* token_out, float* logits_out) {
+  if (!p || !act_in || !token_out) return MDI_ERR_ARG;
+  if (!(p->flags & MDI_HAS_HEAD)) return MDI_ERR_STATE;
+  const mdi_config& c = p->cfg;
+  if (seq >= c.max_seqs || !(temperature > 0.f) || !top_k || top_k > (uint32_t)kMaxTopK) return MDI_ERR_ARG;
+  if ((size_t)c.vocab > kStaticVocabMax) return MDI_ERR_LIMIT;
+  const int nwg = p->head_nwg ? p->head_nwg : gemv_grid((int)c.vocab);
+  if ((size_t)nwg > kStaticCand) return MDI_ERR_LIMIT;
+  unsigned char* base = nullptr;
+  const mdi_status sst = static_scratch(p->device, &base);   // taken at create; here only read
+  if (sst != MDI_OK) return sst;
+  float* logits = (float*)(base + kStaticLogitsOff);
+  const HeadScratch hs{(float*)(base + kStaticValOff), (int*)(base + kStaticIdxOff), (unsigned*)(base + kStaticCounterOff)};
+  // the array keeps the last call's contents: the arrival counter must start at zero (a fill kernel, not a
+  // memset node, so that the call can be captured into a graph); everything else is written before it is read
+  launch_fill_u32(p->stream, hs.counter, 1, 0u);
+  launch_head(p, act_in, token_out, logits, hs);
+  if (logits_out) launch_copy_rows(p->stream, 4, logits, logits_out, 1, (long)c.vocab, 1, 0);
+  SampleArgs sa{logits, (int)c.vocab, (int)std::min<uint32_t>(top_k, c.vocab), 1.f / temperature, seq, step,
+                (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), token_out};
+  launch_sample_topk(p->stream, sa);
+  return hip_status();
+}
+
 mdi_status mdi_partition_sync(mdi_partition* p) {
   if (!p) return MDI_ERR_ARG;
   if (hipStreamSynchronize(p->stream) != hipSuccess) return MDI_ERR_HIP;
@@ -882,6 +946,7 @@ const char* mdi_strerror(mdi_status st) {
     case MDI_ERR_CTX: return "context length exceeded";
     case MDI_ERR_NOMEM: return "arena too small or KV page pool exhausted";
     case MDI_ERR_HIP: return "HIP runtime error";
+    case MDI_ERR_LIMIT: return "size beyond the fixed scratch of the entry point that allocates nothing";
   }
   return "unknown status";
 }

@@ -14,12 +14,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmdi.so")
 
 MDI_ABI_VERSION = 1
-MDI_OK, MDI_ERR_ARG, MDI_ERR_STATE, MDI_ERR_CTX, MDI_ERR_NOMEM, MDI_ERR_HIP = 0, -1, -2, -3, -4, -5
+MDI_OK, MDI_ERR_ARG, MDI_ERR_STATE, MDI_ERR_CTX, MDI_ERR_NOMEM, MDI_ERR_HIP, MDI_ERR_LIMIT = 0, -1, -2, -3, -4, -5, -6
 MDI_F32, MDI_BF16 = 0, 1
 MDI_HAS_EMBED, MDI_HAS_HEAD = 1, 2
 
 EXPORTS = ["mdi_partition_bytes", "mdi_partition_create", "mdi_prefill", "mdi_prefill_chunk", "mdi_decode_step", "mdi_decode_steps",
-           "mdi_sample_greedy", "mdi_sample_topk", "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel",
+           "mdi_sample_greedy", "mdi_sample_topk", "mdi_sample_topk_static", "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel",
            "mdi_partition_info", "mdi_partition_trace", "mdi_partition_destroy", "mdi_strerror"]
 
 
@@ -69,6 +69,7 @@ def lib():
         L.mdi_decode_steps.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(vp), C.POINTER(vp)]
         L.mdi_sample_greedy.argtypes = [vp, u32, vp, vp, vp]
         L.mdi_sample_topk.argtypes = [vp, u32, vp, C.c_float, u32, C.c_uint64, u32, vp, vp]
+        L.mdi_sample_topk_static.argtypes = [vp, u32, vp, C.c_float, u32, C.c_uint64, u32, vp, vp]
         L.mdi_partition_sync.argtypes = [vp]
         L.mdi_seq_reset.argtypes = [vp, u32]
         L.mdi_seq_len.argtypes = [vp, u32, C.POINTER(u32)]
@@ -80,7 +81,7 @@ def lib():
         L.mdi_partition_destroy.restype = None
         L.mdi_strerror.argtypes = [C.c_int]
         L.mdi_strerror.restype = C.c_char_p
-        for name in EXPORTS[:15]:
+        for name in EXPORTS[:16]:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -249,6 +250,16 @@ class Partition:
         st = lib().mdi_sample_topk(self._h, seq, _ptr(act_in), temperature, top_k, seed, step, _ptr(token_out), _ptr(logits_out))
         if st != MDI_OK:
             raise MdiError(st, "mdi_sample_topk")
+        return token_out
+
+    def sample_topk_static(self, seq, act_in, temperature, top_k, seed, step, token_out=None, logits_out=None):
+        """mdi_sample_topk with the kernels' scratch in the library's fixed array; token_out must be passed by
+        callers that may not allocate."""
+        if token_out is None:
+            token_out = torch.empty((1,), dtype=torch.int32, device=self.device)
+        st = lib().mdi_sample_topk_static(self._h, seq, _ptr(act_in), temperature, top_k, seed, step, _ptr(token_out), _ptr(logits_out))
+        if st != MDI_OK:
+            raise MdiError(st, "mdi_sample_topk_static")
         return token_out
 
     # -- bookkeeping --------------------------------------------------------

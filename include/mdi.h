@@ -233,6 +233,27 @@ MDI_API mdi_status mdi_decode_steps(mdi_partition *part, uint32_t n, const uint3
                             const void *const *acts_in, void *const *acts_out);
 
 /*
+ * Later visits of n different samples whose messages wait in the input queue
+ * (Sec. III-A, III-C), taken through the local layers TOGETHER: one pass over
+ * the layer weights serves up to 16 messages (each weight is fetched once and
+ * multiplied with all their vectors on the matrix cores), attention runs per
+ * sample over each sample's own cache (Sec. III-D).  This goes beyond the
+ * paper's one-message-at-a-time rule: the traffic of a pass is the weights
+ * once plus every sample's cache, instead of the weights once per message.
+ * More than 16 messages take several passes; a lone message is forwarded as
+ * by mdi_decode_step.  Needs bf16 storage, RMSNorm, the persistent decode
+ * path and d_model, n_head * head_dim, d_ff multiples of 32 (d_model at most
+ * 4096); other partitions forward the messages as mdi_decode_steps does
+ * (mdi_partition_info(4) tells).  Vectors between the matrix products are
+ * rounded to bf16 here (as in a first visit), so a sample's result agrees with
+ * mdi_decode_step's within the bf16 parity bar, not to the last bits; for a
+ * given call pattern results are reproducible bit for bit.
+ * Arguments and errors: as mdi_decode_steps.
+ */
+MDI_API mdi_status mdi_decode_batch(mdi_partition *part, uint32_t n, const uint32_t *seq_ids,
+                            const void *const *acts_in, void *const *acts_out);
+
+/*
  * Output layers (Alg. 1 "process output layers ... get token", with greedy
  * argmax in place of sampling): final norm, vocabulary projection, argmax
  * (lowest index on exact ties).  Needs MDI_HAS_HEAD; touches no KV state.
@@ -333,7 +354,9 @@ MDI_API mdi_status mdi_time_kernel(mdi_partition *part, int which, uint32_t reps
  * Introspection.  what: 0 = decode path in use (2 = persistent single launch,
  * 1 = one kernel per operation), 1 = workgroups in one set of the persistent
  * launch (0 on the other path), 2 = its LDS bytes per workgroup (0 likewise),
- * 3 = arena bytes in use.  value: host pointer.
+ * 3 = arena bytes in use, 4 = messages one pass of mdi_decode_batch can take
+ * (0: this partition forwards them one pass each), 5 = bytes of the local
+ * layers' matrices (what one pass over the weights reads).  value: host pointer.
  */
 MDI_API mdi_status mdi_partition_info(const mdi_partition *part, uint32_t what, uint64_t *value);
 

@@ -83,6 +83,17 @@ struct mdi_partition {
     unsigned *flags = nullptr, *tickets = nullptr;
     unsigned epoch = 0;
   } sc[kMaxSlots];
+  // decode of several queued messages with one pass over the weights (step_batch.h)
+  bool batch_region = false;           // the arena holds the exchange region of that launch (bf16 storage, RMSNorm)
+  bool use_batch = false;              // ... and the shape allows the launch on this device
+  char* b_slot0 = nullptr; size_t b_stride = 0;
+  size_t b_off_xn = 0, b_off_q = 0, b_off_ob = 0, b_off_ub = 0, b_off_part = 0, b_off_knew = 0, b_off_tickets = 0;
+  tagged_t* b_ssq = nullptr;
+  unsigned* b_flags = nullptr;
+  unsigned b_epoch = 0;
+  int b_R[4] = {16, 16, 16, 16};
+  int b_lds_xres = 0, b_lds_sq = 0, b_lds_part = 0;
+  size_t b_lds = 0;
   int n_cu = 0;
   int device = 0;         // HIP device the partition was created on (index into the per-device launch chain)
 };
@@ -180,6 +191,24 @@ size_t carve(mdi_partition* p, void* arena) {
       sc.part = (tagged_t*)cv.take(H * kMaxSplits * (h + 2) * 8);
       sc.knew = (tagged_t*)cv.take(2 * K * h * 8);
     }
+    p->batch_region = c.dtype == MDI_BF16 && c.norm_kind == MDI_NORM_RMSNORM;
+    if (p->batch_region) {
+      // one block per message of a batched launch, all laid out alike, so that message j's vectors are message
+      // 0's advanced by j strides
+      size_t off = 0;
+      auto sub = [&off](size_t bytes) { const size_t at = off; off = (off + bytes + 255) & ~(size_t)255; return at; };
+      p->b_off_xn = sub(d / 2 * 8);
+      p->b_off_q = sub(H * h * 8);
+      p->b_off_ob = sub(H * h / 2 * 8);
+      p->b_off_ub = sub(F / 2 * 8);
+      p->b_off_part = sub(H * kMaxSplits * (h + 2) * 8);
+      p->b_off_knew = sub(2 * K * h * 8);
+      p->b_off_tickets = sub(H * 4);
+      p->b_stride = off;
+      p->b_slot0 = (char*)cv.take(p->b_stride * kMaxBatch);
+      p->b_ssq = (tagged_t*)cv.take((size_t)kMaxBatch * 1024 * 8);
+      p->b_flags = (unsigned*)cv.take(1024 * 4);
+    }
     const size_t T = p->Tm;
     p->p_xres = (float*)cv.take(T * d * 4);
     p->p_xn = cv.take(T * d * B);
@@ -236,6 +265,40 @@ void plan_step(mdi_partition* p, int n_cu) {
   p->step_lds = (size_t)(128 + p->part_floats + xs) * sizeof(float);
   if (p->step_lds > 64 * 1024) return;
   p->use_step = true;
+}
+
+// Decides whether several queued messages can share one pass over the weights (step_batch.h) and lays out its LDS.
+void plan_batch(mdi_partition* p) {
+  const mdi_config& c = p->cfg;
+  p->use_batch = false;
+  if (!p->use_step || !p->batch_region) return;
+  const int H = c.n_head, K = c.n_kv_head, h = c.head_dim, d = c.d_model, F = c.d_ff, nwg = p->nwg;
+  if (d % 32 || (H * h) % 32 || F % 32) return;                 // a column step of the matrix instruction is 32 wide
+  if (((d / 32 + kStepWavesMax - 1) / kStepWavesMax) > 16) return;   // a wavefront keeps its slice of a d-sized vector in registers
+  const int nup = c.mlp_kind == MDI_MLP_SWIGLU ? 2 * F : F;
+  const int rows[4] = {(H + 2 * K) * h, d, nup, d};
+  int nb_max = 1, nb_d = 1;
+  for (int j = 0; j < 4; ++j) {
+    // 16 rows per block when that still gives every workgroup a block, else 8 (twice the blocks to spread)
+    int R = (rows[j] + 15) / 16 >= nwg ? 16 : 8;
+    if (j == 0 && (h / 2) % (R / 2)) R = 8;                      // a block holds R/2 rows of a half head and their partners
+    if (j == 0 && (h / 2) % (R / 2)) return;
+    if (j == 2 && c.mlp_kind == MDI_MLP_SWIGLU && rows[j] % 4) return;
+    p->b_R[j] = R;
+    const int nb = ((rows[j] + R - 1) / R + nwg - 1) / nwg;
+    nb_max = std::max(nb_max, nb);
+    if (j == 1) nb_d = nb;
+  }
+  p->b_R[3] = p->b_R[1];                                        // the two residual products own the same rows
+  p->b_lds_xres = 128;
+  p->b_lds_sq = p->b_lds_xres + nb_d * 256;
+  p->b_lds_part = p->b_lds_sq + std::max(nb_d * 128, 128);
+  const int attn_floats = std::max(p->G * h, kStepWavesMax * p->G * (h + 2)) + 64;
+  const int part_floats = std::max(nb_max * 2048, attn_floats);
+  p->b_lds = (size_t)(p->b_lds_part + part_floats) * sizeof(float);
+  if (p->b_lds > 160 * 1024) return;
+  if (p->b_lds > 64 * 1024 && !step_batch_allow_lds(p->b_lds)) return;
+  p->use_batch = true;
 }
 
 // The one piece of state that partitions share (see mdi.h, "Process-wide state").  A persistent launch needs
@@ -402,6 +465,13 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
     p->n_cu = n_cu;
     p->device = dev;
     plan_step(p, n_cu);
+    plan_batch(p);
+    if (p->batch_region) {
+      launch_fill_u32(p->stream, (uint32_t*)p->b_slot0, (long)(p->b_stride * kMaxBatch / 4), 0u);
+      launch_fill_u32(p->stream, (uint32_t*)p->b_ssq, (long)kMaxBatch * 1024 * 2, 0u);
+      launch_fill_u32(p->stream, p->b_flags, 1024, 1u);
+      p->b_epoch = 1;
+    }
     launch_fill_u32(p->stream, p->bar_flags, 1024, 1u);     // phase counters start at 1: tag 0 marks "never written"
     p->epoch = 1;
     launch_fill_u32(p->stream, (uint32_t*)p->t_xres, 2 * d, 0u);
@@ -763,6 +833,103 @@ mdi_status mdi_decode_steps(mdi_partition* p, uint32_t n, const uint32_t* seqs, 
 }
 
 namespace {
+
+// Launches one pass over the weights for n (2 .. kMaxBatch) planned messages.
+mdi_status launch_batch(mdi_partition* p, int n, const uint32_t* seqs, const MessagePlan* mp, const void* const* ins, void* const* outs) {
+  const mdi_config& c = p->cfg;
+  BatchArgs a{};
+  int ctx_max = 0;
+  long ctx_sum = 0;
+  for (int j = 0; j < n; ++j) { ctx_max = std::max(ctx_max, mp[j].ctx); ctx_sum += mp[j].ctx; }
+  const int G = step_group(p, ctx_max);
+  a.l0 = p->h_step_layers[0];
+  a.w_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].wqkv - (const char*)p->h_step_layers[0].wqkv : 0;
+  a.kv_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].kv - (const char*)p->h_step_layers[0].kv : 0;
+  a.n_layer = p->n_local;
+  a.d = c.d_model; a.H = c.n_head; a.K = c.n_kv_head; a.h = c.head_dim; a.F = c.d_ff; a.pt = p->pt;
+  a.pt_h = (long)p->pt * c.head_dim;
+  a.mlp_kind = c.mlp_kind; a.eps = c.norm_eps;
+  a.wte = p->wte; a.wpe = p->wpe; a.vocab = (int)c.vocab;
+  a.in_kind = (p->flags & MDI_HAS_EMBED) ? IN_TOKEN : act_kind(c);
+  a.act_kind = act_kind(c);
+  a.err = p->err; a.spin_limit = 1 << 21;
+  a.n_hg = (int)c.n_head / G;
+  a.scale = 1.f / sqrtf((float)c.head_dim);
+  a.nwg = p->nwg; a.m = n;
+  a.epoch0 = p->b_epoch;
+  a.slot0 = p->b_slot0; a.slot_stride = (long)p->b_stride;
+  a.off_xn = (long)p->b_off_xn; a.off_q = (long)p->b_off_q; a.off_ob = (long)p->b_off_ob; a.off_ub = (long)p->b_off_ub;
+  a.off_part = (long)p->b_off_part; a.off_knew = (long)p->b_off_knew; a.off_tickets = (long)p->b_off_tickets;
+  a.ssq = p->b_ssq; a.flags = p->b_flags;
+  for (int j = 0; j < 4; ++j) a.R[j] = p->b_R[j];
+  a.lds_xres = p->b_lds_xres; a.lds_sq = p->b_lds_sq; a.lds_part = p->b_lds_part;
+  a.trace = p->trace;
+  // Attention work items: (message, head group, context split).  Splits of about equal length over all messages,
+  // as many items as there are workgroups when the contexts allow it, no split shorter than 128 positions.
+  const long h = c.head_dim;
+  (void)h;
+  int chunk = (int)std::max<long>(128, (ctx_sum * a.n_hg + a.nwg - 1) / a.nwg);
+  chunk = (chunk + 15) / 16 * 16;
+  auto items_at = [&](int ch) { long t = 0; for (int j = 0; j < n; ++j) t += (long)a.n_hg * std::min(kMaxSplits, (mp[j].ctx + ch - 1) / ch); return t; };
+  while (items_at(chunk) > a.nwg && chunk < ctx_max) chunk += 16;
+  int item = 0;
+  for (int j = 0; j < n; ++j) {
+    BatchSlot& s = a.s[j];
+    s.in = ins[j]; s.act_out = outs[j];
+    s.pos = mp[j].len; s.ctx = mp[j].ctx;
+    s.rope = p->rope ? p->rope + (size_t)mp[j].len * (c.head_dim / 2) : nullptr;
+    s.table = mp[j].drow; s.table_entry = mp[j].new_entry; s.new_page = mp[j].page;
+    s.kv_tok_off = (long)mp[j].page * c.n_kv_head * 2 * a.pt_h + (long)mp[j].slot * c.head_dim;
+    int ch = chunk;
+    if ((mp[j].ctx + ch - 1) / ch > kMaxSplits) ch = ((mp[j].ctx + kMaxSplits - 1) / kMaxSplits + 15) / 16 * 16;
+    s.chunk = ch; s.n_splits = (mp[j].ctx + ch - 1) / ch;
+    s.item_lo = item;
+    item += a.n_hg * s.n_splits;
+  }
+  a.n_items = item;
+  const mdi_status st = launch_step_serialised(p, [&]() { launch_step_batch(p->stream, G, p->b_lds, a); });
+  if (st != MDI_OK) return st;
+  p->b_epoch += 5u * (unsigned)p->n_local;
+  for (int j = 0; j < n; ++j) p->seq_len[seqs[j]] = (uint32_t)mp[j].ctx;
+  return MDI_OK;
+}
+
+}  // namespace
+
+mdi_status mdi_decode_batch(mdi_partition* p, uint32_t n, const uint32_t* seqs, const void* const* acts_in, void* const* acts_out) {
+  if (!p || !n || !seqs || !acts_in || !acts_out || !p->n_local) return MDI_ERR_ARG;
+  if (!p->use_batch) return mdi_decode_steps(p, n, seqs, acts_in, acts_out);
+  // everything that can be refused is checked before the first message is taken, so a refusal leaves no message half done
+  size_t new_pages = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (!acts_in[i] || !acts_out[i]) return MDI_ERR_ARG;
+    const mdi_status st = check_message(p, seqs[i]);
+    if (st != MDI_OK) return st;
+    for (uint32_t k = 0; k < i; ++k)
+      if (seqs[k] == seqs[i]) return MDI_ERR_ARG;            // a sequence has one message in flight
+    if (p->seq_len[seqs[i]] % (uint32_t)p->pt == 0) ++new_pages;
+  }
+  if (new_pages > p->free_pages.size()) return MDI_ERR_NOMEM;
+  for (uint32_t i = 0; i < n;) {
+    const uint32_t m = std::min<uint32_t>(kMaxBatch, n - i);
+    if (m == 1) {
+      const mdi_status st = mdi_decode_step(p, seqs[i], acts_in[i], acts_out[i]);
+      if (st != MDI_OK) return st;
+    } else {
+      MessagePlan mp[kMaxBatch];
+      for (uint32_t k = 0; k < m; ++k) {
+        const mdi_status st = plan_message(p, seqs[i + k], &mp[k]);
+        if (st != MDI_OK) return st;
+      }
+      const mdi_status st = launch_batch(p, (int)m, seqs + i, mp, acts_in + i, acts_out + i);
+      if (st != MDI_OK) return st;
+    }
+    i += m;
+  }
+  return hip_status();
+}
+
+namespace {
 // Scratch of the output layers' kernels: per-workgroup argmax candidates and the arrival counter.
 struct HeadScratch { float* amax_val; int* amax_idx; unsigned* counter; };
 
@@ -926,6 +1093,13 @@ mdi_status mdi_partition_info(const mdi_partition* p, uint32_t what, uint64_t* v
     case 1: *value = p->use_step ? (uint64_t)p->nwg : 0; return MDI_OK;
     case 2: *value = p->use_step ? (uint64_t)p->step_lds : 0; return MDI_OK;
     case 3: *value = p->arena_bytes; return MDI_OK;
+    case 4: *value = p->use_batch ? (uint64_t)kMaxBatch : 0; return MDI_OK;
+    case 5: {
+      const mdi_config& c = p->cfg;
+      const uint64_t B = p->esz, d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff;
+      *value = (uint64_t)p->n_local * ((H + 2 * K) * h * d + d * H * h + (c.mlp_kind == MDI_MLP_SWIGLU ? 3 : 2) * d * F) * B;
+      return MDI_OK;
+    }
     default: return MDI_ERR_ARG;
   }
 }

@@ -211,6 +211,49 @@ struct LogitsArgs {
 };
 void launch_logits(hipStream_t s, int dtype, int nwg, size_t lds_bytes, const LogitsArgs& a);
 
+// ---- decode step of several queued messages with ONE pass over the weights (step_w8.hip) ----------------
+// The messages waiting in the node's input queue (Sec. III-A; several samples are in flight, Sec. III-C) are
+// taken through every layer together: a weight tile is fetched once and multiplied with all their vectors on the
+// matrix cores (the messages are the second operand's columns), attention stays per sample.
+constexpr int kMaxBatch = 16;        // messages one pass can carry: the matrix instruction's column count
+
+struct BatchSlot {                   // what belongs to one message of the launch
+  const void* in;                    // token id (int32) or activation [d] in storage dtype
+  const float2* rope;                // (cos, sin)[h/2] of its position, or nullptr
+  const int32_t* table; int32_t* table_entry;
+  void* act_out;
+  long kv_tok_off;                   // element offset of K[kv head 0][slot] of the new token inside a layer's pool
+  int pos, ctx, new_page;
+  int n_splits, chunk;               // context splits of its attention
+  int item_lo;                       // its attention work items are item_lo .. item_lo + n_hg * n_splits - 1
+};
+struct BatchArgs {
+  StepLayer l0; long w_stride, kv_stride; int n_layer;
+  int d, H, K, h, F, pt; long pt_h;
+  int mlp_kind; float eps;
+  const void* wte; const void* wpe; int vocab;
+  int in_kind, act_kind;
+  int* err; int spin_limit;          // as in StepArgs
+  int n_hg; float scale;
+  int nwg, m;                        // workgroups (one set), messages
+  unsigned epoch0;
+  // Exchange buffers: message j's are message 0's advanced by j * slot_stride bytes.  Vectors that feed a matrix
+  // product travel as pairs of bf16 with the writing phase's counter in one 8-byte word (xn: the residual stream
+  // times the gain of the norm that follows; ob: attention output; ub: MLP hidden); q, the newest K/V row and the
+  // attention partials as (float, counter) like in StepSlot.
+  char* slot0; long slot_stride;
+  long off_xn, off_q, off_ob, off_ub, off_part, off_knew, off_tickets;
+  tagged_t* ssq;                     // [kMaxBatch][nwg] per-workgroup sums of squares of the residual rows they own
+  unsigned* flags;                   // [nwg] phase counters of the workgroups
+  int R[4];                          // rows per matrix-instruction block in the QKV / output / up / down products (8 or 16)
+  int lds_xres, lds_sq, lds_part;    // LDS layout in floats
+  int n_items;                       // attention work items of the launch
+  unsigned long long* trace;         // optional [workgroup][n_layer][5][8] timestamps (100 MHz ticks), or nullptr
+  BatchSlot s[kMaxBatch];
+};
+void launch_step_batch(hipStream_t s, int G, size_t lds_bytes, const BatchArgs& a);
+bool step_batch_allow_lds(size_t lds_bytes);
+
 // ---- set-up ---------------------------------------------------------------
 void launch_rope_table(hipStream_t s, float2* table, int max_ctx, int h, double base);
 // dst[r*dst_stride_rows + ...]: copy `rows` rows of `cols` elements, dst row = r*row_mul + row_off

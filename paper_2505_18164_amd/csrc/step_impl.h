@@ -431,8 +431,8 @@ __device__ __forceinline__ int page_of(const AttnGeo& g, int tok) {
   return g.pt_sh >= 0 ? tok >> g.pt_sh : (int)__umulhi((unsigned)tok, g.pt_magic);
 }
 
-template <typename WT, int G>
-__device__ __forceinline__ AttnGeo make_attn_geo(const StepArgs& a, const StepSlot& S, int wg, int wave, int lane) {
+template <typename WT, int G, typename AR, typename SL>
+__device__ __forceinline__ AttnGeo make_attn_geo(const AR& a, const SL& S, int wg, int wave, int lane) {
   constexpr int V = Storage<WT>::kVec;
   AttnGeo g;
   g.L = a.h / V; g.tpw = 64 / g.L; g.sub = lane / g.L; g.hoff = (lane % g.L) * V;
@@ -454,7 +454,8 @@ __device__ __forceinline__ AttnGeo make_attn_geo(const StepArgs& a, const StepSl
 // Page numbers of the tokens of tile ti (slots without a token take token 0's).  The table entries of every position
 // before the newest were written by earlier launches, so they are fetched a tile pair ahead of the rows they locate:
 // a row's address then never waits for a table look-up.
-__device__ __forceinline__ void attn_pages(int (&pg)[kTile], const AttnGeo& g, const StepArgs& a, const StepSlot& S, int ti, int wave) {
+template <typename AR, typename SL>
+__device__ __forceinline__ void attn_pages(int (&pg)[kTile], const AttnGeo& g, const AR& a, const SL& S, int ti, int wave) {
   const MDI_GLOBAL int32_t* table = (const MDI_GLOBAL int32_t*)S.table;
 #pragma unroll
   for (int s = 0; s < kTile; ++s) {
@@ -467,8 +468,8 @@ __device__ __forceinline__ void attn_pages(int (&pg)[kTile], const AttnGeo& g, c
 
 // Issues exactly 2 * kTile row loads (see gemv_issue) for tile ti, whose page numbers are in pg, then asks for the
 // page numbers of the tile that goes into the same registers next; slots without a token re-read token 0.
-template <typename WT>
-__device__ __forceinline__ void attn_issue(Tile& t, int (&pg)[kTile], const AttnGeo& g, const StepArgs& a, const StepSlot& S, const void* pool_,
+template <typename WT, typename AR, typename SL>
+__device__ __forceinline__ void attn_issue(Tile& t, int (&pg)[kTile], const AttnGeo& g, const AR& a, const SL& S, const void* pool_,
                                            int ti, int wave) {
   const MDI_GLOBAL WT* pool = (const MDI_GLOBAL WT*)pool_;
 #pragma unroll
@@ -536,9 +537,9 @@ __device__ __forceinline__ void attn_compute(AttnState<WT, G>& st, const Tile& t
 }
 
 // The streaming loop of the attention phase: two tiles in flight, each multiplied while the other's rows arrive.
-template <typename WT, int G>
+template <typename WT, int G, typename AR, typename SL>
 __device__ __forceinline__ void attn_stream(AttnState<WT, G>& st, Tile& A, Tile& B, int (&pgA)[kTile], int (&pgB)[kTile], const AttnGeo& ga,
-                                            const StepArgs& a, const StepSlot& S, const void* kv, int nte, int wave, const float* xs) {
+                                            const AR& a, const SL& S, const void* kv, int nte, int wave, const float* xs) {
 #pragma nounroll
   for (int t = 0; t < nte; t += 2) {
     attn_compute<WT, G>(st, A, ga, a.h, t, wave, xs);
@@ -549,8 +550,8 @@ __device__ __forceinline__ void attn_stream(AttnState<WT, G>& st, Tile& A, Tile&
 }
 
 // queries into LDS (pre-scaled); the newest position through coherent loads
-template <typename WT, int G>
-__device__ __forceinline__ void attn_begin(AttnState<WT, G>& st, const AttnGeo& g, const StepArgs& a, const StepSlot& S, float* qs, unsigned epoch) {
+template <typename WT, int G, typename AR, typename SL>
+__device__ __forceinline__ void attn_begin(AttnState<WT, G>& st, const AttnGeo& g, const AR& a, const SL& S, float* qs, unsigned epoch) {
   constexpr int V = Storage<WT>::kVec;
 #pragma unroll
   for (int gi = 0; gi < G; ++gi) {
@@ -609,8 +610,8 @@ __device__ __forceinline__ void attn_to_lds(AttnState<WT, G>& st, const AttnGeo&
 
 // Wavefront records -> split partial (or the final output when there is one split);
 // the last workgroup of a head group to arrive folds the splits in split order.
-template <int G>
-__device__ __forceinline__ void attn_finish(const AttnGeo& g, const StepArgs& a, const StepSlot& S, const float* sm, int* s_flag, unsigned epoch) {
+template <int G, typename AR, typename SL>
+__device__ __forceinline__ void attn_finish(const AttnGeo& g, const AR& a, const SL& S, const float* sm, int* s_flag, unsigned epoch) {
   const unsigned wtag = epoch + 1;
   const int h = a.h, rec = h + 2;
   if (!g.active) return;
@@ -710,7 +711,8 @@ __device__ __forceinline__ int gemv_index(int ph) { return ph == PH_QKV ? 0 : ph
 // the first layer's advanced by i strides: no pointer has to be fetched from memory.
 template <typename T> __device__ __forceinline__ T* advance(T* p, long bytes) { return p ? (T*)((char*)p + bytes) : p; }
 __device__ __forceinline__ const void* advance(const void* p, long bytes) { return p ? (const void*)((const char*)p + bytes) : p; }
-__device__ __forceinline__ StepLayer layer_at(const StepArgs& a, int layer) {
+template <typename AR>
+__device__ __forceinline__ StepLayer layer_at(const AR& a, int layer) {
   const long w = a.w_stride * layer, kv = a.kv_stride * layer;
   StepLayer L;
   L.wqkv = advance(a.l0.wqkv, w); L.wo = advance(a.l0.wo, w); L.wup = advance(a.l0.wup, w); L.wdown = advance(a.l0.wdown, w);

@@ -18,7 +18,7 @@ MDI_OK, MDI_ERR_ARG, MDI_ERR_STATE, MDI_ERR_CTX, MDI_ERR_NOMEM, MDI_ERR_HIP, MDI
 MDI_F32, MDI_BF16 = 0, 1
 MDI_HAS_EMBED, MDI_HAS_HEAD = 1, 2
 
-EXPORTS = ["mdi_partition_bytes", "mdi_partition_create", "mdi_prefill", "mdi_prefill_chunk", "mdi_decode_step", "mdi_decode_steps",
+EXPORTS = ["mdi_partition_bytes", "mdi_partition_create", "mdi_prefill", "mdi_prefill_chunk", "mdi_decode_step", "mdi_decode_steps", "mdi_decode_batch",
            "mdi_sample_greedy", "mdi_sample_topk", "mdi_sample_topk_static", "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel",
            "mdi_partition_info", "mdi_partition_trace", "mdi_partition_destroy", "mdi_strerror"]
 
@@ -67,6 +67,7 @@ def lib():
         L.mdi_prefill_chunk.argtypes = [vp, u32, vp, u32, vp]
         L.mdi_decode_step.argtypes = [vp, u32, vp, vp]
         L.mdi_decode_steps.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(vp), C.POINTER(vp)]
+        L.mdi_decode_batch.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(vp), C.POINTER(vp)]
         L.mdi_sample_greedy.argtypes = [vp, u32, vp, vp, vp]
         L.mdi_sample_topk.argtypes = [vp, u32, vp, C.c_float, u32, C.c_uint64, u32, vp, vp]
         L.mdi_sample_topk_static.argtypes = [vp, u32, vp, C.c_float, u32, C.c_uint64, u32, vp, vp]
@@ -81,7 +82,7 @@ def lib():
         L.mdi_partition_destroy.restype = None
         L.mdi_strerror.argtypes = [C.c_int]
         L.mdi_strerror.restype = C.c_char_p
-        for name in EXPORTS[:16]:
+        for name in EXPORTS[:17]:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -234,6 +235,19 @@ class Partition:
         st = lib().mdi_decode_steps(self._h, n, ids, ins, outs)
         if st != MDI_OK:
             raise MdiError(st, "mdi_decode_steps")
+        return acts_out
+
+    def decode_batch(self, seqs, acts_in, acts_out=None):
+        """Later visits of several different samples with one pass over the weights (mdi_decode_batch)."""
+        n = len(seqs)
+        if acts_out is None:
+            acts_out = [torch.empty((self.d,), dtype=self.tdtype, device=self.device) for _ in range(n)]
+        ids = (C.c_uint32 * n)(*seqs)
+        ins = (C.c_void_p * n)(*[t.data_ptr() for t in acts_in])
+        outs = (C.c_void_p * n)(*[t.data_ptr() for t in acts_out])
+        st = lib().mdi_decode_batch(self._h, n, ids, ins, outs)
+        if st != MDI_OK:
+            raise MdiError(st, "mdi_decode_batch")
         return acts_out
 
     def sample_greedy(self, seq, act_in, token_out=None, logits_out=None):

@@ -1,0 +1,123 @@
+"""GPU parity of mdi_decode_batch: several queued messages taken through the local layers with ONE pass over the
+weights (matrix-core products over all messages, attention per sample), against the float64 oracle's one-message-
+at-a-time decode (Sec. III-D), message by message, at the bf16 bar (rel-L2 <= 2e-2 on hidden states)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mdi_oracle as O
+from paper_2505_18164_amd import mdi, synth as S
+from gpu_util import check, dev_acts, dev_ids, host, pair, rel_l2, scale_matrices, tol
+
+pytestmark = pytest.mark.gpu
+
+# shapes whose widths are multiples of 32 (what one pass over the weights needs)
+SHAPES = {
+    "gqa_h16": dict(d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96),
+    "mha_h16": dict(d_model=64, n_head=4, n_kv_head=4, head_dim=16, d_ff=96),
+    "gqa8_h8": dict(d_model=64, n_head=8, n_kv_head=1, head_dim=8, d_ff=160),
+    "h64": dict(d_model=128, n_head=2, n_kv_head=1, head_dim=64, d_ff=288),
+    "gelu_rms_bias": dict(d_model=64, n_head=4, n_kv_head=4, head_dim=16, d_ff=96, mlp_kind=S.MLP_GELU_TANH, has_bias=1),
+    "gelu_erf_learned_pos": dict(d_model=96, n_head=6, n_kv_head=2, head_dim=16, d_ff=128, mlp_kind=S.MLP_GELU_ERF,
+                                 pos_kind=S.POS_LEARNED),
+    "swiglu_attn_bias": dict(d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96, has_bias=1),
+    "wide": dict(d_model=256, n_head=4, n_kv_head=2, head_dim=64, d_ff=704),
+}
+
+
+@pytest.mark.parametrize("n_msg", [2, 5, 16])
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_batched_pass_against_the_oracle(name, n_msg):
+    cfg = S.tiny(n_layer=3, dtype=S.DT_BF16, max_ctx=64, vocab=211, **SHAPES[name])
+    w = scale_matrices(S.make_weights(cfg, 17, exercise=True), 2.0)   # every sub-layer moves the residual stream, bf16 noise stays small
+    o, g = pair(cfg, w, 0, 3, embed=True, head=False, max_seqs=n_msg, kv_page_tokens=8)
+    assert g.info(4) == 16, "this shape should take the batched pass"
+    prompts = S.make_prompts(cfg, 17, n_msg, 23)
+    for s in range(n_msg):
+        prompts[s] = prompts[s][:3 + (5 * s) % 20]                 # ragged contexts, some shorter than a page
+        check(g.prefill(s, dev_ids(prompts[s])), o.prefill(s, prompts[s]), cfg, ("prefill", s))
+    rng = np.random.default_rng(3)
+    worst = 0.0
+    for step in range(12):                                        # crosses page boundaries of 8 tokens
+        order = [int(s) for s in rng.permutation(n_msg)]
+        toks = [int(rng.integers(0, cfg["vocab"])) for _ in order]
+        outs = g.decode_batch(order, [dev_ids([t]) for t in toks])
+        for s, t, got in zip(order, toks, outs):
+            worst = max(worst, check(got, o.decode_step(s, t), cfg, ("batched decode", step, s)))
+    for s in range(n_msg):
+        assert g.seq_len(s) == len(prompts[s]) + 12
+    g.sync()
+    print(f"{name} x{n_msg}: worst rel-L2 {worst:.2e}", flush=True)
+
+
+def test_batched_pass_on_a_mid_partition_and_more_messages_than_one_pass():
+    """Activations in and out (a secondary node, Alg. 2), 19 messages = a pass of 16 and one of 3, then a lone
+    message (forwarded as by mdi_decode_step); a second partition fed the same calls reproduces the bits."""
+    cfg = S.tiny(n_layer=4, dtype=S.DT_BF16, max_ctx=48, d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96)
+    w = scale_matrices(S.make_weights(cfg, 23, exercise=True), 3.0)
+    n = 19
+    o, g = pair(cfg, w, 1, 3, max_seqs=n, kv_page_tokens=16)
+    g2 = mdi.Partition(cfg, w, 1, 3, max_seqs=n, kv_page_tokens=16)
+    for s in range(n):
+        a = S.make_activations(cfg, 23, s, 2 + s % 7)
+        check(g.prefill(s, dev_acts(a, cfg)), o.prefill(s, a), cfg, ("prefill", s))
+        g2.prefill(s, dev_acts(a, cfg))
+    for step in range(5):
+        order = list(range(n)) if step < 4 else [7]
+        xs = [S.make_activations(cfg, 23, s, 1, step=step + 1)[0] for s in order]
+        outs = g.decode_batch(order, [dev_acts(x, cfg) for x in xs])
+        outs2 = g2.decode_batch(order, [dev_acts(x, cfg) for x in xs])
+        for s, x, got, got2 in zip(order, xs, outs, outs2):
+            check(got, o.decode_step(s, x), cfg, ("batched decode", step, s))
+            assert torch.equal(got, got2), (step, s)
+    g.sync()
+    g2.sync()
+
+
+def test_shapes_that_cannot_share_a_pass_fall_back_to_one_pass_per_message():
+    for over in (dict(dtype=S.DT_F32), dict(norm_kind=S.NORM_LAYERNORM), dict(d_ff=48)):
+        cfg = S.tiny(n_layer=2, max_ctx=32, **dict(dict(dtype=S.DT_BF16, d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96), **over))
+        w = scale_matrices(S.make_weights(cfg, 5, exercise=True), 3.0)
+        o, g = pair(cfg, w, 0, 2, embed=True, max_seqs=3, kv_page_tokens=8)
+        assert g.info(4) == 0
+        prompts = S.make_prompts(cfg, 5, 3, 6)
+        for s in range(3):
+            g.prefill(s, dev_ids(prompts[s]))
+            o.prefill(s, prompts[s])
+        outs = g.decode_batch([2, 0, 1], [dev_ids([4]), dev_ids([9]), dev_ids([1])])
+        for s, t, got in zip((2, 0, 1), (4, 9, 1), outs):
+            check(got, o.decode_step(s, t), cfg, ("fallback", s))
+        g.sync()
+
+
+def test_batched_pass_error_paths():
+    cfg = S.tiny(n_layer=1, dtype=S.DT_BF16, max_ctx=16, d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96)
+    w = S.make_weights(cfg, 3)
+    g = mdi.Partition(cfg, w, 0, 1, has_embed=True, max_seqs=3, kv_page_tokens=8, kv_pages=3)
+    ids = dev_ids(np.arange(8))
+    g.prefill(0, ids)
+    g.prefill(1, ids)
+    t = dev_ids([1])
+    for seqs, status in (([0, 0], mdi.MDI_ERR_ARG), ([0, 2], mdi.MDI_ERR_STATE), ([0, 7], mdi.MDI_ERR_ARG)):
+        with pytest.raises(mdi.MdiError) as e:
+            g.decode_batch(seqs, [t, t])
+        assert e.value.status == status
+        assert g.seq_len(0) == 8 and g.seq_len(1) == 8          # a refused call advances no sample
+    with pytest.raises(mdi.MdiError) as e:                       # both need a new page, one is left
+        g.decode_batch([0, 1], [t, t])
+    assert e.value.status == mdi.MDI_ERR_NOMEM and g.seq_len(0) == 8
+    g.sync()
+
+
+def test_token_id_out_of_range_in_a_batched_pass_is_reported():
+    cfg = S.tiny(n_layer=2, dtype=S.DT_BF16, max_ctx=32, d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96)
+    w = S.make_weights(cfg, 5)
+    g = mdi.Partition(cfg, w, 0, 2, has_embed=True, max_seqs=2)
+    good = dev_ids(np.arange(4))
+    g.prefill(0, good)
+    g.prefill(1, good)
+    g.sync()
+    g.decode_batch([0, 1], [dev_ids([3]), dev_ids([cfg["vocab"]])])
+    with pytest.raises(mdi.MdiError) as e:
+        g.sync()
+    assert e.value.status == mdi.MDI_ERR_ARG

@@ -40,7 +40,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the decode kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this script, keyed by
 # (workload, messages per launch, batched arithmetic).  A figure is only reported while the kernel sources still
 # hash to what they were when it was measured; otherwise `roofline.traffic` is null.
-KERNEL_SOURCES = ("step_impl.h", "step_w4.hip", "step_w8.hip", "device_utils.h", "mdi_internal.h")
+KERNEL_SOURCES = ("step_impl.h", "step_batch.h", "step_w4.hip", "step_w8.hip", "device_utils.h", "mdi_internal.h")
 MEASURED_TRAFFIC = {}
 
 
@@ -73,6 +73,10 @@ def parse(argv=None):
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--decode-path", type=int, default=0, help="0 = automatic (persistent single-launch step), 1 = one kernel per operation")
+    ap.add_argument("--passes", choices=["auto", "shared", "per-message"], default="auto",
+                    help="how the messages of one call take the weights: 'shared' = one pass over the weights for all "
+                         "of them (mdi_decode_batch), 'per-message' = a pass each (mdi_decode_steps, the paper's rule "
+                         "inside one launch), 'auto' = shared where the partition supports it")
     ap.add_argument("--queue", type=int, default=0,
                     help="messages of different samples handed to the partition per call: 0 = all samples in flight "
                          "(mdi_decode_steps drains the queue), 1 = one at a time (mdi_decode_step)")
@@ -189,9 +193,9 @@ def main():
         g = torch.Generator(device=dev).manual_seed(seed + 3)
         return [torch.randn((d,), generator=g, device=dev, dtype=torch.float32).to(tdt) for _ in range(n_seqs)]
 
-    def run(p, p_embed, T, wins, q):
+    def run(p, p_embed, T, wins, q, shared=False):
         """Per window: first visits of all samples at T tokens (timed separately), warm-up steps, then the timed
-        steps, q messages per call.  Returns rates over all windows."""
+        steps, q messages per call (shared: one pass over the weights per call).  Returns rates over all windows."""
         ins = first_inputs(p_embed, T)
         outs = [torch.empty((T, d), dtype=tdt, device=dev) for _ in range(n_seqs)]
         xs = step_inputs(p_embed)
@@ -206,6 +210,8 @@ def main():
         def visit(ids):
             if len(ids) == 1:
                 p.decode_step(ids[0], xs[ids[0]], douts[0])
+            elif shared:
+                p.decode_batch(ids, [xs[i] for i in ids], douts[:len(ids)])
             else:
                 p.decode_steps(ids, [xs[i] for i in ids], douts[:len(ids)])
 
@@ -238,7 +244,12 @@ def main():
             ctx_sum += 0.5 * (ctx_first + ctx_last) * timed
         ms = total_ms / total_steps
         ctx_mean = int(round(ctx_sum / total_steps))
-        nbytes = p.step_bytes(ctx_mean)
+        # algorithmic bytes: every message reads its sample's cache and writes its row; the layer matrices are read
+        # once per message, or once per call when the call's messages share a pass
+        total_bytes = total_steps * p.step_bytes(ctx_mean)
+        if shared:
+            total_bytes -= (total_steps - launches) * p.info(5)
+        nbytes = total_bytes / total_steps
         return dict(ctx=ctx_mean, ms_per_step=ms, tokens_per_s=1000.0 / ms, bytes_per_step=nbytes,
                     gbs=nbytes / ms / 1e6, prefill_ms=prefill_ms, launches=launches, steps=total_steps,
                     avg_launch_us=total_ms * 1e3 / launches)
@@ -251,7 +262,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    main_run = run(part, embed, prompt, windows, queue)
+    shared = queue > 1 and part.info(4) > 0 and args.passes != "per-message"
+    if args.passes == "shared" and not shared:
+        print("bench.py: this partition cannot share a pass over the weights among messages; timing a pass per message",
+              file=sys.stderr)
+    main_run = run(part, embed, prompt, windows, queue, shared)
     n_local = hi - lo
     params = sum(a * b for a, b in S.layer_tensor_shapes(cfg).values())
     prefill_flops = n_local * (2.0 * prompt * params + 2.0 * prompt * prompt * cfg["n_head"] * cfg["head_dim"])
@@ -261,24 +276,30 @@ def main():
     path_kind = part.info(0)          # 2 = persistent launch, 1 = one kernel per operation
     persistent = path_kind == 2
     side = not args.no_side_runs
-    # the paper's own rule, one message at a time, next to the queue-draining figure
-    one_run = None
+    # next to it: the same calls with a pass over the weights per message, and the paper's own rule, one message
+    # at a time
+    one_run, per_msg_run = None, None
     if side and queue > 1:
         _, one_w = plan_windows(n_seqs, prompt, cfg["max_ctx"], min(400, steps_run), min(40, warmup_run), 1)
         one_run = run(part, embed, prompt, one_w, 1)
+        if shared:
+            _, pm_w = plan_windows(n_seqs, prompt, cfg["max_ctx"], min(800, steps_run), min(40, warmup_run), queue)
+            per_msg_run = run(part, embed, prompt, pm_w, queue, False)
     kernels = {}
     if persistent:
         # the whole step is one kernel launch; its mean duration over the timed region (HIP events on the
         # partition's stream, launches back to back) against the bytes the launch must move
         in_launch = main_run["steps"] / main_run["launches"]          # messages a launch carried on average
-        traffic, traffic_src = measured_traffic(args.workload, queue, False)
-        roofline = {"bound": "hbm", "kernel": f"k_step (persistent decode launch, all layers, {queue} message(s) per launch)",
+        traffic, traffic_src = measured_traffic(args.workload, queue, shared)
+        kname = (f"k_step_batch (persistent decode launch, all layers, {queue} messages share one pass over the weights)" if shared
+                 else f"k_step (persistent decode launch, all layers, {queue} message(s) per launch, a pass over the weights each)")
+        roofline = {"bound": "hbm", "kernel": kname,
                     "achieved": main_run["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": main_run["gbs"] / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
                     "avg_launch_us": main_run["avg_launch_us"],
                     "bytes_per_launch": main_run["bytes_per_step"] * in_launch, "messages_per_launch": in_launch,
                     "launches_timed": main_run["launches"],
-                    "workgroups": part.info(1) * (2 if queue > 1 else 1), "lds_bytes": part.info(2),
+                    "workgroups": part.info(1) * (2 if queue > 1 and not shared else 1),
                     "kernel_rev": kernel_rev()}
     else:
         # dominant kernel: the MLP up(+gate) projection GEMV, timed with HIP events inside the library
@@ -294,7 +315,7 @@ def main():
     if args.ctx_sweep:
         sweep = []
         for T in (prompt + wl["n_new"] // 2, prompt + wl["n_new"] - 8 - -(-440 // n_seqs)):   # 440 = timed + warm-up steps
-            r = run(part, embed, T, [(40, 400)], queue)
+            r = run(part, embed, T, [(40, 400)], queue, shared)
             sweep.append({k: r[k] for k in ("ctx", "ms_per_step", "tokens_per_s", "gbs")})
 
     result = {
@@ -304,6 +325,7 @@ def main():
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": wl["name"], "layers": [lo, hi], "seqs_in_flight": n_seqs, "prompt": prompt,
                    "context_during_timing": main_run["ctx"], "kv_page_tokens": 64, "messages_per_call": queue,
+                   "weight_passes": "one per call (mdi_decode_batch)" if shared else "one per message",
                    "timed_windows": len(windows), "requested": {"steps": args.steps, "warmup": args.warmup},
                    "decode_path": {2: "persistent", 1: "per_op"}[path_kind]},
         "step_bytes": main_run["bytes_per_step"], "step_GBps": main_run["gbs"],
@@ -318,6 +340,10 @@ def main():
         result["one_message_per_launch"] = {"ms_per_step": one_run["ms_per_step"], "tokens_per_s": one_run["tokens_per_s"],
                                             "step_GBps": one_run["gbs"], "frac_of_hbm_peak": one_run["gbs"] / HBM_PEAK_GBS,
                                             "steps": one_run["steps"]}
+    if per_msg_run:
+        result["one_pass_per_message"] = {"ms_per_step": per_msg_run["ms_per_step"], "tokens_per_s": per_msg_run["tokens_per_s"],
+                                          "step_GBps": per_msg_run["gbs"], "frac_of_hbm_peak": per_msg_run["gbs"] / HBM_PEAK_GBS,
+                                          "steps": per_msg_run["steps"]}
     if sweep:
         result["ctx_sweep"] = sweep
 
@@ -332,7 +358,7 @@ def main():
         sw = plan_windows(n_seqs, prompt, cfg["max_ctx"], min(400, steps_run), min(40, warmup_run), queue)[1]
         alone = [{"layers": list(wl["parts"][0]), "tokens_per_s": main_run["tokens_per_s"], "step_GBps": main_run["gbs"]}]
         for (p, pe), (plo, phi) in zip(all_parts[1:], wl["parts"][1:]):
-            r = run(p, pe, prompt, sw, queue)
+            r = run(p, pe, prompt, sw, queue, shared)
             alone.append({"layers": [plo, phi], "tokens_per_s": r["tokens_per_s"], "step_GBps": r["gbs"]})
         # all partitions, each on a stream of its own in the library's eyes (here: one stream; persistent launches
         # of different partitions are ordered one after the other anyway), visited in ring order per round
@@ -350,9 +376,12 @@ def main():
                 xs = ins[id(p)][1]
                 if len(ids) == 1:
                     p.decode_step(ids[0], xs[ids[0]], douts[0])
+                elif shared:
+                    p.decode_batch(ids, [xs[i] for i in ids], douts[:len(ids)])
                 else:
                     p.decode_steps(ids, [xs[i] for i in ids], douts[:len(ids)])
 
+        n_calls = len(calls_of(wu, timed, queue, n_seqs))
         for ids in calls_of(0, wu, queue, n_seqs):
             ring_visit(ids)
         torch.cuda.synchronize()
@@ -366,7 +395,7 @@ def main():
             p.sync()
         ms = e0.elapsed_time(e1)
         ctx_mean = (ctx0 + max(part.seq_len(s) for s in range(n_seqs))) // 2
-        agg_bytes = sum(p.step_bytes(ctx_mean) for p, _ in all_parts) * timed
+        agg_bytes = sum(p.step_bytes(ctx_mean) * timed - ((timed - n_calls) * p.info(5) if shared else 0) for p, _ in all_parts)
         result["all_partitions"] = {
             "partitions": len(all_parts), "alone": alone,
             "round_robin": {"partition_steps_per_s": len(all_parts) * timed / ms * 1e3,

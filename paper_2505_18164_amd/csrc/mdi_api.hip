@@ -87,7 +87,9 @@ struct mdi_partition {
   bool batch_region = false;           // the arena holds the exchange region of that launch (bf16 storage, RMSNorm)
   bool use_batch = false;              // ... and the shape allows the launch on this device
   char* b_slot0 = nullptr; size_t b_stride = 0;
-  size_t b_off_xn = 0, b_off_q = 0, b_off_ob = 0, b_off_ub = 0, b_off_part = 0, b_off_knew = 0, b_off_tickets = 0;
+  size_t b_off_q = 0, b_off_part = 0, b_off_knew = 0, b_off_tickets = 0;
+  tagged_t *b_xn = nullptr, *b_ob = nullptr, *b_ub = nullptr;   // [pair of columns][kMaxBatch messages]
+  size_t b_vec_words = 0;
   tagged_t* b_ssq = nullptr;
   unsigned* b_flags = nullptr;
   unsigned b_epoch = 0;
@@ -197,15 +199,16 @@ size_t carve(mdi_partition* p, void* arena) {
       // 0's advanced by j strides
       size_t off = 0;
       auto sub = [&off](size_t bytes) { const size_t at = off; off = (off + bytes + 255) & ~(size_t)255; return at; };
-      p->b_off_xn = sub(d / 2 * 8);
       p->b_off_q = sub(H * h * 8);
-      p->b_off_ob = sub(H * h / 2 * 8);
-      p->b_off_ub = sub(F / 2 * 8);
       p->b_off_part = sub(H * kMaxSplits * (h + 2) * 8);
       p->b_off_knew = sub(2 * K * h * 8);
       p->b_off_tickets = sub(H * 4);
       p->b_stride = off;
       p->b_slot0 = (char*)cv.take(p->b_stride * kMaxBatch);
+      p->b_vec_words = (d / 2 + H * h / 2 + F / 2) * (size_t)kMaxBatch;
+      p->b_xn = (tagged_t*)cv.take(p->b_vec_words * 8);
+      p->b_ob = p->b_xn ? p->b_xn + d / 2 * kMaxBatch : nullptr;
+      p->b_ub = p->b_xn ? p->b_ob + H * h / 2 * kMaxBatch : nullptr;
       p->b_ssq = (tagged_t*)cv.take((size_t)kMaxBatch * 1024 * 8);
       p->b_flags = (unsigned*)cv.take(1024 * 4);
     }
@@ -279,7 +282,9 @@ void plan_batch(mdi_partition* p) {
   const int rows[4] = {(H + 2 * K) * h, d, nup, d};
   int nb_max = 1, nb_d = 1;
   for (int j = 0; j < 4; ++j) {
-    // 16 rows per block when that still gives every workgroup a block, else 8 (twice the blocks to spread)
+    // 16 rows per block when that gives every workgroup a block, else 8 (twice the blocks to spread).  Measured on
+    // the 7B shape's gate/up product (1376 blocks of 16 over 256 workgroups: 5 or 6 each): blocks of 8 balance better
+    // (10 or 11 each) but every load and matrix instruction then carries half the rows, and the phase took twice as long.
     int R = (rows[j] + 15) / 16 >= nwg ? 16 : 8;
     if (j == 0 && (h / 2) % (R / 2)) R = 8;                      // a block holds R/2 rows of a half head and their partners
     if (j == 0 && (h / 2) % (R / 2)) return;
@@ -468,6 +473,7 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
     plan_batch(p);
     if (p->batch_region) {
       launch_fill_u32(p->stream, (uint32_t*)p->b_slot0, (long)(p->b_stride * kMaxBatch / 4), 0u);
+      launch_fill_u32(p->stream, (uint32_t*)p->b_xn, (long)p->b_vec_words * 2, 0u);
       launch_fill_u32(p->stream, (uint32_t*)p->b_ssq, (long)kMaxBatch * 1024 * 2, 0u);
       launch_fill_u32(p->stream, p->b_flags, 1024, 1u);
       p->b_epoch = 1;
@@ -841,7 +847,9 @@ mdi_status launch_batch(mdi_partition* p, int n, const uint32_t* seqs, const Mes
   int ctx_max = 0;
   long ctx_sum = 0;
   for (int j = 0; j < n; ++j) { ctx_max = std::max(ctx_max, mp[j].ctx); ctx_sum += mp[j].ctx; }
-  const int G = step_group(p, ctx_max);
+  // Query heads per attention work item: pairs also when one head per item would give more items than workgroups
+  // (every message brings n_head of them), so that a workgroup has one item and a kv head's cache is read half as often.
+  const int G = (ctx_max >= p->group_ctx || n * (int)c.n_head > p->nwg) ? p->G : 1;
   a.l0 = p->h_step_layers[0];
   a.w_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].wqkv - (const char*)p->h_step_layers[0].wqkv : 0;
   a.kv_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].kv - (const char*)p->h_step_layers[0].kv : 0;
@@ -857,9 +865,9 @@ mdi_status launch_batch(mdi_partition* p, int n, const uint32_t* seqs, const Mes
   a.scale = 1.f / sqrtf((float)c.head_dim);
   a.nwg = p->nwg; a.m = n;
   a.epoch0 = p->b_epoch;
+  a.xn = p->b_xn; a.ob = p->b_ob; a.ub = p->b_ub;
   a.slot0 = p->b_slot0; a.slot_stride = (long)p->b_stride;
-  a.off_xn = (long)p->b_off_xn; a.off_q = (long)p->b_off_q; a.off_ob = (long)p->b_off_ob; a.off_ub = (long)p->b_off_ub;
-  a.off_part = (long)p->b_off_part; a.off_knew = (long)p->b_off_knew; a.off_tickets = (long)p->b_off_tickets;
+  a.off_q = (long)p->b_off_q; a.off_part = (long)p->b_off_part; a.off_knew = (long)p->b_off_knew; a.off_tickets = (long)p->b_off_tickets;
   a.ssq = p->b_ssq; a.flags = p->b_flags;
   for (int j = 0; j < 4; ++j) a.R[j] = p->b_R[j];
   a.lds_xres = p->b_lds_xres; a.lds_sq = p->b_lds_sq; a.lds_part = p->b_lds_part;

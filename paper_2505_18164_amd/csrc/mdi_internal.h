@@ -237,12 +237,14 @@ struct BatchArgs {
   int n_hg; float scale;
   int nwg, m;                        // workgroups (one set), messages
   unsigned epoch0;
-  // Exchange buffers: message j's are message 0's advanced by j * slot_stride bytes.  Vectors that feed a matrix
-  // product travel as pairs of bf16 with the writing phase's counter in one 8-byte word (xn: the residual stream
-  // times the gain of the norm that follows; ob: attention output; ub: MLP hidden); q, the newest K/V row and the
-  // attention partials as (float, counter) like in StepSlot.
+  // Exchange buffers.  Vectors that feed a matrix product travel as pairs of bf16 with the writing phase's counter
+  // in one 8-byte word, one array [pair of columns][kMaxBatch messages] per kind for the whole launch (xn: the
+  // residual stream times the gain of the norm that follows; ob: attention output; ub: MLP hidden).  What attention
+  // needs per message - q, the newest K/V row, split partials as (float, counter) like in StepSlot, tickets - sits
+  // in one block per message: message j's are message 0's advanced by j * slot_stride bytes.
+  tagged_t *xn, *ob, *ub;
   char* slot0; long slot_stride;
-  long off_xn, off_q, off_ob, off_ub, off_part, off_knew, off_tickets;
+  long off_q, off_part, off_knew, off_tickets;
   tagged_t* ssq;                     // [kMaxBatch][nwg] per-workgroup sums of squares of the residual rows they own
   unsigned* flags;                   // [nwg] phase counters of the workgroups
   int R[4];                          // rows per matrix-instruction block in the QKV / output / up / down products (8 or 16)

@@ -18,7 +18,9 @@
 //   * Vectors that feed a product cross workgroups as bf16 PAIRS with the writing phase's counter in one 8-byte
 //     word, already multiplied by the gain of the RMSNorm that follows (1/rms is applied to the finished products;
 //     the sum of squares travels as one partial per workgroup and message).  Bytes exchanged per message are half
-//     those of k_step's (float, counter) words, which matters now that 16 messages share a pass.
+//     those of k_step's (float, counter) words, which matters now that 16 messages share a pass.  A vector kind is
+//     ONE array [pair of columns][16 messages] for the whole launch: the 16 lanes that hold the same columns of the
+//     16 messages read 128 consecutive bytes.
 //   * The residual stream never leaves the workgroup that owns its rows: it stays in LDS for the whole launch.
 //   * Products whose input is the d-sized normalised vector (QKV, MLP up) keep each wavefront's column slice of all
 //     messages in registers for all the blocks of the phase; the others (output projection, MLP down: one block per
@@ -49,36 +51,32 @@ __device__ __forceinline__ uint32_t settle_bits(const tagged_t* p, tagged_t u, u
   return (uint32_t)u;
 }
 
-// Four consecutive tagged words (eight bf16 of one message) -> the matrix instruction's second operand, once all four
-// carry the counter `tag`; words that do not are loaded again (the rare case: a store not yet visible on this die).
-__device__ __forceinline__ bf16x8 settle4(const tagged_t* p, tagged_t r0, tagged_t r1, tagged_t r2, tagged_t r3, unsigned tag,
-                                          int spin_limit, int* err) {
-  int it = 0;
-  while (((uint32_t)(r0 >> 32) != tag) | ((uint32_t)(r1 >> 32) != tag) | ((uint32_t)(r2 >> 32) != tag) | ((uint32_t)(r3 >> 32) != tag)) {
-    if (++it > spin_limit) { __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
-    __builtin_amdgcn_s_sleep(1);
-    r0 = ld_raw(p); r1 = ld_raw(p + 1); r2 = ld_raw(p + 2); r3 = ld_raw(p + 3);
-  }
-  return __builtin_bit_cast(bf16x8, u32x4{(uint32_t)r0, (uint32_t)r1, (uint32_t)r2, (uint32_t)r3});
-}
+// A word of an exchanged vector: loaded at agent scope, i.e. from memory, not from a die's L2, which may hold an
+// older copy.  (Measured: ordinary loads that L2 may answer - with one address per (layer, phase) instance of every
+// vector so that no older copy can exist, and a coherent second look for words that were fetched too early - move
+// 32 times less over the fabric and are not faster: the phases that stream these vectors are bound by what a
+// compute unit's memory pipeline passes per unit of time, whichever cache answers.)
+__device__ __forceinline__ tagged_t ld_word(const MDI_GLOBAL tagged_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // What the attention helpers of step_impl.h read of a message.
 struct BatchView {
   const tagged_t *q, *knew;
-  tagged_t *part, *ob;
+  tagged_t *part, *ob;             // ob: the launch's [pair][16 messages] array of attention outputs
   unsigned* tickets;
   const int32_t* table;
-  int ctx, n_splits, chunk;
+  int ctx, n_splits, chunk, msg;
 };
-__device__ __forceinline__ BatchView view_of(const BatchArgs& a, int j) {
+__device__ __forceinline__ BatchView view_of(const BatchArgs& a, int j, tagged_t* ob) {
   char* base = a.slot0 + (long)j * a.slot_stride;
   BatchView v;
   v.q = (const tagged_t*)(base + a.off_q); v.knew = (const tagged_t*)(base + a.off_knew);
-  v.part = (tagged_t*)(base + a.off_part); v.ob = (tagged_t*)(base + a.off_ob);
+  v.part = (tagged_t*)(base + a.off_part); v.ob = ob; v.msg = j;
   v.tickets = (unsigned*)(base + a.off_tickets);
   v.table = a.s[j].table; v.ctx = a.s[j].ctx; v.n_splits = a.s[j].n_splits; v.chunk = a.s[j].chunk;
   return v;
 }
+
+constexpr int kStrSteps = 4;            // column steps per tile of a streamed product
 
 // ---------------------------------------------------------------------------
 // geometry of a product (all values uniform across the wavefront)
@@ -88,7 +86,8 @@ struct BGeo {
   int N, R;             // rows; rows per block (16 or 8)
   int rope_sh;          // >= 0: rows pair as RoPE partners (i, i + h/2), h = 2 << rope_sh; -1: rows (2p, 2p + 1)
   int nb_local;         // this workgroup's blocks: its block lb is block lb * nwg + wg of the matrix
-  int ks0, nks;         // this wavefront's column steps [ks0, ks0 + nks), 32 columns each
+  int ks0, nks;         // this wavefront's column steps [ks0, ks0 + nks), 32 columns each (products with a resident operand)
+  int ktot, slice, snks; // streamed products: the wavefront's i-th step is step 4 * (8 * (i / 4) + slice) + i % 4 of ktot
 };
 __device__ __forceinline__ BGeo make_bgeo(const void* W, int N, int Kd, int R, int rope_h, int wg, int nwg, int wave) {
   BGeo g;
@@ -96,10 +95,20 @@ __device__ __forceinline__ BGeo make_bgeo(const void* W, int N, int Kd, int R, i
   g.rope_sh = rope_h ? 31 - __builtin_clz(rope_h >> 1) : -1;
   const int nblk = (N + R - 1) / R;
   g.nb_local = nblk > wg ? (nblk - wg + nwg - 1) / nwg : 0;
+  // The columns are cut into one slice per wavefront; which wavefront takes which slice rotates with the workgroup,
+  // so that at any moment the workgroups read different parts of the messages' vectors (every workgroup walks the
+  // same vectors: in step they would all queue up at the same few memory channels).
   const int total = Kd >> 5, c = (total + kStepWaves - 1) / kStepWaves;
-  g.ks0 = wave * c;
+  g.ks0 = ((wave + wg) & (kStepWaves - 1)) * c;
   g.nks = max(0, min(c, total - g.ks0));
   if (g.nks == 0) g.ks0 = 0;          // a wavefront without columns still issues its (unused) loads inside the matrix
+  // Streamed products deal tiles of 4 column steps round-robin to the wavefronts instead: at any moment the eight
+  // wavefronts then read 2 KiB that lie next to each other in every one of the block's rows (long rows cut into
+  // eight far-apart slices made every access open another DRAM page).
+  g.ktot = total;
+  g.slice = (wave + wg) & (kStepWaves - 1);
+  const int tiles = (total + kStrSteps - 1) / kStrSteps;
+  g.snks = tiles > g.slice ? ((tiles - g.slice + kStepWaves - 1) / kStepWaves) * kStrSteps : 0;
   return g;
 }
 // Row of the matrix that row i (< R) of block `block` stands for.  With RoPE pairing a block is R/2 consecutive
@@ -111,26 +120,20 @@ __device__ __forceinline__ int block_row(const BGeo& g, int block, int i) {
   const int head = block >> bsh, off = (block & ((1 << bsh) - 1)) << hsh;
   return (head << (g.rope_sh + 1)) + off + (i & ((g.R >> 1) - 1)) + ((i >> hsh) << g.rope_sh);
 }
-// Address of this lane's 16 bytes of column step 0 of block lb: lane (i, kg) holds row i, columns 8 kg .. 8 kg + 7
-// of a step.  Lanes past the block's rows repeat its rows (their results are never read), rows past the matrix
-// its last row.
-__device__ __forceinline__ const MDI_GLOBAL char* lane_row_ptr(const BGeo& g, int lb, int wg, int nwg, int lane) {
-  const int i = lane & (g.R - 1) & 15, kg = lane >> 4;
-  const int row = min(block_row(g, lb * nwg + wg, i), g.N - 1);
-  return (const MDI_GLOBAL char*)g.W + (long)row * g.row_bytes + ((long)g.ks0 << 6) + (kg << 4);
-}
-
 // ---------------------------------------------------------------------------
 // products whose second operand stays in registers (QKV, MLP up): Bv[ks] = this wavefront's column step ks of all
 // messages.  A tile is 8 column steps of a block; with more than 8 steps per wavefront a block is two tiles.
 constexpr int kResSteps = 16;          // column steps a wavefront can keep: widths up to 8 * 16 * 32 = 4096
 template <int HALF>
 __device__ __forceinline__ void res_issue(Tile& t, const BGeo& g, int lb, int wg, int nwg, int lane) {
-  const MDI_GLOBAL char* rp = lane_row_ptr(g, min(lb, max(g.nb_local - 1, 0)), wg, nwg, lane);
+  const int i = lane & (g.R - 1) & 15, kg = lane >> 4;
+  const int row = min(block_row(g, min(lb, max(g.nb_local - 1, 0)) * nwg + wg, i), g.N - 1);
+  const uint32_t woff = (uint32_t)row * (uint32_t)g.row_bytes + (uint32_t)(kg << 4);
+  const MDI_GLOBAL char* base = (const MDI_GLOBAL char*)g.W + ((long)g.ks0 << 6);
   const int last = max(g.nks - 1 - HALF * 8, 0);
 #pragma unroll
   for (int s = 0; s < 8; ++s)
-    t.r[s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(rp + ((long)(HALF * 8 + min(s, last)) << 6));
+    t.r[s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(base + ((long)(HALF * 8 + min(s, last)) << 6) + woff);
 }
 template <int HALF, bool LAST_HALF>
 __device__ __forceinline__ void res_compute(const Tile& t, const BGeo& g, int lb, const bf16x8 (&Bv)[kResSteps], f32x4& acc,
@@ -150,54 +153,93 @@ __device__ __forceinline__ void res_compute(const Tile& t, const BGeo& g, int lb
 
 // products whose second operand streams beside the weights (output projection, MLP down): tiles of 4 column steps,
 // three in flight.  A tile is issued in two parts: the weights (addresses depend on nothing another workgroup
-// writes, so the first tiles are requested before the barrier) and the vectors.
-constexpr int kStrSteps = 4;
+// writes, so the first tiles are requested before the barrier) and the vectors.  Every address is a uniform base
+// that advances with the column step plus a per-lane offset that is fixed for the block: the loop spends its
+// instructions on loads and products, not on 64-bit address arithmetic per lane.
 struct StrTile { u32x4 w[kStrSteps]; tagged_t b[kStrSteps][4]; };
-struct StrCursor {
-  int lb, ks;                           // next column step of the wavefront's flat sequence (block, step)
-  int row_lb;                           // block whose row address `rp` holds (-1: none)
-  const MDI_GLOBAL char* rp;
-};
-__device__ __forceinline__ StrCursor str_start() { StrCursor c; c.lb = 0; c.ks = 0; c.row_lb = -1; c.rp = nullptr; return c; }
-__device__ __forceinline__ void str_next(const BGeo& g, int& lb, int& ks) { if (++ks >= g.nks) { ks = 0; ++lb; } }
-__device__ __forceinline__ void str_issue_w(StrTile& t, const BGeo& g, StrCursor& c, int wg, int nwg, int lane) {
+// lane offset (bytes) of this lane's row and column group inside the matrix, for block lb
+__device__ __forceinline__ uint32_t lane_w_off(const BGeo& g, int lb, int wg, int nwg, int lane) {
+  const int i = lane & (g.R - 1) & 15, kg = lane >> 4;
+  const int row = min(block_row(g, lb * nwg + wg, i), g.N - 1);
+  return (uint32_t)row * (uint32_t)g.row_bytes + (uint32_t)(kg << 4);
+}
+// The column step of the matrix that the wavefront's i-th step stands for (i is a multiple of 4 plus s < 4); steps past
+// the end repeat the last column step of the matrix (their products are skipped).
+__device__ __forceinline__ int str_k(const BGeo& g, int i, int s) {
+  return min((((i >> 2) * kStepWaves + g.slice) << 2) + s, g.ktot - 1);
+}
+// Steps i .. i + 3 (i a multiple of 4) of the block whose lane offset is woff.
+__device__ __forceinline__ void str_issue_w(StrTile& t, const BGeo& g, uint32_t woff, int i) {
+  const MDI_GLOBAL char* base = (const MDI_GLOBAL char*)g.W;
+  const int it = min(i, max(g.snks - kStrSteps, 0));
+#pragma unroll
+  for (int s = 0; s < kStrSteps; ++s)
+    t.w[s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(base + ((long)str_k(g, it, s) << 6) + woff);
+}
+// bvec: this phase's [pair of columns][16 messages] array; boff: this lane's (column group, message) offset in words.
+// A lane's eight columns of a step are four words 16 apart.
+__device__ __forceinline__ void str_issue_b(StrTile& t, const BGeo& g, const tagged_t* bvec, uint32_t boff, int i) {
+  const MDI_GLOBAL tagged_t* base = (const MDI_GLOBAL tagged_t*)bvec;
+  const int it = min(i, max(g.snks - kStrSteps, 0));
 #pragma unroll
   for (int s = 0; s < kStrSteps; ++s) {
-    const bool past = c.lb >= g.nb_local;                        // uniform; steps past the end repeat the last one
-    const int lb = past ? max(g.nb_local - 1, 0) : c.lb, ks = past ? max(g.nks - 1, 0) : c.ks;
-    if (lb != c.row_lb) { c.rp = lane_row_ptr(g, lb, wg, nwg, lane); c.row_lb = lb; }
-    t.w[s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(c.rp + ((long)ks << 6));
-    if (!past) str_next(g, c.lb, c.ks);
+    const MDI_GLOBAL tagged_t* p = base + ((long)str_k(g, it, s) << 8) + boff;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) t.b[s][e] = ld_word(p + (e << 4));
   }
 }
-// bvec: this lane's message vector as tagged pairs; pair index of column k is k / 2
-__device__ __forceinline__ void str_issue_b(StrTile& t, const BGeo& g, StrCursor& c, const tagged_t* bvec, int lane) {
-  const int kg = lane >> 4;
+// Four tagged words -> the matrix instruction's second operand; `bad` collects whether any of them does not carry the
+// counter `tag` (a store not yet visible on this die: the rare case).  No load is retried here: a reload inside
+// the pipelined loop would cost the compiler its count of the loads in flight, and with it the overlap of the tiles;
+// the caller repeats the whole pass over the block instead.
+__device__ __forceinline__ bf16x8 take4(tagged_t r0, tagged_t r1, tagged_t r2, tagged_t r3, unsigned tag, uint32_t& bad) {
+  bad |= (((uint32_t)(r0 >> 32) ^ tag) | ((uint32_t)(r1 >> 32) ^ tag)) | (((uint32_t)(r2 >> 32) ^ tag) | ((uint32_t)(r3 >> 32) ^ tag));
+  return __builtin_bit_cast(bf16x8, u32x4{(uint32_t)r0, (uint32_t)r1, (uint32_t)r2, (uint32_t)r3});
+}
+__device__ __forceinline__ void str_compute(const StrTile& t, const BGeo& g, int i, unsigned tag, f32x4& acc, uint32_t& bad) {
+  if (i >= g.snks) return;                                       // uniform
 #pragma unroll
   for (int s = 0; s < kStrSteps; ++s) {
-    const bool past = c.lb >= g.nb_local;
-    const int ks = past ? max(g.nks - 1, 0) : c.ks;
-    const tagged_t* p = bvec + ((g.ks0 + ks) << 4) + (kg << 2);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) t.b[s][e] = ld_raw(p + e);
-    if (!past) str_next(g, c.lb, c.ks);
+    const int k = (((i >> 2) * kStepWaves + g.slice) << 2) + s;
+    if (k < g.ktot)                                              // uniform
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.w[s]),
+                                                   take4(t.b[s][0], t.b[s][1], t.b[s][2], t.b[s][3], tag, bad), acc, 0, 0, 0);
   }
 }
-__device__ __forceinline__ void str_compute(const StrTile& t, const BGeo& g, StrCursor& c, const tagged_t* bvec, unsigned tag, f32x4& acc,
-                                            float* part, int wave, int lane, int spin_limit, int* err) {
-  const int kg = lane >> 4;
-#pragma unroll
-  for (int s = 0; s < kStrSteps; ++s) {
-    if (c.lb < g.nb_local) {                                     // uniform
-      const tagged_t* p = bvec + ((g.ks0 + c.ks) << 4) + (kg << 2);
-      const bf16x8 bv = settle4(p, t.b[s][0], t.b[s][1], t.b[s][2], t.b[s][3], tag, spin_limit, err);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.w[s]), bv, acc, 0, 0, 0);
-      if (c.ks == g.nks - 1) {
-        *reinterpret_cast<f32x4*>(part + (((c.lb * kStepWaves + wave) << 6) + lane) * 4) = acc;
-        acc = f32x4{0.f, 0.f, 0.f, 0.f};
-      }
-      str_next(g, c.lb, c.ks);
-    }
+// One pass over a block's columns: three tiles in flight, each consumed while the other two's loads arrive.  The
+// first tiles are already requested when `issued` (before the barrier: weights; right after it: vectors).  Nothing in
+// here branches around a load: with a conditional load in the loop the compiler no longer knows how many loads are in
+// flight where a tile is consumed, and waits for (nearly) all of them.
+__device__ __forceinline__ void str_pass(StrTile& T0, StrTile& T1, StrTile& T2, const BGeo& g, const tagged_t* bvec, uint32_t woff, uint32_t boff,
+                                         unsigned tag, f32x4& acc, uint32_t& bad, bool issued) {
+  if (!issued) {
+    str_issue_w(T0, g, woff, 0); str_issue_w(T1, g, woff, kStrSteps); str_issue_w(T2, g, woff, 2 * kStrSteps);
+    str_issue_b(T0, g, bvec, boff, 0); str_issue_b(T1, g, bvec, boff, kStrSteps); str_issue_b(T2, g, bvec, boff, 2 * kStrSteps);
+  }
+#pragma nounroll
+  for (int ks = 0; ks < g.snks; ks += 3 * kStrSteps) {
+    str_compute(T0, g, ks, tag, acc, bad);
+    str_issue_w(T0, g, woff, ks + 3 * kStrSteps); str_issue_b(T0, g, bvec, boff, ks + 3 * kStrSteps);
+    str_compute(T1, g, ks + kStrSteps, tag, acc, bad);
+    str_issue_w(T1, g, woff, ks + 4 * kStrSteps); str_issue_b(T1, g, bvec, boff, ks + 4 * kStrSteps);
+    str_compute(T2, g, ks + 2 * kStrSteps, tag, acc, bad);
+    str_issue_w(T2, g, woff, ks + 5 * kStrSteps); str_issue_b(T2, g, bvec, boff, ks + 5 * kStrSteps);
+  }
+}
+// The same pass the slow, sure way - one column step at a time, vector words loaded at agent scope until they carry
+// the counter - for the rare block whose first look through L2 met words that were not there yet.
+__device__ __forceinline__ void str_pass_coherent(const BGeo& g, const tagged_t* bvec, uint32_t woff, uint32_t boff, unsigned tag, f32x4& acc,
+                                                  int spin_limit, int* err) {
+#pragma nounroll
+  for (int i = 0; i < g.snks; ++i) {
+    const int k = (((i >> 2) * kStepWaves + g.slice) << 2) + (i & 3);
+    if (k >= g.ktot) continue;                                   // uniform
+    const u32x4 w = *reinterpret_cast<const MDI_GLOBAL u32x4*>((const MDI_GLOBAL char*)g.W + ((long)k << 6) + woff);
+    const tagged_t* p = bvec + ((long)k << 8) + boff;
+    u32x4 bw;
+    bw.x = settle_bits(p, ld_raw(p), tag, spin_limit, err); bw.y = settle_bits(p + 16, ld_raw(p + 16), tag, spin_limit, err);
+    bw.z = settle_bits(p + 32, ld_raw(p + 32), tag, spin_limit, err); bw.w = settle_bits(p + 48, ld_raw(p + 48), tag, spin_limit, err);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, bw), acc, 0, 0, 0);
   }
 }
 
@@ -229,7 +271,7 @@ __device__ __forceinline__ void attn_finish_pairs(const AttnGeo& g, const BatchA
     }
     const int head = g.hg * G + gi;
     if (single) {
-      st_pair(S.ob + (((long)head * h + e) >> 1), pack_bf16x2(o0 / l, o1 / l), wtag);
+      st_pair(S.ob + ((((long)head * h + e) >> 1) << 4) + S.msg, pack_bf16x2(o0 / l, o1 / l), wtag);
     } else {
       tagged_t* pr = S.part + ((long)head * kMaxSplits + g.split) * rec;
       st_tag(pr + e, o0, wtag); st_tag(pr + e + 1, o1, wtag);
@@ -275,7 +317,7 @@ __device__ __forceinline__ void attn_finish_pairs(const AttnGeo& g, const BatchA
         }
       }
     }
-    st_pair(S.ob + (((long)head * h + e) >> 1), pack_bf16x2(o0 / l, o1 / l), wtag);
+    st_pair(S.ob + ((((long)head * h + e) >> 1) << 4) + S.msg, pack_bf16x2(o0 / l, o1 / l), wtag);
   }
   if (threadIdx.x == 0) __hip_atomic_store(S.tickets + g.hg, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -320,7 +362,6 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
   float* part = smem + a.lds_part;               // the wavefronts' partial products [block][wavefront][lane][4]; attention scratch
   const int kg = lane >> 4;
   const int nmsg = min(lane & 15, m - 1);        // the message this lane's column stands for (columns past m repeat the last)
-  const char* myslot = a.slot0 + (long)nmsg * a.slot_stride;
 
   if (threadIdx.x == 0) {
     for (int j = 0; j < m; ++j) {
@@ -348,8 +389,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
         const float x0 = batch_input(a, sl, j, r0), x1 = batch_input(a, sl, j, r0 + 1);
         float* xr = xres + ((lb << 4) + 2 * p) * 16 + j;
         xr[0] = x0; xr[16] = x1;
-        tagged_t* xn = (tagged_t*)(a.slot0 + (long)j * a.slot_stride + a.off_xn);
-        st_pair(xn + (r0 >> 1), pack_bf16x2(x0 * a.l0.ln1_g[r0], x1 * a.l0.ln1_g[r0 + 1]), a.epoch0);
+        st_pair(a.xn + ((r0 >> 1) << 4) + j, pack_bf16x2(x0 * a.l0.ln1_g[r0], x1 * a.l0.ln1_g[r0 + 1]), a.epoch0);
         s2 = x0 * x0 + x1 * x1;
       }
       sq[e] = s2;
@@ -404,8 +444,12 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
       // The per-lane addresses of the exchange vectors do not change from phase to phase; computed once outside
       // the loops they would occupy dozens of registers for the whole launch, so they are derived from a value
       // the compiler cannot see through and are recomputed where they are used.
-      const char* slotp = myslot;
-      asm volatile("" : "+v"(slotp));
+      int lane_msg = nmsg;
+      asm volatile("" : "+v"(lane_msg));
+      const tagged_t* xn_in = a.xn;
+      tagged_t* xn_out = a.xn;
+      tagged_t* ob_l = a.ob;
+      tagged_t* ub_l = a.ub;
       bstamp(a, layer, ph, 0);
 
       // Every kind of phase keeps its registers to itself (tiles in flight, the second operand, attention state are
@@ -413,7 +457,6 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
       // Each branch first issues the requests that depend on nothing another workgroup writes - they are in flight
       // while the barrier completes - and then waits for the barrier.
       if (ph == PH_ATTN) {
-#ifndef BATCH_NO_ATTN
         // ---- attention: one work item = (message, head group, context split); items dealt round-robin
         AttnState<WT, G> st;
         AttnGeo ga{};
@@ -423,7 +466,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
         int item = wg, slot = 0;
         if (item < a.n_items) {
           while (slot + 1 < m && item >= a.s[slot + 1].item_lo) ++slot;
-          V = view_of(a, slot);
+          V = view_of(a, slot, ob_l);
           ga = make_attn_geo<WT, G>(a, V, item - a.s[slot].item_lo, wave, lane);
           attn_pages(pgA, ga, a, V, 0, wave); attn_pages(pgB, ga, a, V, 1, wave);
           attn_issue<WT>(A, pgA, ga, a, V, Lv.kv, 0, wave); attn_issue<WT>(B, pgB, ga, a, V, Lv.kv, 1, wave);
@@ -439,7 +482,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
             if (item >= a.n_items) break;
             __syncthreads();                                       // the records in LDS have been read
             while (slot + 1 < m && item >= a.s[slot + 1].item_lo) ++slot;
-            V = view_of(a, slot);
+            V = view_of(a, slot, ob_l);
             ga = make_attn_geo<WT, G>(a, V, item - a.s[slot].item_lo, wave, lane);
             attn_pages(pgA, ga, a, V, 0, wave); attn_pages(pgB, ga, a, V, 1, wave);
             attn_issue<WT>(A, pgA, ga, a, V, Lv.kv, 0, wave); attn_issue<WT>(B, pgB, ga, a, V, Lv.kv, 1, wave);
@@ -447,11 +490,9 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
         } else {
           if (!barrier(epoch)) return;                             // a workgroup without an item still takes part in the barrier
         }
-#endif
         bstamp(a, layer, ph, 3);
       } else {
         if (ph == PH_QKV || ph == PH_UP) {
-#ifndef BATCH_NO_RES
           // ---- a product whose second operand stays in registers
           Tile A, B;
           bf16x8 Bv[kResSteps];
@@ -481,20 +522,30 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
               if (j < m && c == 0) rscale[j] = 1.f / sqrtf(t / (float)a.d + a.eps);
             }
             // the slice, as published: bf16 pairs of x * gain
-            const tagged_t* bvec = (const tagged_t*)(slotp + a.off_xn);
+            const MDI_GLOBAL tagged_t* bbase = (const MDI_GLOBAL tagged_t*)xn_in + ((long)g.ks0 << 8);
+            const uint32_t boff = (uint32_t)((kg << 6) + lane_msg);
+            const int last = max(g.nks - 1, 0);
+            uint32_t bad = 0u;
 #pragma unroll
             for (int h0 = 0; h0 < kResSteps; h0 += 4) {
               tagged_t raw[4][4];
 #pragma unroll
               for (int s = 0; s < 4; ++s) {          // steps past the slice repeat its last one: every register gets a value
-                const tagged_t* p = bvec + ((g.ks0 + min(h0 + s, max(g.nks - 1, 0))) << 4) + (kg << 2);
+                const MDI_GLOBAL tagged_t* p = bbase + ((long)min(h0 + s, last) << 8) + boff;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) raw[s][e] = ld_raw(p + e);
+                for (int e = 0; e < 4; ++e) raw[s][e] = ld_word(p + (e << 4));
               }
 #pragma unroll
-              for (int s = 0; s < 4; ++s) {
-                const tagged_t* p = bvec + ((g.ks0 + min(h0 + s, max(g.nks - 1, 0))) << 4) + (kg << 2);
-                Bv[h0 + s] = settle4(p, raw[s][0], raw[s][1], raw[s][2], raw[s][3], epoch, a.spin_limit, a.err);
+              for (int s = 0; s < 4; ++s) Bv[h0 + s] = take4(raw[s][0], raw[s][1], raw[s][2], raw[s][3], epoch, bad);
+            }
+            if (__any(bad != 0u)) {                  // rare: every step again at agent scope, until its words carry the counter
+#pragma unroll
+              for (int ks = 0; ks < kResSteps; ++ks) {
+                const tagged_t* p = xn_in + ((long)(g.ks0 + min(ks, last)) << 8) + boff;
+                u32x4 bw;
+                bw.x = settle_bits(p, ld_raw(p), epoch, a.spin_limit, a.err); bw.y = settle_bits(p + 16, ld_raw(p + 16), epoch, a.spin_limit, a.err);
+                bw.z = settle_bits(p + 32, ld_raw(p + 32), epoch, a.spin_limit, a.err); bw.w = settle_bits(p + 48, ld_raw(p + 48), epoch, a.spin_limit, a.err);
+                Bv[ks] = __builtin_bit_cast(bf16x8, bw);
               }
             }
           }
@@ -517,29 +568,31 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
               res_issue<0>(B, g, lb + 3, wg, nwg, lane);
             }
           }
-#endif
         } else {
-#ifndef BATCH_NO_STR
           // ---- a product whose second operand streams beside the weights
           StrTile T0, T1, T2;
-          StrCursor cw = str_start(), cb = str_start(), cc = str_start();
-          str_issue_w(T0, g, cw, wg, nwg, lane); str_issue_w(T1, g, cw, wg, nwg, lane); str_issue_w(T2, g, cw, wg, nwg, lane);
+          uint32_t woff = lane_w_off(g, 0, wg, nwg, lane);
+          const uint32_t boff = (uint32_t)((kg << 6) + lane_msg);
+          str_issue_w(T0, g, woff, 0); str_issue_w(T1, g, woff, kStrSteps); str_issue_w(T2, g, woff, 2 * kStrSteps);
           if (!barrier(epoch)) return;
           bstamp(a, layer, ph, 1);
-          const tagged_t* bvec = (const tagged_t*)(slotp + (ph == PH_OPROJ ? a.off_ob : a.off_ub));
-          str_issue_b(T0, g, cb, bvec, lane); str_issue_b(T1, g, cb, bvec, lane); str_issue_b(T2, g, cb, bvec, lane);
+          const tagged_t* bvec = ph == PH_OPROJ ? ob_l : ub_l;
+          str_issue_b(T0, g, bvec, boff, 0); str_issue_b(T1, g, bvec, boff, kStrSteps); str_issue_b(T2, g, bvec, boff, 2 * kStrSteps);
           bstamp(a, layer, ph, 2);
-          const int n_steps = g.nb_local * g.nks;
 #pragma nounroll
-          for (int f = 0; f < n_steps; f += 3 * kStrSteps) {
-            str_compute(T0, g, cc, bvec, epoch, acc, part, wave, lane, a.spin_limit, a.err);
-            str_issue_w(T0, g, cw, wg, nwg, lane); str_issue_b(T0, g, cb, bvec, lane);
-            str_compute(T1, g, cc, bvec, epoch, acc, part, wave, lane, a.spin_limit, a.err);
-            str_issue_w(T1, g, cw, wg, nwg, lane); str_issue_b(T1, g, cb, bvec, lane);
-            str_compute(T2, g, cc, bvec, epoch, acc, part, wave, lane, a.spin_limit, a.err);
-            str_issue_w(T2, g, cw, wg, nwg, lane); str_issue_b(T2, g, cb, bvec, lane);
+          for (int lb = 0; lb < g.nb_local; ++lb) {
+            if (lb) woff = lane_w_off(g, lb, wg, nwg, lane);
+            uint32_t bad = 0u;
+            acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            str_pass(T0, T1, T2, g, bvec, woff, boff, epoch, acc, bad, lb == 0);
+            if (__any(bad != 0u)) {                                // rare: the block once more, the slow and sure way
+              acc = f32x4{0.f, 0.f, 0.f, 0.f};
+              str_pass_coherent(g, bvec, woff, boff, epoch, acc, a.spin_limit, a.err);
+            }
+            // the wavefront's share of the block (zeros when it has no columns)
+            *reinterpret_cast<f32x4*>(part + (((lb * kStepWaves + wave) << 6) + lane) * 4) = acc;
+            acc = f32x4{0.f, 0.f, 0.f, 0.f};
           }
-#endif
         }
         bstamp(a, layer, ph, 3);
         __syncthreads();                                             // every wavefront's partial products are in LDS
@@ -589,8 +642,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
                 for (int w = 0; w < kStepWaves; ++w) { const f32x4 t = *reinterpret_cast<const f32x4*>(pp + (w << 8)); v += t; }
                 const float rs = rscale[j];
                 const float u0 = silu_f(v.x * rs) * (v.y * rs), u1 = silu_f(v.z * rs) * (v.w * rs);
-                tagged_t* ub = (tagged_t*)(a.slot0 + (long)j * a.slot_stride + a.off_ub);
-                st_pair(ub + (r0 >> 2), pack_bf16x2(u0, u1), wtag);
+                st_pair(ub_l + ((r0 >> 2) << 4) + j, pack_bf16x2(u0, u1), wtag);
               }
             }
           } else {
@@ -601,8 +653,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
               if (r0 < g.N) {
                 float v0 = part_sum(part, lb, 2 * p, j) * rscale[j], v1 = part_sum(part, lb, 2 * p + 1, j) * rscale[j];
                 if (Lv.bup) { v0 += Lv.bup[r0]; v1 += Lv.bup[r0 + 1]; }
-                tagged_t* ub = (tagged_t*)(a.slot0 + (long)j * a.slot_stride + a.off_ub);
-                st_pair(ub + (r0 >> 1), pack_bf16x2(tanh_form ? gelu_tanh_f(v0) : gelu_erf_f(v0), tanh_form ? gelu_tanh_f(v1) : gelu_erf_f(v1)), wtag);
+                st_pair(ub_l + ((r0 >> 1) << 4) + j, pack_bf16x2(tanh_form ? gelu_tanh_f(v0) : gelu_erf_f(v0), tanh_form ? gelu_tanh_f(v1) : gelu_erf_f(v1)), wtag);
               }
             }
           }
@@ -625,8 +676,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
               if (last) {
                 store_kind(sl.out[j], a.act_kind, r0, x0); store_kind(sl.out[j], a.act_kind, r0 + 1, x1);
               } else {
-                tagged_t* xn = (tagged_t*)(a.slot0 + (long)j * a.slot_stride + a.off_xn);
-                st_pair(xn + (r0 >> 1), pack_bf16x2(x0 * gain[r0], x1 * gain[r0 + 1]), wtag);
+                st_pair(xn_out + ((r0 >> 1) << 4) + j, pack_bf16x2(x0 * gain[r0], x1 * gain[r0 + 1]), wtag);
                 s2 = x0 * x0 + x1 * x1;
               }
             }

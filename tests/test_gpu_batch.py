@@ -22,6 +22,8 @@ SHAPES = {
                                  pos_kind=S.POS_LEARNED),
     "swiglu_attn_bias": dict(d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96, has_bias=1),
     "wide": dict(d_model=256, n_head=4, n_kv_head=2, head_dim=64, d_ff=704),
+    # 9 column steps of 32 in the down projection: some wavefronts of a workgroup get none
+    "idle_wavefronts": dict(d_model=256, n_head=4, n_kv_head=2, head_dim=64, d_ff=288),
 }
 
 
@@ -48,6 +50,28 @@ def test_batched_pass_against_the_oracle(name, n_msg):
         assert g.seq_len(s) == len(prompts[s]) + 12
     g.sync()
     print(f"{name} x{n_msg}: worst rel-L2 {worst:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("name", ["gqa_h16", "gqa8_h8", "h64", "idle_wavefronts"])
+def test_batched_pass_with_pairs_of_query_heads_and_context_splits(name, monkeypatch):
+    """Long contexts (or more attention work items than workgroups) let two query heads share a pass over their kv
+    head's cache, and contexts of more than 128 positions are split among workgroups and folded; both are reached
+    here on small shapes by lowering the switch-over length and by a context of a few hundred positions."""
+    monkeypatch.setenv("MDI_GROUP_CTX", "12")
+    cfg = S.tiny(n_layer=2, dtype=S.DT_BF16, max_ctx=512, vocab=211, **SHAPES[name])
+    w = scale_matrices(S.make_weights(cfg, 29, exercise=True), 2.0)
+    o, g = pair(cfg, w, 0, 2, embed=True, max_seqs=3, kv_page_tokens=16)
+    lens = (300, 7, 140)
+    for s, T in enumerate(lens):
+        ids = S.make_prompts(cfg, 29 + s, 1, T)[0]
+        check(g.prefill(s, dev_ids(ids)), o.prefill(s, ids), cfg, ("prefill", s))
+    rng = np.random.default_rng(4)
+    for step in range(8):
+        toks = [int(rng.integers(0, cfg["vocab"])) for _ in range(3)]
+        outs = g.decode_batch([2, 0, 1], [dev_ids([toks[s]]) for s in (2, 0, 1)])
+        for s, got in zip((2, 0, 1), outs):
+            check(got, o.decode_step(s, toks[s]), cfg, ("batched decode", step, s))
+    g.sync()
 
 
 def test_batched_pass_on_a_mid_partition_and_more_messages_than_one_pass():

@@ -42,11 +42,15 @@
  * partition must then be destroyed (its exchange counters are no longer
  * consistent), other partitions are unaffected.
  *
- * One tuning knob is read from the environment when a partition is created:
+ * Two tuning knobs are read from the environment when a partition is created:
  * MDI_GROUP_CTX = context length from which, in models whose query heads share
  * kv heads in even groups, the decode kernel lets two query heads take one pass
  * over the cache together (default 4096; below it every head takes its own).
  * Results are within the parity bar either way; the order of additions differs.
+ * MDI_BATCH_GROUP = 1, 2 or 4 fixes the number of query heads per attention
+ * work item of mdi_decode_batch (by default chosen per call from the number of
+ * messages and the longest context); used by tests to reach every variant on
+ * small shapes.
  */
 #ifndef MDI_H
 #define MDI_H

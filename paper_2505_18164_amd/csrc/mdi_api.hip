@@ -94,6 +94,7 @@ struct mdi_partition {
   unsigned* b_flags = nullptr;
   unsigned b_epoch = 0;
   int b_R[4] = {16, 16, 16, 16};
+  int batch_group = 0;                 // MDI_BATCH_GROUP: query heads per attention work item of a batched pass (0: chosen per launch)
   int b_lds_xres = 0, b_lds_sq = 0, b_lds_part = 0;
   size_t b_lds = 0;
   int n_cu = 0;
@@ -254,6 +255,7 @@ void plan_step(mdi_partition* p, int n_cu) {
   p->G = group % 2 == 0 ? 2 : 1;
   p->group_ctx = 4096;
   if (const char* e = getenv("MDI_GROUP_CTX")) p->group_ctx = std::max(0, atoi(e));   // tuning / test knob, see mdi.h
+  if (const char* e = getenv("MDI_BATCH_GROUP")) { const int v = atoi(e); p->batch_group = (v == 1 || v == 2 || v == 4) ? v : 0; }
   p->n_hg = H;                           // the most head groups a launch has (one head each)
   p->nwg = std::min(n_cu, 1024);
   if (p->n_hg > p->nwg) return;
@@ -298,7 +300,8 @@ void plan_batch(mdi_partition* p) {
   p->b_lds_xres = 128;
   p->b_lds_sq = p->b_lds_xres + nb_d * 256;
   p->b_lds_part = p->b_lds_sq + std::max(nb_d * 128, 128);
-  const int attn_floats = std::max(p->G * h, kStepWavesMax * p->G * (h + 2)) + 64;
+  const int Gmax = (H / K) % 4 == 0 ? 4 : p->G;
+  const int attn_floats = std::max(Gmax * h, kStepWavesMax * Gmax * (h + 2)) + 64;
   const int part_floats = std::max(nb_max * 2048, attn_floats);
   p->b_lds = (size_t)(p->b_lds_part + part_floats) * sizeof(float);
   if (p->b_lds > 160 * 1024) return;
@@ -849,7 +852,11 @@ mdi_status launch_batch(mdi_partition* p, int n, const uint32_t* seqs, const Mes
   for (int j = 0; j < n; ++j) { ctx_max = std::max(ctx_max, mp[j].ctx); ctx_sum += mp[j].ctx; }
   // Query heads per attention work item: pairs also when one head per item would give more items than workgroups
   // (every message brings n_head of them), so that a workgroup has one item and a kv head's cache is read half as often.
-  const int G = (ctx_max >= p->group_ctx || n * (int)c.n_head > p->nwg) ? p->G : 1;
+  // With more items than workgroups even so, four heads take the pass together (one work item then serves a whole
+  // group of the 8B shape; the context splits that fill the grid are folded by one workgroup per item group).
+  const int group = (int)(c.n_head / c.n_kv_head);
+  int G = (n * (int)c.n_head >= 2 * p->nwg && group % 4 == 0) ? 4 : (ctx_max >= p->group_ctx || n * (int)c.n_head > p->nwg) ? p->G : 1;
+  if (p->batch_group && group % p->batch_group == 0) G = p->batch_group;   // test knob, see mdi.h
   a.l0 = p->h_step_layers[0];
   a.w_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].wqkv - (const char*)p->h_step_layers[0].wqkv : 0;
   a.kv_stride = p->n_local > 1 ? (const char*)p->h_step_layers[1].kv - (const char*)p->h_step_layers[0].kv : 0;

@@ -708,13 +708,15 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
 bool step_batch_allow_lds(size_t lds) {
   using namespace step_w8;
   return hipFuncSetAttribute((const void*)k_step_batch<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess &&
-         hipFuncSetAttribute((const void*)k_step_batch<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
+         hipFuncSetAttribute((const void*)k_step_batch<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess &&
+         hipFuncSetAttribute((const void*)k_step_batch<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
 }
 
 void launch_step_batch(hipStream_t s, int G, size_t lds, const BatchArgs& a) {
   using namespace step_w8;
   const dim3 grid(a.nwg), block(kStepThreads);
-  if (G == 2) hipLaunchKernelGGL((k_step_batch<2>), grid, block, lds, s, a);
+  if (G == 4) hipLaunchKernelGGL((k_step_batch<4>), grid, block, lds, s, a);
+  else if (G == 2) hipLaunchKernelGGL((k_step_batch<2>), grid, block, lds, s, a);
   else hipLaunchKernelGGL((k_step_batch<1>), grid, block, lds, s, a);
 }
 

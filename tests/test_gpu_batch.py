@@ -52,13 +52,19 @@ def test_batched_pass_against_the_oracle(name, n_msg):
     print(f"{name} x{n_msg}: worst rel-L2 {worst:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("heads", [2, 4])
 @pytest.mark.parametrize("name", ["gqa_h16", "gqa8_h8", "h64", "idle_wavefronts"])
-def test_batched_pass_with_pairs_of_query_heads_and_context_splits(name, monkeypatch):
+def test_batched_pass_with_pairs_of_query_heads_and_context_splits(name, heads, monkeypatch):
     """Long contexts (or more attention work items than workgroups) let two query heads share a pass over their kv
     head's cache, and contexts of more than 128 positions are split among workgroups and folded; both are reached
     here on small shapes by lowering the switch-over length and by a context of a few hundred positions."""
+    shape = dict(SHAPES[name])
+    if heads == 4:                                                 # four heads per work item need groups of a multiple of four
+        if name != "gqa8_h8":
+            shape.update(n_head=4 * shape["n_kv_head"], d_model=4 * shape["n_kv_head"] * shape["head_dim"])
+        monkeypatch.setenv("MDI_BATCH_GROUP", "4")
     monkeypatch.setenv("MDI_GROUP_CTX", "12")
-    cfg = S.tiny(n_layer=2, dtype=S.DT_BF16, max_ctx=512, vocab=211, **SHAPES[name])
+    cfg = S.tiny(n_layer=2, dtype=S.DT_BF16, max_ctx=512, vocab=211, **shape)
     w = scale_matrices(S.make_weights(cfg, 29, exercise=True), 2.0)
     o, g = pair(cfg, w, 0, 2, embed=True, max_seqs=3, kv_page_tokens=16)
     lens = (300, 7, 140)

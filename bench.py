@@ -410,7 +410,7 @@ def main():
         # of their own as in the paper's layout; one call per generated token
         L = cfg["n_layer"]
         hw = S.make_weights(cfg, seed, L, L, embed=False, head=True)
-        hp = mdi.Partition(cfg, hw, L, L, has_head=True, max_seqs=1)
+        hp = mdi.Partition(cfg, hw, L, L, has_head=True, max_seqs=max(1, n_seqs))
         g = torch.Generator(device=dev).manual_seed(seed + 4)
         x = torch.randn((d,), generator=g, device=dev, dtype=torch.float32).to(tdt)
         tok = torch.empty((1,), dtype=torch.int32, device=dev)
@@ -427,6 +427,25 @@ def main():
         hb = hp.step_bytes(0, head=True)
         result["output_layers"] = {"vocab": cfg["vocab"], "us_per_call": us, "bytes": hb, "GB/s": hb / us / 1e3,
                                    "frac_of_hbm_peak": hb / us / 1e3 / HBM_PEAK_GBS}
+        if hp.info(6) and n_seqs > 1:
+            # the same layers for every sample in flight with one pass over the vocabulary matrix (mdi_sample_batch)
+            m = min(n_seqs, int(hp.info(6)))
+            xs = [torch.randn((d,), generator=g, device=dev, dtype=torch.float32).to(tdt) for _ in range(m)]
+            toks = torch.empty((m,), dtype=torch.int32, device=dev)
+            ids = list(range(m))
+            for _ in range(10):
+                hp.sample_batch(ids, xs, tokens_out=toks)
+            torch.cuda.synchronize()
+            h0.record()
+            for _ in range(100):
+                hp.sample_batch(ids, xs, tokens_out=toks)
+            h1.record()
+            hp.sync()
+            usb = h0.elapsed_time(h1) * 10.0
+            bb = hb + (m - 1) * (d * xs[0].element_size() + 4)
+            result["output_layers"]["shared_pass"] = {
+                "samples_per_call": m, "us_per_call": usb, "us_per_sample": usb / m, "bytes": bb, "GB/s": bb / usb / 1e3,
+                "frac_of_hbm_peak": bb / usb / 1e3 / HBM_PEAK_GBS}
         del hp, hw
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, w, lo, hi, seed, S, prompt, embed)

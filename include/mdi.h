@@ -293,7 +293,7 @@ MDI_API mdi_status mdi_sample_topk(mdi_partition *part, uint32_t seq_id, const v
  * the kernels' scratch - the [V] float logits the sampler works on, the
  * per-workgroup argmax candidates and the arrival counter - is not taken from
  * the partition's arena: it lives in a fixed array inside the library
- * (1 MiB + 8.25 KiB of device memory per GPU, held until the process ends).
+ * (1 MiB + 24.25 KiB of device memory per GPU, held until the process ends).
  * The call allocates and frees nothing and records no memset (the counter is
  * cleared by a small fill kernel).  Limit: vocab <= 262144, else MDI_ERR_LIMIT.
  * All calls on one GPU share the array: calls that overlap on a GPU (different
@@ -304,6 +304,32 @@ MDI_API mdi_status mdi_sample_topk(mdi_partition *part, uint32_t seq_id, const v
 MDI_API mdi_status mdi_sample_topk_static(mdi_partition *part, uint32_t seq_id, const void *act_in,
                                   float temperature, uint32_t top_k, uint64_t seed, uint32_t step,
                                   int32_t *token_out, float *logits_out);
+
+/*
+ * Output layers for n samples whose last hidden states wait at the starter
+ * together (Alg. 1 "process output layers ... get token", once per returning
+ * sample; several samples are in flight, Sec. III-C): ONE pass over the
+ * vocabulary matrix serves up to 16 samples (each row is fetched once and
+ * multiplied with all their normalised activations on the matrix cores); more
+ * than 16 take several passes.  top_k = 1: greedy argmax as mdi_sample_greedy
+ * (temperature, seed, steps ignored; steps may be NULL); top_k > 1: the draw
+ * of mdi_sample_topk per sample with counter (seq_ids[i], steps[i]).
+ * seq_ids, acts_in, steps: HOST arrays of n; acts_in[i]: device, [d] in
+ * cfg.dtype.  tokens_out: device int32[n].  logits_out: device float[n][V]
+ * (row i = sample i) or NULL.  Needs bf16 storage, RMSNorm, d_model a
+ * multiple of 32 (at most 4608), activations aligned to 16 bytes and the
+ * persistent decode path; otherwise, and for n = 1, the samples are served
+ * one by one exactly as mdi_sample_greedy / mdi_sample_topk would
+ * (mdi_partition_info(6) tells).  In the shared pass the normalised
+ * activations are rounded to bf16, so logits agree with mdi_sample_greedy's
+ * within the bf16 parity bar, not to the last bits; the token is the argmax of
+ * (or the draw from) the logits this call returns.  Errors: as
+ * mdi_sample_topk; n = 0 does nothing.
+ */
+MDI_API mdi_status mdi_sample_batch(mdi_partition *part, uint32_t n, const uint32_t *seq_ids,
+                            const void *const *acts_in, float temperature, uint32_t top_k,
+                            uint64_t seed, const uint32_t *steps, int32_t *tokens_out,
+                            float *logits_out);
 
 /*
  * Wait for everything enqueued on the partition's stream and report errors that
@@ -360,7 +386,9 @@ MDI_API mdi_status mdi_time_kernel(mdi_partition *part, int which, uint32_t reps
  * launch (0 on the other path), 2 = its LDS bytes per workgroup (0 likewise),
  * 3 = arena bytes in use, 4 = messages one pass of mdi_decode_batch can take
  * (0: this partition forwards them one pass each), 5 = bytes of the local
- * layers' matrices (what one pass over the weights reads).  value: host pointer.
+ * layers' matrices (what one pass over the weights reads), 6 = samples one
+ * pass of mdi_sample_batch can take (0: it serves them one by one).  value:
+ * host pointer.
  */
 MDI_API mdi_status mdi_partition_info(const mdi_partition *part, uint32_t what, uint64_t *value);
 

@@ -235,7 +235,7 @@ __device__ __forceinline__ uint32_t philox4x32_10_first(uint32_t c0, uint32_t c1
   return c0;
 }
 
-__global__ __launch_bounds__(1024) void k_sample_topk(SampleArgs a) {
+__device__ __forceinline__ void sample_topk_body(const SampleArgs& a) {
   __shared__ float cv[kMaxTopK];
   __shared__ int ci[kMaxTopK];
   __shared__ float rv[16];
@@ -282,7 +282,15 @@ __global__ __launch_bounds__(1024) void k_sample_topk(SampleArgs a) {
     *a.token_out = tok;
   }
 }
+__global__ __launch_bounds__(1024) void k_sample_topk(SampleArgs a) { sample_topk_body(a); }
+// one workgroup per sample of a batch: sample j works on row j of the logits with its own counter
+__global__ __launch_bounds__(1024) void k_sample_topk_batch(SampleBatchArgs b) {
+  const int j = blockIdx.x;
+  const SampleArgs a{b.logits + (long)j * b.stride, b.V, b.k, b.inv_t, b.ctr0[j], b.ctr1[j], b.key0, b.key1, b.token_out + j};
+  sample_topk_body(a);
+}
 void launch_sample_topk(hipStream_t s, const SampleArgs& a) { hipLaunchKernelGGL(k_sample_topk, dim3(1), dim3(1024), 0, s, a); }
+void launch_sample_topk_batch(hipStream_t s, int m, const SampleBatchArgs& a) { hipLaunchKernelGGL(k_sample_topk_batch, dim3(m), dim3(1024), 0, s, a); }
 
 int gemv_grid(int N) {
   const int n_groups = (N + 3) / 4;

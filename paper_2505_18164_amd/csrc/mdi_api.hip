@@ -3,6 +3,7 @@
 // visit (prefill) and a later visit (decode step) of a sample (Alg. 1, Alg. 2).
 #include <algorithm>
 #include <cstdlib>
+#include <atomic>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -54,6 +55,9 @@ struct mdi_partition {
   float* logits = nullptr;       // [V] scratch of the stochastic sampler
   int head_nwg = 0, head_part_floats = 0;   // streaming launch of the output layers (0: per-operation GEMV)
   size_t head_lds = 0;
+  // output layers of several samples per pass over the vocabulary matrix (bf16 + RMSNorm heads)
+  int hb_nwg = 0; size_t hb_lds = 0;
+  tagged_t* hb_cand = nullptr; tagged_t* cand = nullptr; int* herr = nullptr; float* hb_logits = nullptr;
   unsigned* counters = nullptr;  // [H] attention + [1] argmax
   // prefill scratch
   float *p_xres = nullptr, *p_qkv = nullptr, *p_q = nullptr;
@@ -159,8 +163,14 @@ size_t carve(mdi_partition* p, void* arena) {
     p->amax_val = (float*)cv.take(1024 * 4);
     p->amax_idx = (int*)cv.take(1024 * 4);
     p->logits = (float*)cv.take(V * 4);
+    p->cand = (tagged_t*)cv.take(1024 * 2 * sizeof(tagged_t));
+    p->herr = (int*)cv.take(256);
+    if (c.dtype == MDI_BF16 && !ln) {
+      p->hb_cand = (tagged_t*)cv.take((size_t)kMaxBatch * 1024 * 2 * sizeof(tagged_t));
+      p->hb_logits = (float*)cv.take((size_t)kMaxBatch * V * 4);
+    }
   }
-  p->counters = (unsigned*)cv.take((H + 1) * 4);
+  p->counters = (unsigned*)cv.take((H + 2) * 4);
   if (p->n_local) {
     if (c.pos_kind == MDI_POS_ROPE) p->rope = (float2*)cv.take((size_t)c.max_ctx * (h / 2) * sizeof(float2));
     const size_t layer_pool = (size_t)p->n_pages * K * 2 * p->pt * h * B;
@@ -338,14 +348,17 @@ mdi_status launch_step_serialised(mdi_partition* p, Launch&& launch) {
 }
 
 // Scratch of mdi_sample_topk_static, the entry point for callers that cannot allocate: a [V] float logits buffer
-// for vocabularies up to kStaticVocabMax, the per-workgroup argmax candidates and the arrival counter.  One copy
+// for vocabularies up to kStaticVocabMax, the per-workgroup argmax candidates (plain for the per-operation kernel,
+// tagged for the streaming one), the arrival counter and an error word.  One copy
 // per GPU, held until the process ends; its device address is taken once per device and kept.
 constexpr size_t kStaticVocabMax = 262144;
 constexpr size_t kStaticCand = 1024;                       // workgroups of the output-layer launch, at most
 constexpr size_t kStaticLogitsOff = 0;
 constexpr size_t kStaticValOff = kStaticVocabMax * 4;
 constexpr size_t kStaticIdxOff = kStaticValOff + kStaticCand * 4;
-constexpr size_t kStaticCounterOff = kStaticIdxOff + kStaticCand * 4;
+constexpr size_t kStaticCandOff = kStaticIdxOff + kStaticCand * 4;        // tagged candidates of the streaming launch
+constexpr size_t kStaticCounterOff = kStaticCandOff + kStaticCand * 2 * sizeof(tagged_t);
+constexpr size_t kStaticErrOff = kStaticCounterOff + 128;
 constexpr size_t kStaticScratchBytes = kStaticCounterOff + 256;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 std::mutex g_scratch_mutex;
@@ -463,7 +476,12 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
     if (ln) { if (w->lnf_b) put_rows(p, w->lnf_b, p->lnf_b, 1, d, 4); else launch_fill_f32(p->stream, (float*)p->lnf_b, d, 0.f); }
     if (!c.tie_embed) put_rows(p, w->lm_head, p->lm_head, V, d, B);
   }
-  launch_fill_u32(p->stream, p->counters, H + 1, 0u);
+  launch_fill_u32(p->stream, p->counters, H + 2, 0u);
+  if (p->cand) {
+    launch_fill_u32(p->stream, (uint32_t*)p->cand, 1024 * 4, 0u);                          // tag 0 = no call's
+    launch_fill_u32(p->stream, (uint32_t*)p->herr, 64, 0u);
+  }
+  if (p->hb_cand) launch_fill_u32(p->stream, (uint32_t*)p->hb_cand, (long)kMaxBatch * 1024 * 4, 0u);
   if (p->rope) launch_rope_table(p->stream, p->rope, (int)c.max_ctx, (int)h, (double)c.rope_base);
 
   if (p->n_local) {
@@ -534,6 +552,12 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
       const int part_floats = (max_pairs * 2 * kStepWavesMax + 3) & ~3;
       const size_t lds = (size_t)(128 + part_floats + ((d + 3) & ~(size_t)3)) * sizeof(float);
       if (lds <= 64 * 1024) { p->head_nwg = nwg; p->head_part_floats = part_floats; p->head_lds = lds; }
+      // several samples per pass: all normalised activations in LDS as bf16 ([d / 8][16] units of 16 bytes)
+      const size_t hb_lds = (size_t)d * kMaxBatch * 2;
+      if (p->hb_cand && d % 32 == 0 && (uint64_t)V * d * 2 < (1ull << 32) && hb_lds <= 144 * 1024 &&
+          (hb_lds <= 60 * 1024 || logits_batch_allow_lds(hb_lds))) {
+        p->hb_nwg = nwg; p->hb_lds = hb_lds;
+      }
     }
   }
   p->seq_len.assign(c.max_seqs, 0u);
@@ -946,14 +970,23 @@ mdi_status mdi_decode_batch(mdi_partition* p, uint32_t n, const uint32_t* seqs, 
 
 namespace {
 // Scratch of the output layers' kernels: per-workgroup argmax candidates and the arrival counter.
-struct HeadScratch { float* amax_val; int* amax_idx; unsigned* counter; };
+struct HeadScratch { float* amax_val; int* amax_idx; tagged_t* cand; unsigned* counter; int* err; };
+
+// Tag of an output-layer launch: unique in the process, so that no word an earlier launch (of any partition, in the
+// arena or in the static array) left behind can pass for this launch's.  0 is what fresh scratch holds.
+std::atomic<unsigned> g_head_tag{0};
+unsigned next_head_tag() {
+  unsigned t = ++g_head_tag;
+  while (t == 0) t = ++g_head_tag;
+  return t;
+}
 
 // final norm + vocabulary projection + greedy argmax; logits (optional) go to `logits`
 void launch_head(mdi_partition* p, const void* act_in, int32_t* token_out, float* logits, const HeadScratch& hs) {
   const mdi_config& c = p->cfg;
   if (p->head_nwg) {
     LogitsArgs a{p->lm_head, (int)c.vocab, (int)c.d_model, act_in, act_kind(c), (int)c.norm_kind, p->lnf_g, p->lnf_b, c.norm_eps,
-                 logits, hs.amax_val, hs.amax_idx, hs.counter, token_out, p->head_part_floats};
+                 logits, hs.cand, next_head_tag(), hs.counter, token_out, p->head_part_floats, hs.err, 1 << 21};
     launch_logits(p->stream, c.dtype, p->head_nwg, p->head_lds, a);
     return;
   }
@@ -964,7 +997,9 @@ void launch_head(mdi_partition* p, const void* act_in, int32_t* token_out, float
   a.counter = hs.counter; a.token_out = token_out;
   launch_gemv(p->stream, c.dtype, PRO_NORM, EPI_LOGITS, a);
 }
-HeadScratch arena_head_scratch(const mdi_partition* p) { return HeadScratch{p->amax_val, p->amax_idx, p->counters + p->cfg.n_head}; }
+HeadScratch arena_head_scratch(const mdi_partition* p) {
+  return HeadScratch{p->amax_val, p->amax_idx, p->cand, p->counters + p->cfg.n_head, p->herr};
+}
 }  // namespace
 
 mdi_status mdi_sample_greedy(mdi_partition* p, uint32_t seq, const void* act_in, int32_t* token_out, float* logits_out) {
@@ -1004,7 +1039,8 @@ mdi_status mdi_sample_topk_static(mdi_partition* p, uint32_t seq, const void* ac
   const mdi_status sst = static_scratch(p->device, &base);   // taken at create; here only read
   if (sst != MDI_OK) return sst;
   float* logits = (float*)(base + kStaticLogitsOff);
-  const HeadScratch hs{(float*)(base + kStaticValOff), (int*)(base + kStaticIdxOff), (unsigned*)(base + kStaticCounterOff)};
+  const HeadScratch hs{(float*)(base + kStaticValOff), (int*)(base + kStaticIdxOff), (tagged_t*)(base + kStaticCandOff),
+                       (unsigned*)(base + kStaticCounterOff), (int*)(base + kStaticErrOff)};
   // the array keeps the last call's contents: the arrival counter must start at zero (a fill kernel, not a
   // memset node, so that the call can be captured into a graph); everything else is written before it is read
   launch_fill_u32(p->stream, hs.counter, 1, 0u);
@@ -1016,9 +1052,69 @@ mdi_status mdi_sample_topk_static(mdi_partition* p, uint32_t seq, const void* ac
   return hip_status();
 }
 
+mdi_status mdi_sample_batch(mdi_partition* p, uint32_t n, const uint32_t* seqs, const void* const* acts_in, float temperature,
+                            uint32_t top_k, uint64_t seed, const uint32_t* steps, int32_t* tokens_out, float* logits_out) {
+  if (!p) return MDI_ERR_ARG;
+  if (!(p->flags & MDI_HAS_HEAD)) return MDI_ERR_STATE;
+  if (n == 0) return MDI_OK;
+  if (!acts_in || !tokens_out || !seqs) return MDI_ERR_ARG;
+  const mdi_config& c = p->cfg;
+  if (!top_k || top_k > (uint32_t)kMaxTopK || (top_k > 1 && (!(temperature > 0.f) || !steps))) return MDI_ERR_ARG;
+  bool aligned = true;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (seqs[i] >= c.max_seqs || !acts_in[i]) return MDI_ERR_ARG;
+    aligned = aligned && ((uintptr_t)acts_in[i] & 15u) == 0;
+  }
+  const size_t V = c.vocab;
+  if (!p->hb_nwg || !aligned || n == 1) {
+    // one sample, or a head the shared pass does not cover: the output layers once per sample
+    for (uint32_t i = 0; i < n; ++i) {
+      float* lg = logits_out ? logits_out + (size_t)i * V : nullptr;
+      const mdi_status st = top_k == 1 ? mdi_sample_greedy(p, seqs[i], acts_in[i], tokens_out + i, lg)
+                                       : mdi_sample_topk(p, seqs[i], acts_in[i], temperature, top_k, seed, steps[i], tokens_out + i, lg);
+      if (st != MDI_OK) return st;
+    }
+    return hip_status();
+  }
+  for (uint32_t i = 0; i < n; i += kMaxBatch) {
+    const int m = (int)std::min<uint32_t>(kMaxBatch, n - i);
+    float* user = logits_out ? logits_out + (size_t)i * V : nullptr;
+    // the draw overwrites the logits it picks from: with top_k > 1 the pass writes the library's rows
+    float* rows = top_k > 1 ? p->hb_logits : user;
+    LogitsBatchArgs a{};
+    a.W = p->lm_head; a.N = (int)V; a.Kd = (int)c.d_model;
+    for (int j = 0; j < m; ++j) a.x[j] = acts_in[i + j];
+    a.m = m; a.g = p->lnf_g; a.eps = c.norm_eps;
+    a.out = rows; a.out_stride = (long)V;
+    a.cand = p->hb_cand; a.tag = next_head_tag(); a.counter = p->counters + c.n_head + 1;
+    a.err = p->herr; a.spin_limit = 1 << 21;
+    a.token_out = tokens_out + i;
+    launch_logits_batch(p->stream, p->hb_nwg, p->hb_lds, a);
+    if (top_k > 1) {
+      if (user && hipMemcpyAsync(user, rows, (size_t)m * V * 4, hipMemcpyDeviceToDevice, p->stream) != hipSuccess) return MDI_ERR_HIP;
+      SampleBatchArgs sb{};
+      sb.logits = rows; sb.stride = (long)V; sb.V = (int)V; sb.k = (int)std::min<uint32_t>(top_k, c.vocab);
+      sb.inv_t = 1.f / temperature; sb.key0 = (uint32_t)(seed & 0xFFFFFFFFu); sb.key1 = (uint32_t)(seed >> 32);
+      sb.token_out = tokens_out + i;
+      for (int j = 0; j < m; ++j) { sb.ctr0[j] = seqs[i + j]; sb.ctr1[j] = steps[i + j]; }
+      launch_sample_topk_batch(p->stream, m, sb);
+    }
+  }
+  return hip_status();
+}
+
 mdi_status mdi_partition_sync(mdi_partition* p) {
   if (!p) return MDI_ERR_ARG;
   if (hipStreamSynchronize(p->stream) != hipSuccess) return MDI_ERR_HIP;
+  if (p->herr) {                         // output layers: a candidate never showed its launch's tag
+    int e = 0;
+    if (hipMemcpy(&e, p->herr, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return MDI_ERR_HIP;
+    if (e) return MDI_ERR_HIP;
+    unsigned char* base = nullptr;       // the same word of the static scratch, if this device's was ever used
+    { std::lock_guard<std::mutex> lock(g_scratch_mutex); base = g_scratch_ptr[p->device]; }
+    if (base && hipMemcpy(&e, base + kStaticErrOff, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return MDI_ERR_HIP;
+    if (e) return MDI_ERR_HIP;
+  }
   if (p->err) {
     int e = 0;
     if (hipMemcpy(&e, p->err, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return MDI_ERR_HIP;
@@ -1109,6 +1205,7 @@ mdi_status mdi_partition_info(const mdi_partition* p, uint32_t what, uint64_t* v
     case 2: *value = p->use_step ? (uint64_t)p->step_lds : 0; return MDI_OK;
     case 3: *value = p->arena_bytes; return MDI_OK;
     case 4: *value = p->use_batch ? (uint64_t)kMaxBatch : 0; return MDI_OK;
+    case 6: *value = p->hb_nwg ? (uint64_t)kMaxBatch : 0; return MDI_OK;
     case 5: {
       const mdi_config& c = p->cfg;
       const uint64_t B = p->esz, d = c.d_model, H = c.n_head, K = c.n_kv_head, h = c.head_dim, F = c.d_ff;

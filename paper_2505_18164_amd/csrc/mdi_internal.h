@@ -92,6 +92,14 @@ struct SampleArgs {
   int32_t* token_out;
 };
 void launch_sample_topk(hipStream_t s, const SampleArgs& a);
+struct SampleBatchArgs {              // the same draw for up to 16 samples, one workgroup each
+  float* logits; long stride;         // row j = sample j's logits [V]; destroyed like SampleArgs::logits
+  int V, k; float inv_t;
+  uint32_t key0, key1;
+  int32_t* token_out;                 // [m]
+  uint32_t ctr0[16], ctr1[16];        // (sample, step) per sample
+};
+void launch_sample_topk_batch(hipStream_t s, int m, const SampleBatchArgs& a);
 
 // ---- prefill (first visit: T positions at once; Alg. 2) -------------------
 struct RowsInArgs {
@@ -204,10 +212,11 @@ struct LogitsArgs {
   const void* x; int x_kind;         // activation [Kd]
   int norm_kind; const float* g; const float* b; float eps;
   float* out;                        // logits [N] or nullptr
-  float* amax_val; int* amax_idx;    // per-workgroup candidates
+  tagged_t* cand; unsigned tag;      // per-workgroup candidates [workgroups][2] as (value | tag), (index | tag); tag = this call's
   unsigned* counter;                 // arrival counter, zero between calls
   int32_t* token_out;
   int part_floats;                   // LDS floats reserved for pair partials (multiple of 4)
+  int* err; int spin_limit;          // error word, set when a candidate never shows this call's tag
 };
 void launch_logits(hipStream_t s, int dtype, int nwg, size_t lds_bytes, const LogitsArgs& a);
 
@@ -253,6 +262,20 @@ struct BatchArgs {
   unsigned long long* trace;         // optional [workgroup][n_layer][5][8] timestamps (100 MHz ticks), or nullptr
   BatchSlot s[kMaxBatch];
 };
+// Output layers of up to kMaxBatch samples with one pass over the vocabulary matrix (step_w8.hip; bf16, RMSNorm).
+struct LogitsBatchArgs {
+  const void* W; int N, Kd;          // vocabulary matrix [N, Kd] bf16; Kd a multiple of 32, N * Kd * 2 < 2^32
+  const void* x[kMaxBatch]; int m;   // activations [Kd] bf16, 16-byte aligned, one per sample
+  const float* g; float eps;         // gain of the final RMSNorm
+  float* out; long out_stride;       // logits: row j = sample j, [N] floats each, rows out_stride floats apart; or nullptr
+  tagged_t* cand; unsigned tag;      // candidates [kMaxBatch][workgroups][2] as (value | tag), (index | tag); tag = this call's
+  unsigned* counter;                 // arrival counter, zero between calls
+  int32_t* token_out;                // [m]
+  int* err; int spin_limit;          // error word, set when a candidate never shows this call's tag
+};
+bool logits_batch_allow_lds(size_t lds_bytes);
+void launch_logits_batch(hipStream_t s, int nwg, size_t lds_bytes, const LogitsBatchArgs& a);
+
 void launch_step_batch(hipStream_t s, int G, size_t lds_bytes, const BatchArgs& a);
 bool step_batch_allow_lds(size_t lds_bytes);
 

@@ -1022,20 +1022,29 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
   }
   if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
   __syncthreads();
+  // The candidate crosses workgroups as two 8-byte words that carry the call's counter (value | tag, index | tag),
+  // stored and loaded at agent scope; the last workgroup to arrive reloads a word until its tag is this call's.  No
+  // fence: on this chip an agent-scope fence writes back a die's L2 (measured: about 5 us per wavefront that runs one).
   if (threadIdx.x == 0) {
     for (int k = 1; k < kStepWaves; ++k) if (better_logit(sv[k], si[k], bv, bi)) { bv = sv[k]; bi = si[k]; }
-    a.amax_val[wg] = bv; a.amax_idx[wg] = bi;
-    __threadfence();
-    const unsigned ticket = atomicAdd(a.counter, 1u);
+    __hip_atomic_store(a.cand + 2 * wg, ((tagged_t)a.tag << 32) | __float_as_uint(bv), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(a.cand + 2 * wg + 1, ((tagged_t)a.tag << 32) | (uint32_t)bi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned ticket = __hip_atomic_fetch_add(a.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = ticket == (unsigned)nwg - 1;
   }
   __syncthreads();
   if (s_last) {
-    __threadfence();
     bv = -INFINITY; bi = 0x7FFFFFFF;
     for (int k = threadIdx.x; k < nwg; k += kStepThreads) {
-      const float v = __hip_atomic_load(a.amax_val + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const int i = __hip_atomic_load(a.amax_idx + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      tagged_t uv = ld_raw(a.cand + 2 * k), ui = ld_raw(a.cand + 2 * k + 1);
+      int it = 0;
+      while ((uint32_t)(uv >> 32) != a.tag || (uint32_t)(ui >> 32) != a.tag) {
+        if (++it > a.spin_limit) { __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
+        __builtin_amdgcn_s_sleep(1);
+        uv = ld_raw(a.cand + 2 * k); ui = ld_raw(a.cand + 2 * k + 1);
+      }
+      const float v = __uint_as_float((uint32_t)uv);
+      const int i = (int)(uint32_t)ui;
       if (better_logit(v, i, bv, bi)) { bv = v; bi = i; }
     }
 #pragma unroll
@@ -1049,7 +1058,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
     if (threadIdx.x == 0) {
       for (int k = 1; k < kStepWaves; ++k) if (better_logit(sv[k], si[k], bv, bi)) { bv = sv[k]; bi = si[k]; }
       *a.token_out = bi;
-      *a.counter = 0u;
+      __hip_atomic_store(a.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }

@@ -19,7 +19,7 @@ MDI_F32, MDI_BF16 = 0, 1
 MDI_HAS_EMBED, MDI_HAS_HEAD = 1, 2
 
 EXPORTS = ["mdi_partition_bytes", "mdi_partition_create", "mdi_prefill", "mdi_prefill_chunk", "mdi_decode_step", "mdi_decode_steps", "mdi_decode_batch",
-           "mdi_sample_greedy", "mdi_sample_topk", "mdi_sample_topk_static", "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel",
+           "mdi_sample_greedy", "mdi_sample_topk", "mdi_sample_topk_static", "mdi_sample_batch", "mdi_partition_sync", "mdi_seq_reset", "mdi_seq_len", "mdi_step_bytes", "mdi_time_kernel",
            "mdi_partition_info", "mdi_partition_trace", "mdi_partition_destroy", "mdi_strerror"]
 
 
@@ -71,6 +71,7 @@ def lib():
         L.mdi_sample_greedy.argtypes = [vp, u32, vp, vp, vp]
         L.mdi_sample_topk.argtypes = [vp, u32, vp, C.c_float, u32, C.c_uint64, u32, vp, vp]
         L.mdi_sample_topk_static.argtypes = [vp, u32, vp, C.c_float, u32, C.c_uint64, u32, vp, vp]
+        L.mdi_sample_batch.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(vp), C.c_float, u32, C.c_uint64, C.POINTER(u32), vp, vp]
         L.mdi_partition_sync.argtypes = [vp]
         L.mdi_seq_reset.argtypes = [vp, u32]
         L.mdi_seq_len.argtypes = [vp, u32, C.POINTER(u32)]
@@ -82,7 +83,7 @@ def lib():
         L.mdi_partition_destroy.restype = None
         L.mdi_strerror.argtypes = [C.c_int]
         L.mdi_strerror.restype = C.c_char_p
-        for name in EXPORTS[:17]:
+        for name in EXPORTS[:18]:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -275,6 +276,20 @@ class Partition:
         if st != MDI_OK:
             raise MdiError(st, "mdi_sample_topk_static")
         return token_out
+
+    def sample_batch(self, seqs, acts_in, temperature=1.0, top_k=1, seed=0, steps=None, tokens_out=None, logits_out=None):
+        """Output layers of several samples with one pass over the vocabulary matrix (mdi_sample_batch)."""
+        n = len(seqs)
+        if tokens_out is None:
+            tokens_out = torch.empty((n,), dtype=torch.int32, device=self.device)
+        ids = (C.c_uint32 * n)(*seqs)
+        ins = (C.c_void_p * n)(*[t.data_ptr() for t in acts_in])
+        st_arr = (C.c_uint32 * n)(*steps) if steps is not None else None
+        st = lib().mdi_sample_batch(self._h, n, ids, ins, temperature, top_k, seed, st_arr,
+                                    _ptr(tokens_out), _ptr(logits_out))
+        if st != MDI_OK:
+            raise MdiError(st, "mdi_sample_batch")
+        return tokens_out
 
     # -- bookkeeping --------------------------------------------------------
     def sync(self):

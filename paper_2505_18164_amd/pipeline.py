@@ -9,7 +9,9 @@ input of the embedding stage.  Hand-offs between stages are stream events (the
 analogue of the paper's FIFO queues); the host never waits inside the loop.
 With `drain=True` a stage takes all the messages waiting in its queue in one
 call (mdi_decode_steps) instead of one call per message: on one GPU every
-sample's message is waiting when a stage gets its turn.
+sample's message is waiting when a stage gets its turn.  With `drain="shared"`
+the waiting messages also share one pass over the stage's weights
+(mdi_decode_batch) and over the vocabulary matrix (mdi_sample_batch).
 No arithmetic happens here.
 """
 from __future__ import annotations
@@ -47,7 +49,7 @@ class RecurrentPipeline:
         counter-based uniform number of (seed, s, j)."""
         self.sampling = sampling
         if drain:
-            return self._generate_draining(prompts, n_new, keep_logits, keep_hidden)
+            return self._generate_draining(prompts, n_new, keep_logits, keep_hidden, shared=(drain == "shared"))
         ns, dev = len(prompts), self.device
         d, V = self.head.d, self.head.V
         toks = torch.zeros((ns, n_new), dtype=torch.int32, device=dev)
@@ -97,14 +99,16 @@ class RecurrentPipeline:
             main.wait_event(done)
         return toks, logits, hidden
 
-    def _generate_draining(self, prompts, n_new, keep_logits, keep_hidden):
+    def _generate_draining(self, prompts, n_new, keep_logits, keep_hidden, shared=False):
         """Same schedule, but in every round after the first a stage takes the messages of all samples in one
-        call; a sample's values are those of the one-message-at-a-time schedule up to summation order."""
+        call; a sample's values are those of the one-message-at-a-time schedule up to summation order (shared:
+        within the storage type's parity bar, the vectors between the matrix products being rounded)."""
         ns, dev = len(prompts), self.device
         d, V = self.head.d, self.head.V
         tdt = self.head.tdtype
-        toks = torch.zeros((ns, n_new), dtype=torch.int32, device=dev)
-        logits = torch.zeros((ns, n_new, V), dtype=torch.float32, device=dev) if keep_logits else None
+        # stored round-major: a round's tokens (and logits) of all samples are contiguous, as one call writes them
+        toks = torch.zeros((n_new, ns), dtype=torch.int32, device=dev)
+        logits = torch.zeros((n_new, ns, V), dtype=torch.float32, device=dev) if keep_logits else None
         hidden = torch.zeros((ns, n_new, d), dtype=tdt, device=dev) if keep_hidden else None
         nb = len(self.blocks)
         act = [[torch.empty((d,), dtype=tdt, device=dev) for _ in range(nb)] for s in range(ns)]
@@ -130,15 +134,21 @@ class RecurrentPipeline:
                 if keep_hidden:
                     with torch.cuda.stream(hs):
                         hidden[s, r - 1].copy_(back[s])
-                self._token(s, r, back[s], toks[s, r - 1:r], logits[s, r - 1] if keep_logits else None)
+                if not shared:
+                    self._token(s, r, back[s], toks[r - 1, s:s + 1], logits[r - 1, s] if keep_logits else None)
+            if shared:
+                temperature, top_k, seed = self.sampling if self.sampling is not None else (1.0, 1, 0)
+                self.head.sample_batch(list(range(ns)), back, temperature, top_k, seed, [r - 1] * ns, toks[r - 1],
+                                       logits[r - 1] if keep_logits else None)
             last = torch.cuda.Event()
             last.record(hs)
             if r == n_new:
                 break
-            msgs = [toks[s, r - 1:r] for s in range(ns)]
+            msgs = [toks[r - 1, s:s + 1] for s in range(ns)]
             for i, p in enumerate(self.blocks):
                 p.stream.wait_event(last)
-                msgs = p.decode_steps(list(range(ns)), msgs, [act[s][i] for s in range(ns)])
+                step = p.decode_batch if shared else p.decode_steps
+                msgs = step(list(range(ns)), msgs, [act[s][i] for s in range(ns)])
                 last = torch.cuda.Event()
                 last.record(p.stream)
             back = msgs
@@ -146,7 +156,7 @@ class RecurrentPipeline:
             done = torch.cuda.Event()
             done.record(p.stream)
             main.wait_event(done)
-        return toks, logits, hidden
+        return toks.t(), (logits.transpose(0, 1) if keep_logits else None), hidden
 
     def reset(self, n_seqs):
         for p in self.blocks:

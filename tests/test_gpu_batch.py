@@ -151,3 +151,58 @@ def test_token_id_out_of_range_in_a_batched_pass_is_reported():
     with pytest.raises(mdi.MdiError) as e:
         g.sync()
     assert e.value.status == mdi.MDI_ERR_ARG
+
+
+def test_driver_with_shared_passes_on_a_three_node_ring():
+    """Alg. 1 / Alg. 2 through the recurrent-pipeline driver with every stage taking the waiting messages of all
+    samples through ONE pass over its weights and the starter drawing all their tokens with one pass over the
+    vocabulary matrix.  The oracle follows the GPU's tokens sample by sample (its own one-message-at-a-time
+    arithmetic, Sec. III-D), so every step is comparable at the bf16 bar whatever a near-tie decided."""
+    from paper_2505_18164_amd.pipeline import RecurrentPipeline
+    cfg = S.tiny(n_layer=6, dtype=S.DT_BF16, max_ctx=64, vocab=1003, **SHAPES["wide"])
+    w = scale_matrices(S.make_weights(cfg, 41, exercise=True), 2.0)
+    n_seqs, n_new = 5, 7
+    prompts = [p[:2 + 3 * s] for s, p in enumerate(S.make_prompts(cfg, 41, n_seqs, 16))]
+    bounds = [0, 2, 4, 6]
+    parts = [mdi.Partition(cfg, w, bounds[i], bounds[i + 1], has_embed=i == 0, has_head=i == 0, max_seqs=n_seqs,
+                           kv_page_tokens=8, stream=torch.cuda.Stream()) for i in range(3)]
+    assert all(p.info(4) == 16 for p in parts) and parts[0].info(6) == 16
+    pipe = RecurrentPipeline(parts, head=parts[0])
+    toks, logits, hidden = pipe.generate([dev_ids(p) for p in prompts], n_new, keep_logits=True, keep_hidden=True, drain="shared")
+    torch.cuda.synchronize()
+    for p in parts:
+        p.sync()
+    toks, logits, hidden = host(toks).astype(np.int64), host(logits), host(hidden)
+    ops = [O.Partition(cfg, w, bounds[i], bounds[i + 1], has_embed=i == 0, has_head=i == 0) for i in range(3)]
+    worst = 0.0
+    for s in range(n_seqs):
+        x = prompts[s]
+        for o in ops:
+            x = o.prefill(s, x)
+        x = x[-1]
+        for j in range(n_new):
+            worst = max(worst, check(hidden[s, j], x, cfg, ("hidden", s, j)))
+            xr = S.storage_round(x.astype(np.float32), cfg["dtype"])
+            want_tok, want = ops[0].sample_greedy(xr)
+            check(logits[s, j], want, cfg, ("logits", s, j))
+            assert toks[s, j] == int(np.flatnonzero(logits[s, j] == logits[s, j].max())[0])
+            top2 = np.sort(want)[-2:]
+            if top2[1] - top2[0] > 10 * np.abs(logits[s, j] - want).max():
+                assert toks[s, j] == want_tok
+            if j + 1 < n_new:
+                x = np.array([toks[s, j]], dtype=np.int32)
+                for o in ops:
+                    x = o.decode_step(s, x)
+    print(f"driver, shared passes: worst hidden rel-L2 {worst:.2e}", flush=True)
+    # sampled tokens: the same driver with draws from the top-k pmf gives every sample the draw of (seed, sample, step)
+    pipe.reset(n_seqs)
+    t2, lg2, _ = pipe.generate([dev_ids(p) for p in prompts], 3, keep_logits=True, drain="shared", sampling=(0.9, 8, 77))
+    torch.cuda.synchronize()
+    t2, lg2 = host(t2).astype(np.int64), host(lg2)
+    for s in range(n_seqs):
+        for j in range(3):
+            u = O.uniform01(77, s, j)
+            pmf = O.topk_pmf(lg2[s, j].astype(np.float64), 0.9, 8)
+            assert int(t2[s, j]) in pmf
+            if np.abs(np.cumsum(list(pmf.values())) - u).min() > 1e-5:
+                assert int(t2[s, j]) == O.sample_topk(lg2[s, j], 0.9, 8, u), (s, j)

@@ -1,0 +1,234 @@
+"""Output layers of several samples with one pass over the vocabulary matrix (mdi_sample_batch), through the C ABI,
+against the float64 oracle: Alg. 1 runs the output layers once per returning sample; here the samples that wait at
+the starter together share the pass.  Every sample's logits must meet the bar on their own, the token must be the
+argmax of (or the oracle's draw from) the logits the call returns, and heads the shared pass does not cover must
+give exactly what the one-sample entry points give."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mdi_oracle as O
+from paper_2505_18164_amd import mdi, synth as S
+from gpu_util import check, dev_acts, host, tol
+
+pytestmark = pytest.mark.gpu
+
+
+def head_pair(cfg, seed, exercise=True, scale=1.0):
+    L = cfg["n_layer"]
+    w = S.make_weights(cfg, seed, L, L, embed=cfg["tie_embed"], head=True, exercise=exercise)
+    if scale != 1.0:
+        w["lm_head"] = S.storage_round(w["lm_head"] * np.float32(scale), cfg["dtype"])
+        if cfg["tie_embed"]:
+            w["wte"] = w["lm_head"]
+    o = O.Partition(cfg, w, L, L, has_head=True)
+    g = mdi.Partition(cfg, w, L, L, has_head=True, max_seqs=32)
+    return o, g
+
+
+def activations(cfg, seed, n):
+    return [S.make_activations(cfg, seed, s, 1)[0] for s in range(n)]
+
+
+def lowest_argmax(v):
+    return int(np.flatnonzero(v == v.max())[0])
+
+
+SHAPES = {
+    # ragged vocabulary (not a multiple of 16), one column step tile
+    "v211_d64": dict(vocab=211, d_model=64),
+    # several tiles per block, rows past the end in the last block of several wavefronts
+    "v1003_d288": dict(vocab=1003, d_model=288),
+    # fewer blocks than wavefronts in the launch: most wavefronts idle
+    "v40_d128": dict(vocab=40, d_model=128),
+    # tied vocabulary matrix
+    "v4099_d512_tied": dict(vocab=4099, d_model=512, tie_embed=1),
+}
+
+
+def tiny_head_cfg(**kw):
+    base = dict(n_layer=1, dtype=S.DT_BF16, n_head=4, n_kv_head=2, head_dim=16, d_ff=96)
+    base.update(kw)
+    return S.tiny(**base)
+
+
+@pytest.mark.parametrize("n", [2, 5, 16, 19])
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_shared_pass_logits_and_greedy_tokens_against_the_oracle(name, n):
+    cfg = tiny_head_cfg(**SHAPES[name])
+    o, g = head_pair(cfg, 400 + n, scale=6.0)
+    assert g.info(6) == 16
+    V = cfg["vocab"]
+    xs = activations(cfg, 900 + n, n)
+    lg = torch.full((n, V), float("nan"), dtype=torch.float32, device="cuda:0")
+    seqs = [(3 * i + 1) % 32 for i in range(n)]
+    toks = g.sample_batch(seqs, [dev_acts(x, cfg) for x in xs], logits_out=lg)
+    g.sync()
+    got = host(lg)
+    toks = host(toks).astype(np.int64)
+    assert np.isfinite(got).all()
+    for i, x in enumerate(xs):
+        want_tok, want = o.sample_greedy(x)
+        check(got[i], want, cfg, (name, "logits of sample", i))
+        assert toks[i] == lowest_argmax(got[i])                       # the kernel's argmax is that of its own logits
+        top2 = np.sort(want)[-2:]
+        if top2[1] - top2[0] > 10 * np.abs(got[i] - want).max():
+            assert toks[i] == want_tok
+    # without a logits buffer the tokens are the same; a second call is bit-identical
+    toks2 = g.sample_batch(seqs, [dev_acts(x, cfg) for x in xs])
+    lg2 = torch.empty_like(lg)
+    toks3 = g.sample_batch(seqs, [dev_acts(x, cfg) for x in xs], logits_out=lg2)
+    g.sync()
+    assert np.array_equal(host(toks2).astype(np.int64), toks) and np.array_equal(host(toks3).astype(np.int64), toks)
+    assert torch.equal(lg, lg2)
+    # and each sample agrees with the one-sample entry point within the bar
+    one = torch.empty(V, dtype=torch.float32, device="cuda:0")
+    g.sample_greedy(seqs[0], dev_acts(xs[0], cfg), logits_out=one)
+    check(got[0], host(one).astype(np.float64), cfg, (name, "against mdi_sample_greedy"))
+
+
+def test_exact_ties_go_to_the_lowest_index():
+    """Identical rows of the vocabulary matrix met by an activation with a single non-zero element give identical
+    logits whatever the order of the additions: the lower index wins, inside a block of 16 rows (5 and 7), across
+    wavefronts and workgroups (5 and 900; 17, 18 and the last row)."""
+    cfg = tiny_head_cfg(vocab=1003, d_model=64)
+    L = cfg["n_layer"]
+    w = S.make_weights(cfg, 31, L, L, embed=False, head=True, exercise=True)
+    x = activations(cfg, 32, 3)
+    x[0] = np.zeros_like(x[0])
+    x[0][9] = 2.0
+    big = np.zeros(cfg["d_model"], dtype=np.float32)
+    big[9] = 3.0 * np.sign(w["lnf_g"][9])
+    for rows in ((5, 7), (5, 900), (17, 18, 1002)):
+        w2 = dict(w)
+        w2["lm_head"] = w["lm_head"].copy()
+        for r in rows:
+            w2["lm_head"][r] = big
+        g = mdi.Partition(cfg, w2, L, L, has_head=True, max_seqs=4)
+        lg = torch.empty((3, cfg["vocab"]), dtype=torch.float32, device="cuda:0")
+        toks = host(g.sample_batch([0, 1, 2], [dev_acts(v, cfg) for v in x], logits_out=lg)).astype(np.int64)
+        got = host(lg)
+        assert all(got[0][r] == got[0][rows[0]] for r in rows) and got[0][rows[0]] == got[0].max()
+        assert toks[0] == rows[0]
+        assert all(toks[i] == lowest_argmax(got[i]) for i in range(3))
+
+
+def test_shared_pass_draws_follow_the_oracle_sampler():
+    """Alg. 1 samples the output distribution: with top_k > 1 every sample's token is the oracle's draw from the
+    logits the call returns, at the counter-based uniform number of (seed, sample, step) - the same decision in the
+    same precision, so equal unless the number lies at a boundary of the cumulative distribution."""
+    cfg = tiny_head_cfg(vocab=211, d_model=64)
+    o, g = head_pair(cfg, 77, scale=8.0)
+    n, seed, temperature, top_k = 13, 0xFEDCBA9876543210, 0.8, 12
+    xs = activations(cfg, 78, n)
+    xd = [dev_acts(x, cfg) for x in xs]
+    seqs = list(range(n))
+    lg = torch.empty((n, cfg["vocab"]), dtype=torch.float32, device="cuda:0")
+    decided = 0
+    for rnd in range(30):
+        steps = [rnd * 3 + i for i in range(n)]
+        toks = host(g.sample_batch(seqs, xd, temperature, top_k, seed, steps, logits_out=lg)).astype(np.int64)
+        got = host(lg)
+        for i in range(n):
+            if rnd == 0:
+                check(got[i], o.logits(xs[i]), cfg, ("logits of sample", i))
+            u = O.uniform01(seed, seqs[i], steps[i])
+            pmf = O.topk_pmf(got[i].astype(np.float64), temperature, top_k)
+            assert int(toks[i]) in pmf
+            if np.abs(np.cumsum(list(pmf.values())) - u).min() > 1e-5:
+                decided += 1
+                assert int(toks[i]) == O.sample_topk(got[i], temperature, top_k, u), (rnd, i)
+    assert decided >= 0.95 * 30 * n
+    # the same draw as the one-sample entry point makes from its own logits, sample by sample
+    one = torch.empty(cfg["vocab"], dtype=torch.float32, device="cuda:0")
+    toks = host(g.sample_batch(seqs, xd, temperature, top_k, seed, [5] * n)).astype(np.int64)
+    same = 0
+    for i in range(n):
+        t = int(g.sample_topk(seqs[i], xd[i], temperature, top_k, seed, 5, logits_out=one).item())
+        same += t == toks[i]
+    assert same >= n - 2                       # logits differ in the last bits between the two paths
+    # top_k = 1 is greedy whatever the seed and temperature
+    a = host(g.sample_batch(seqs, xd, 0.3, 1, 99, [1] * n)).astype(np.int64)
+    b = host(g.sample_batch(seqs, xd)).astype(np.int64)
+    assert np.array_equal(a, b)
+    g.sync()
+
+
+@pytest.mark.parametrize("which", ["f32", "layernorm", "per_op", "odd_width"])
+def test_heads_outside_the_shared_pass_are_served_one_by_one(which):
+    kw = dict(vocab=211, d_model=64)
+    if which == "f32":
+        kw["dtype"] = S.DT_F32
+    if which == "layernorm":
+        kw["norm_kind"] = S.NORM_LAYERNORM
+    if which == "odd_width":
+        kw.update(d_model=48, n_head=3, n_kv_head=3)
+    cfg = tiny_head_cfg(**kw)
+    L = cfg["n_layer"]
+    w = S.make_weights(cfg, 5, L, L, embed=False, head=True, exercise=True)
+    g = mdi.Partition(cfg, w, L, L, has_head=True, max_seqs=8, decode_path=1 if which == "per_op" else 0)
+    assert g.info(6) == 0
+    xs = [dev_acts(x, cfg) for x in activations(cfg, 6, 5)]
+    lg = torch.empty((5, cfg["vocab"]), dtype=torch.float32, device="cuda:0")
+    toks = g.sample_batch([0, 1, 2, 3, 4], xs, logits_out=lg)
+    drawn = g.sample_batch([0, 1, 2, 3, 4], xs, 0.9, 7, 11, [3, 4, 5, 6, 7])
+    one = torch.empty(cfg["vocab"], dtype=torch.float32, device="cuda:0")
+    for i in range(5):
+        t = g.sample_greedy(i, xs[i], logits_out=one)
+        assert int(t.item()) == int(toks[i].item()) and torch.equal(one, lg[i])
+        assert int(g.sample_topk(i, xs[i], 0.9, 7, 11, 3 + i).item()) == int(drawn[i].item())
+    g.sync()
+
+
+def test_argument_errors():
+    cfg = tiny_head_cfg(vocab=211, d_model=64)
+    o, g = head_pair(cfg, 3)
+    xs = [dev_acts(x, cfg) for x in activations(cfg, 4, 2)]
+
+    def status(*a, **k):
+        with pytest.raises(mdi.MdiError) as e:
+            g.sample_batch(*a, **k)
+        return e.value.status
+
+    assert status([0, 40], xs) == mdi.MDI_ERR_ARG                      # sample id out of range
+    assert status([0, 1], xs, 1.0, 65, 1, [0, 0]) == mdi.MDI_ERR_ARG   # top_k beyond 64
+    assert status([0, 1], xs, 0.0, 5, 1, [0, 0]) == mdi.MDI_ERR_ARG    # temperature must be positive for a draw
+    assert status([0, 1], xs, 1.0, 5, 1, None) == mdi.MDI_ERR_ARG      # a draw needs the step counters
+    assert g.sample_batch([], []).numel() == 0                         # nothing to do
+    L = cfg["n_layer"]
+    w = S.make_weights(cfg, 3, 0, 1, embed=False, head=False)
+    body = mdi.Partition(cfg, w, 0, 1, max_seqs=2)
+    with pytest.raises(mdi.MdiError) as e:
+        body.sample_batch([0, 1], xs)
+    assert e.value.status == mdi.MDI_ERR_STATE
+    # an activation that is not 16-byte aligned is served by the one-sample path
+    buf = torch.zeros(cfg["d_model"] + 1, dtype=torch.bfloat16, device="cuda:0")
+    buf[1:] = xs[0]
+    t = g.sample_batch([0, 1], [buf[1:], xs[1]])
+    assert int(t[0].item()) == int(g.sample_greedy(0, xs[0]).item())
+    g.sync()
+
+
+@pytest.mark.parametrize("workload", [4, 5])
+def test_benchmark_heads_sixteen_samples(workload):
+    """The 7B- and 8B-shaped output layers (32000 x 4096 and 128256 x 4096, bf16): 16 samples in one pass, every
+    sample against the oracle."""
+    cfg, seed = S.WORKLOADS[workload]["cfg"](), S.workload_seed(workload)
+    L = cfg["n_layer"]
+    w = S.make_weights(cfg, seed, L, L, embed=False, head=True)
+    o = O.Partition(cfg, w, L, L, has_head=True)
+    g = mdi.Partition(cfg, w, L, L, has_head=True, max_seqs=16)
+    assert g.info(6) == 16
+    n = 16
+    xs = activations(cfg, seed + 9, n)
+    lg = torch.empty((n, cfg["vocab"]), dtype=torch.float32, device="cuda:0")
+    toks = host(g.sample_batch(list(range(n)), [dev_acts(x, cfg) for x in xs], logits_out=lg)).astype(np.int64)
+    g.sync()
+    got = host(lg)
+    for i in range(n):
+        want_tok, want = o.sample_greedy(xs[i])
+        check(got[i], want, cfg, ("workload", workload, "logits of sample", i))
+        assert toks[i] == lowest_argmax(got[i])
+        top2 = np.sort(want)[-2:]
+        if top2[1] - top2[0] > 10 * np.abs(got[i] - want).max():
+            assert toks[i] == want_tok

@@ -4,12 +4,14 @@ One step = one later visit of one sample (Sec. III-D) to a partition (all its
 layers: norm, fused QKV + RoPE + KV append, paged attention, output projection,
 MLP).  The N samples in flight are visited round-robin, so consecutive steps
 read different KV caches (the rotating-cache access pattern).  By default the
-messages of all N samples are handed over per call (mdi_decode_steps: the
-node's input queue, Sec. III-A, drained in one call); `--queue 1` hands them
-over one at a time (mdi_decode_step, the paper's own rule), and the default run
-reports that rate too.  Inputs, weights and caches are resident in HBM before
-the timed region; prompts are prefilled (first visit) before it and timed
-separately.
+messages of all N samples are handed over per call (the node's input queue,
+Sec. III-A, drained in one call) and, where the partition supports it, share
+ONE pass over the weights (mdi_decode_batch); the roofline then counts the
+matrices once per launch.  `--passes per-message` keeps one pass per message
+(mdi_decode_steps), `--queue 1` hands the messages over one at a time
+(mdi_decode_step, the paper's own rule); the default run reports both of those
+rates too.  Inputs, weights and caches are resident in HBM before the timed
+region; prompts are prefilled (first visit) before it and timed separately.
 
 Any --steps / --warmup is accepted: exactly --steps steps are timed (the last
 call of a window carries fewer messages when the count does not divide), and a
@@ -40,7 +42,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the decode kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this script, keyed by
 # (workload, messages per launch, batched arithmetic).  A figure is only reported while the kernel sources still
 # hash to what they were when it was measured; otherwise `roofline.traffic` is null.
-KERNEL_SOURCES = ("step_impl.h", "step_batch.h", "step_w4.hip", "step_w8.hip", "device_utils.h", "mdi_internal.h")
+KERNEL_SOURCES = ("step_impl.h", "step_batch.h", "head_batch.h", "step_w4.hip", "step_w8.hip", "device_utils.h", "mdi_internal.h")
 MEASURED_TRAFFIC = {}
 
 

@@ -25,8 +25,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int BQ = 128;       // queries per workgroup (32 per wavefront)
 constexpr int BK = 64;        // keys per step
 
-// values of the first visit: fp32 rows of the fused QKV product -> bf16 [kv head][h][Tp] (zero beyond T)
-__global__ __launch_bounds__(256) void k_v_transpose(const float* qkv, int T, int Tp, int n_rows, int v_off, int h, bf16_t* vt) {
+// values of the T new positions: fp32 rows of the fused QKV product -> bf16 [kv head][h][ldk], row t at column
+// pos0 + t; columns up to pos0 + n_cols - 1 are cleared (keys nobody may see, but finite)
+__global__ __launch_bounds__(256) void k_v_transpose(const float* qkv, int T, int n_cols, int pos0, int ldk, int n_rows, int v_off, int h, bf16_t* vt) {
   __shared__ bf16_t tile[64][64 + 2];
   const int t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;          // 64 positions x 64 channels of the K*h value channels
   for (int i = threadIdx.x; i < 64 * 64; i += 256) {
@@ -37,7 +38,34 @@ __global__ __launch_bounds__(256) void k_v_transpose(const float* qkv, int T, in
   __syncthreads();
   for (int i = threadIdx.x; i < 64 * 64; i += 256) {
     const int c = i >> 6, tt = i & 63;
-    vt[(long)(c0 + c) * Tp + t0 + tt] = tile[tt][c];          // channel c0 + c = kv head * h + element
+    if (t0 + tt < n_cols) vt[(long)(c0 + c) * ldk + pos0 + t0 + tt] = tile[tt][c];          // channel c0 + c = kv head * h + element
+  }
+}
+
+// A later piece of a first visit attends to the positions already in the cache as well (Alg. 2: the cache is
+// extended, never rebuilt): their keys and values are brought from the sample's pages into the operand arrays, keys
+// as they are, values transposed.  One workgroup per (64 positions, 64 channels of one kv head).
+__global__ __launch_bounds__(256) void k_cache_gather(const bf16_t* pool, const int32_t* table, int n_pos, int K, int h, int pt, int ldk,
+                                                      bf16_t* k_bf, bf16_t* vt) {
+  __shared__ bf16_t tile[64][64 + 2];
+  const int t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int kvh = c0 / h, e0 = c0 - kvh * h;
+  const long pt_h = (long)pt * h;
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int tt = i >> 6, c = i & 63;
+    const int t = t0 + tt;
+    if (t < n_pos) {
+      const long base = ((long)table[t / pt] * K + kvh) * 2 * pt_h + (long)(t % pt) * h + e0 + c;
+      k_bf[((long)kvh * ldk + t) * h + e0 + c] = pool[base];
+      tile[tt][c] = pool[base + pt_h];
+    } else {
+      tile[tt][c] = (bf16_t)0;
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int c = i >> 6, tt = i & 63;
+    if (t0 + tt < n_pos) vt[(long)(c0 + c) * ldk + t0 + tt] = tile[tt][c];
   }
 }
 
@@ -81,9 +109,10 @@ __global__ __launch_bounds__(512) void k_flash_prefill(FlashArgs a) {
     for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
   float m = -1e30f, l = 0.f;
 
-  const bf16_t* kbase = a.k + (long)kvh * a.Tp * HD;
-  const bf16_t* vbase = a.vt + (long)kvh * HD * a.Tp;
-  const int n_kb = min((q0 + BQ + BK - 1) / BK, a.Tp / BK);      // key blocks any query of this workgroup may see
+  const bf16_t* kbase = a.k + (long)kvh * a.ldk * HD;
+  const bf16_t* vbase = a.vt + (long)kvh * HD * a.ldk;
+  const int p0 = a.p0;                                           // position of query 0: keys 0 .. p0 + query are visible
+  const int n_kb = min((p0 + q0 + BQ + BK - 1) / BK, a.Tk / BK); // key blocks any query of this workgroup may see
   const int n_it = (n_kb + 1) / 2;                               // steps: block 2 it + grp each
 
   // staging registers: the next block's keys and values travel global -> registers during the arithmetic
@@ -96,7 +125,7 @@ __global__ __launch_bounds__(512) void k_flash_prefill(FlashArgs a) {
       const int p = tid + i * 256;                               // piece p: key p / (HD/8), elements 8 (p % (HD/8))
       kreg[i] = *reinterpret_cast<const u32x4*>(kbase + ((long)kb * BK + p / (HD / 8)) * HD + 8 * (p % (HD / 8)));
       const int c = p / (BK / 8), j = p % (BK / 8);              // channel c, keys [8 j, 8 j + 8) of the block
-      vreg[i] = *reinterpret_cast<const u32x4*>(vbase + (long)c * a.Tp + (long)kb * BK + 8 * j);
+      vreg[i] = *reinterpret_cast<const u32x4*>(vbase + (long)c * a.ldk + (long)kb * BK + 8 * j);
     }
   };
   auto stash = [&]() {
@@ -119,7 +148,7 @@ __global__ __launch_bounds__(512) void k_flash_prefill(FlashArgs a) {
     __syncthreads();
     if (it + 1 < n_it) fetch(kb + 2);
     const int k0 = kb * BK;
-    if (kb >= n_kb || k0 > qw0 + 31) continue;                   // no block, or this wavefront's queries see none of these keys
+    if (kb >= n_kb || k0 > p0 + qw0 + 31) continue;              // no block, or this wavefront's queries see none of these keys
 
     // ---- S^T = K Q^T: two tiles of 32 keys x 32 queries
     f32x16 s[2];
@@ -134,13 +163,13 @@ __global__ __launch_bounds__(512) void k_flash_prefill(FlashArgs a) {
     }
     // ---- causal mask and the lane's share of the row statistics (row of S = column here = this lane's query)
     float mloc = -1e30f;
-    const bool diag = k0 + BK - 1 > qw0;
+    const bool diag = k0 + BK - 1 > p0 + qw0;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = k0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
-        if (diag && key > query) s[t][r] = -1e30f;
+        if (diag && key > p0 + query) s[t][r] = -1e30f;
         mloc = fmaxf(mloc, s[t][r]);
       }
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
@@ -230,9 +259,16 @@ constexpr size_t flash_lds_bytes() {
 
 bool flash_supported(int dtype, int h) { return dtype == MDI_BF16 && (h == 64 || h == 128); }
 
-void launch_v_transpose(hipStream_t s, const float* qkv, int T, int Tp, int H, int K, int h, bf16_t* vt) {
-  const dim3 grid(Tp / 64, K * h / 64);
-  hipLaunchKernelGGL(k_v_transpose, grid, dim3(256), 0, s, qkv, T, Tp, (H + 2 * K) * h, (H + K) * h, h, vt);
+void launch_v_transpose(hipStream_t s, const float* qkv, int T, int n_cols, int pos0, int ldk, int H, int K, int h, bf16_t* vt) {
+  const dim3 grid((n_cols + 63) / 64, K * h / 64);
+  hipLaunchKernelGGL(k_v_transpose, grid, dim3(256), 0, s, qkv, T, n_cols, pos0, ldk, (H + 2 * K) * h, (H + K) * h, h, vt);
+}
+
+void launch_cache_gather(hipStream_t s, const void* pool, const int32_t* table, int n_pos, int K, int h, int pt, int ldk,
+                         bf16_t* k_bf, bf16_t* vt) {
+  if (n_pos <= 0) return;
+  const dim3 grid((n_pos + 63) / 64, K * h / 64);
+  hipLaunchKernelGGL(k_cache_gather, grid, dim3(256), 0, s, (const bf16_t*)pool, table, n_pos, K, h, pt, ldk, k_bf, vt);
 }
 
 void launch_flash_prefill(hipStream_t s, const FlashArgs& a) {

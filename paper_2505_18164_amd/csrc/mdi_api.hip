@@ -231,7 +231,8 @@ size_t carve(mdi_partition* p, void* arena) {
     p->p_o = cv.take(T * H * h * B);
     p->p_u = cv.take(T * F * B);
     if (flash_supported(c.dtype, (int)h)) {
-      p->Tp = (int)((T + 127) / 128 * 128);
+      // keys and values^T of every position a first visit in pieces can reach: up to max_ctx, in blocks of 128
+      p->Tp = (int)(((size_t)c.max_ctx + 127) / 128 * 128);
       p->p_qb = (bf16_t*)cv.take(T * H * h * 2);
       p->p_kc = (bf16_t*)cv.take((size_t)K * p->Tp * h * 2);
       p->p_vt = (bf16_t*)cv.take((size_t)K * h * p->Tp * 2);
@@ -601,15 +602,20 @@ mdi_status prefill_rows(mdi_partition* p, uint32_t seq, const void* acts_in, uin
     launch_norm_rows(s, n1);
     GemmArgs g1{p->p_xn, L.wqkv, L.bqkv, (int)T, (H + 2 * K) * h, d, p->p_qkv, nullptr};
     launch_gemm(s, c.dtype, GEPI_F32_BIAS, g1);
-    const bool flash = p->p_qb != nullptr && pos0 == 0;   // later chunks attend to the cache as well: per-row attention
+    // Attention on the matrix cores over operand arrays that hold the keys and the transposed values of positions
+    // 0 .. pos0 + T - 1: the new ones written by the scatter and the transpose below, the earlier ones (a later piece
+    // of a first visit) brought from the cache pages first.  The arrays are packed to what this call needs.
+    const bool flash = p->p_qb != nullptr;
     const int Tp = ((int)T + 127) / 128 * 128;
+    const int Tk = (pos0 + (int)T + 127) / 128 * 128;      // keys, padded; at most p->Tp
     const float scale = 1.f / sqrtf((float)h);
+    if (flash && pos0) launch_cache_gather(s, L.kv, drow, pos0, K, h, p->pt, Tk, p->p_kc, p->p_vt);
     RopeScatterArgs rs{p->p_qkv, (int)T, H, K, h, p->pt, p->rope, flash ? nullptr : p->p_q, L.kv, drow, (int)c.dtype,
-                       flash ? p->p_qb : nullptr, flash ? p->p_kc : nullptr, Tp, scale, pos0};
+                       flash ? p->p_qb : nullptr, flash ? p->p_kc : nullptr, Tk, Tk - pos0, scale, pos0};
     launch_rope_scatter(s, rs);
     if (flash) {
-      launch_v_transpose(s, p->p_qkv, (int)T, Tp, H, K, h, p->p_vt);
-      FlashArgs fa{p->p_qb, p->p_kc, p->p_vt, (bf16_t*)p->p_o, (int)T, Tp, H, K, h};
+      launch_v_transpose(s, p->p_qkv, (int)T, Tk - pos0, pos0, Tk, H, K, h, p->p_vt);
+      FlashArgs fa{p->p_qb, p->p_kc, p->p_vt, (bf16_t*)p->p_o, (int)T, Tp, H, K, h, pos0, Tk, Tk};
       launch_flash_prefill(s, fa);
     } else {
       AttnArgs at{};

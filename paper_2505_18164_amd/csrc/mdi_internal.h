@@ -137,22 +137,28 @@ struct RopeScatterArgs {
   int dtype;
   // operands of the matrix-core attention of the first visit (bf16), or nullptr
   bf16_t* q_bf;           // [T][H*h], rotated and scaled by `scale`
-  bf16_t* k_bf;           // [K][Tp][h], rotated; rows T..Tp-1 are zero-filled
-  int Tp; float scale;
+  bf16_t* k_bf;           // [K][ldk][h], rotated; row pos0 + t holds position pos0 + t, rows up to pos0 + n_rows - 1 are zero-filled
+  int ldk; int n_rows;    // positions the operand arrays have room for per kv head; rows to write or clear (>= T)
+  float scale;
   int pos0;               // position of row 0
 };
 void launch_rope_scatter(hipStream_t s, const RopeScatterArgs& a);
 
 // Causal attention of a first visit on the matrix cores (bf16 operands, fp32 accumulation and softmax).
 struct FlashArgs {
-  const bf16_t* q;        // [T][H*h] rotated, scaled
-  const bf16_t* k;        // [K][Tp][h]
-  const bf16_t* vt;       // [K][h][Tp]: values transposed, so that the contraction index (position) is contiguous
+  const bf16_t* q;        // [T][H*h] rotated, scaled: the queries of positions p0 .. p0 + T - 1
+  const bf16_t* k;        // [K][ldk][h]: keys of positions 0 .. p0 + T - 1, finite up to Tk - 1
+  const bf16_t* vt;       // [K][h][ldk]: values transposed, so that the contraction index (position) is contiguous
   bf16_t* out;            // [T][H*h]
-  int T, Tp, H, K, h;
+  int T, Tp, H, K, h;     // Tp: T rounded up to 128 (the query grid)
+  int p0, Tk, ldk;        // Tk: p0 + T rounded up to 64 (at most ldk)
 };
 bool flash_supported(int dtype, int h);
-void launch_v_transpose(hipStream_t s, const float* qkv, int T, int Tp, int H, int K, int h, bf16_t* vt);
+// values of T new positions (fp32 rows of the fused QKV product) -> vt[.][pos0 + t], zeros up to column pos0 + n_cols - 1
+void launch_v_transpose(hipStream_t s, const float* qkv, int T, int n_cols, int pos0, int ldk, int H, int K, int h, bf16_t* vt);
+// keys and values of positions 0 .. n_pos - 1 from a layer's cache pages (bf16) into the attention operand arrays
+void launch_cache_gather(hipStream_t s, const void* pool, const int32_t* table, int n_pos, int K, int h, int pt, int ldk,
+                         bf16_t* k_bf, bf16_t* vt);
 void launch_flash_prefill(hipStream_t s, const FlashArgs& a);
 
 // ---- whole decode step as one persistent launch ------------------------------

@@ -411,7 +411,7 @@ __global__ __launch_bounds__(kBlock) void k_rope_scatter(RopeScatterArgs a) {
   const int t = blockIdx.x, h = a.h, half = h >> 1;
   const int n_heads = a.H + 2 * a.K;
   if (t >= a.T) {                                   // padding rows of the attention operand: keys nobody may see, but finite
-    for (int i = threadIdx.x; i < a.K * h; i += kBlock) a.k_bf[((long)(i / h) * a.Tp + t) * h + i % h] = 0;
+    for (int i = threadIdx.x; i < a.K * h; i += kBlock) a.k_bf[((long)(i / h) * a.ldk + a.pos0 + t) * h + i % h] = 0;
     return;
   }
   const float* row = a.qkv + (long)t * n_heads * h;
@@ -457,7 +457,7 @@ __global__ __launch_bounds__(kBlock) void k_rope_scatter(RopeScatterArgs a) {
       put4(a.pool, bf, o, v0);
       put4(a.pool, bf, o + half, v1);
       if (a.k_bf && !is_v) {
-        const long k = ((long)kvh * a.Tp + t) * h + i;
+        const long k = ((long)kvh * a.ldk + pos) * h + i;
         put4(a.k_bf, true, k, v0);
         put4(a.k_bf, true, k + half, v1);
       }
@@ -465,7 +465,7 @@ __global__ __launch_bounds__(kBlock) void k_rope_scatter(RopeScatterArgs a) {
   }
 }
 void launch_rope_scatter(hipStream_t s, const RopeScatterArgs& a) {
-  hipLaunchKernelGGL(k_rope_scatter, dim3(a.k_bf ? a.Tp : a.T), dim3(kBlock), 0, s, a);
+  hipLaunchKernelGGL(k_rope_scatter, dim3(a.k_bf ? a.n_rows : a.T), dim3(kBlock), 0, s, a);
 }
 
 // ---------------------------------------------------------------------------

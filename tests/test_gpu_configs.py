@@ -225,6 +225,32 @@ def test_c4_llama2_7b_layers_8_15_bf16():
     _say(f"C4: one pass for 8, samples 0/2/5 worst rel-L2 {worst_b:.2e} against the oracle; all 8 against one message at a time {worst_1:.2e}")
 
 
+def test_c4_first_visit_in_pieces_of_256():
+    """A 1024-token first visit handed over in pieces (mdi_prefill_chunk): every piece attends to the positions
+    already in the cache through the same matrix-core attention as a whole first visit; rows against the oracle's
+    one first visit of the whole prompt, another sample's later visit between the pieces, then later visits."""
+    cfg, seed = S.WORKLOADS[4]["cfg"](), S.workload_seed(4)
+    w = S.make_weights(cfg, seed, 8, 10, embed=False, head=False)
+    op = O.Partition(cfg, w, 8, 10)
+    g = mdi.Partition(cfg, w, 8, 10, max_seqs=2, kv_page_tokens=64, max_prefill=1024)
+    a = S.make_activations(cfg, seed + 5, 0, 1024)
+    want = op.prefill(0, a)
+    b = S.make_activations(cfg, seed + 5, 1, 90)
+    check(g.prefill(1, dev_acts(b, cfg)), op.prefill(1, b), cfg, "other sample, first visit")
+    at = 0
+    for piece in (256, 256, 300, 1, 211):                          # the verdict's 256s, a ragged one, a single position
+        got = g.prefill_chunk(0, dev_acts(a[at:at + piece], cfg))
+        check(got, want[at:at + piece], cfg, ("C4 piece at", at))
+        at += piece
+        y = S.make_activations(cfg, seed + 5, 1, 1, step=at)[0]
+        check(g.decode_step(1, dev_acts(y, cfg)), op.decode_step(1, y), cfg, ("other sample between pieces", at))
+    assert at == 1024 and g.seq_len(0) == 1024
+    for step in range(2):
+        x = S.make_activations(cfg, seed + 5, 0, 1, step=step + 1)[0]
+        check(g.decode_step(0, dev_acts(x, cfg)), op.decode_step(0, x), cfg, ("later visit", step))
+    g.sync()
+
+
 def test_c4_llama2_7b_to_max_context():
     cfg, seed = S.WORKLOADS[4]["cfg"](), S.workload_seed(4)
     w = S.make_weights(cfg, seed, 8, 9, embed=False, head=False)

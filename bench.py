@@ -68,6 +68,10 @@ def measured_traffic(workload, in_launch, batched):
 def parse(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--paper-run", choices=["nanollama", "tinyllama"], default=None,
+                    help="instead of the partition benchmark: the paper's generation experiment on this model shape "
+                         "(3 samples x 800 tokens from one-token prompts, its cuts and an unbalanced one)")
+    ap.add_argument("--paper-tokens", type=int, default=800, help="tokens per sample of --paper-run")
     ap.add_argument("--steps", type=int, default=1600)
     ap.add_argument("--warmup", type=int, default=80)
     ap.add_argument("--workload", type=int, default=4, help="index into the five benchmark configs (1-5)")
@@ -149,6 +153,85 @@ def cpu_baseline(cfg, w, lo, hi, seed, S, prompt, embed):
             "host_cores_available": len(os.sched_getaffinity(0))}
 
 
+def paper_run(args, torch, mdi, S):
+    """The paper's rate experiment (Sec. IV-B: 3 samples, 800 tokens each, from a one-token prompt) on the shapes and
+    cuts it names (Sec. IV-A: the 304M model whole, 5/7 and 2/5/5; TinyLlama 10/12 and 6/8/8), random-init weights,
+    plus a deliberately unbalanced cut.  Every node of the ring is a partition on this one GPU, so the nodes take
+    turns instead of working side by side: the generation rate does not grow with the number of nodes here.  What
+    the cut decides on real nodes - how long each waits for the slowest (Sec. III-C) - is reported from each
+    stage's measured time per message."""
+    from paper_2505_18164_amd.pipeline import RecurrentPipeline
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    n_seqs, n_new = 3, args.paper_tokens
+    if args.paper_run == "nanollama":
+        shapes = {"fp32 (the paper's precision)": S.nanollama(S.DT_F32, 2048), "bf16": S.nanollama(S.DT_BF16, 2048)}
+        cuts = {"1 node": (12,), "2 nodes 5/7": (5, 7), "3 nodes 2/5/5": (2, 5, 5), "3 nodes 1/1/10 (unbalanced)": (1, 1, 10)}
+    else:
+        shapes = {"bf16": S.tinyllama(S.DT_BF16, 2048)}
+        cuts = {"1 node": (22,), "2 nodes 10/12": (10, 12), "3 nodes 6/8/8": (6, 8, 8), "3 nodes 2/2/18 (unbalanced)": (2, 2, 18)}
+    seed = 20250518 + (11 if args.paper_run == "nanollama" else 12)
+    out = {"metric": f"generated tokens/s, {n_seqs} samples x {n_new} tokens from one-token prompts ({args.paper_run} shape)",
+           "unit": "tokens/s", "n_gpus": 1, "data": "synthetic", "higher_is_better": True, "runs": []}
+    for sname, cfg in shapes.items():
+        w = S.make_weights(cfg, seed)
+        prompts = [torch.from_numpy(p[:1]).to(dev) for p in S.make_prompts(cfg, seed, n_seqs, 4)]
+        for cname, cut in cuts.items():
+            bounds = [0]
+            for c in cut:
+                bounds.append(bounds[-1] + c)
+            parts = [mdi.Partition(cfg, w, bounds[i], bounds[i + 1], has_embed=i == 0, has_head=i == 0, max_seqs=n_seqs,
+                                   kv_page_tokens=64, max_prefill=8, stream=torch.cuda.Stream()) for i in range(len(cut))]
+            pipe = RecurrentPipeline(parts, head=parts[0])
+            rec = {"storage": sname, "cut": cname}
+            modes = [("one message per call (the paper's rule)", False), ("queue drained per call", True)]
+            if all(p.info(4) for p in parts) and parts[0].info(6):
+                modes.append(("queue drained, one pass over the weights", "shared"))
+            for mname, drain in modes:
+                best = None
+                for rep in range(2):                       # the first run also loads the kernels
+                    pipe.reset(n_seqs)
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    toks, _, _ = pipe.generate(prompts, n_new, drain=drain)
+                    torch.cuda.synchronize()
+                    dt = time.perf_counter() - t0
+                    best = dt if best is None else min(best, dt)
+                for p in parts:
+                    p.sync()
+                rec[mname] = {"tokens_per_s": n_seqs * n_new / best, "seconds": best}
+            # time per message of every stage, alone, at a context of about half the run: what each node of a real
+            # ring would be busy for per token; the others wait for the slowest (Sec. III-C)
+            stage_ms = []
+            for i, p in enumerate(parts):
+                x = (torch.zeros((1,), dtype=torch.int32, device=dev) if i == 0
+                     else torch.randn((cfg["d_model"],), device=dev).to(p.tdtype))
+                y = torch.empty((cfg["d_model"],), dtype=p.tdtype, device=dev)
+                tok = torch.empty((1,), dtype=torch.int32, device=dev)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                with torch.cuda.stream(p.stream):
+                    for rep in range(2):
+                        e0.record()
+                        for _ in range(100):
+                            p.decode_step(0, x, y)
+                            if i == 0:
+                                p.sample_greedy(0, y, tok)
+                        e1.record()
+                        p.sync()
+                stage_ms.append(e0.elapsed_time(e1) / 100)
+            slowest = max(stage_ms)
+            rec["stage_ms_per_message"] = stage_ms
+            rec["stage_busy_fraction_on_its_own_gpu"] = [t / slowest for t in stage_ms]
+            rec["tokens_per_s_bound_with_a_gpu_per_stage"] = 1000.0 / slowest * min(1.0, n_seqs / len(cut))
+            out["runs"].append(rec)
+            print(f"bench.py: {sname}, {cname} done", file=sys.stderr, flush=True)
+            del pipe, parts
+        del w
+    best = max(r[m]["tokens_per_s"] for r in out["runs"] for m in r if isinstance(r[m], dict) and "tokens_per_s" in r[m])
+    out["value"] = best
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -159,6 +242,9 @@ def main():
     import torch
     from paper_2505_18164_amd import mdi, synth as S
 
+    if args.paper_run:
+        print(json.dumps(paper_run(args, torch, mdi, S)))
+        return
     wl = S.WORKLOADS[args.workload]
     cfg, seed = wl["cfg"](), S.workload_seed(args.workload)
     n_seqs, prompt = wl["n_seqs"], wl["prompt"]

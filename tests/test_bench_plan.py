@@ -38,3 +38,9 @@ def test_the_drivers_command_line_parses():
 def test_round_robin_calls_continue_where_the_warm_up_stopped():
     assert bench.calls_of(5, 20, 8, 8) == [[5, 6, 7, 0, 1, 2, 3, 4], [5, 6, 7, 0, 1, 2, 3, 4], [5, 6, 7, 0]]
     assert bench.calls_of(0, 3, 1, 2) == [[0], [1], [0]]
+
+
+def test_paper_run_flag_parses():
+    a = bench.parse(["--paper-run", "tinyllama", "--paper-tokens", "50"])
+    assert a.paper_run == "tinyllama" and a.paper_tokens == 50 and a.gpus == 1
+    assert bench.parse([]).paper_run is None

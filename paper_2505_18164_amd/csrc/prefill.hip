@@ -389,7 +389,11 @@ void launch_gemm(hipStream_t s, int dtype, int epi, const GemmArgs& a) {
     // workgroup each (a third less operand traffic than two 128 x 64 tiles), or narrower tiles when even that
     // leaves compute units idle
     const long tiles = (long)((a.N + 127) / 128) * ((a.T + 127) / 128);
+    // (few rows and a narrow product: even 128 x 64 tiles leave compute units without a workgroup; 64 x 64 tiles give
+    // twice as many)
+    const long narrow = (long)((a.N + 63) / 64) * ((a.T + 127) / 128);
     if (tiles <= n_cu && 2 * tiles > n_cu) launch_gemm_bf16<128, 128, 8, 2>(s, epi, a);
+    else if (2 * tiles <= n_cu && narrow < n_cu) launch_gemm_bf16<64, 64, 4, 2>(s, epi, a);
     else if (2 * tiles <= n_cu) launch_gemm_bf16<128, 64, 4, 2>(s, epi, a);
     else launch_gemm_bf16<128, 128, 4, 2>(s, epi, a);
     return;

@@ -95,6 +95,7 @@ struct mdi_partition {
   tagged_t *b_xn = nullptr, *b_ob = nullptr, *b_ub = nullptr;   // [pair of columns][kMaxBatch messages]
   size_t b_vec_words = 0;
   tagged_t* b_ssq = nullptr;
+  tagged_t* b_ppart = nullptr; int b_S = 0, b_oct = 0;   // streamed products split among workgroups (plan_batch)
   unsigned* b_flags = nullptr;
   unsigned b_epoch = 0;
   int b_R[4] = {16, 16, 16, 16};
@@ -221,6 +222,7 @@ size_t carve(mdi_partition* p, void* arena) {
       p->b_ob = p->b_xn ? p->b_xn + d / 2 * kMaxBatch : nullptr;
       p->b_ub = p->b_xn ? p->b_ob + H * h / 2 * kMaxBatch : nullptr;
       p->b_ssq = (tagged_t*)cv.take((size_t)kMaxBatch * 1024 * 8);
+      p->b_ppart = (tagged_t*)cv.take((size_t)((d + 15) / 16) * 16 * 256 * 8);   // [block][up to 16 slices][256]
       p->b_flags = (unsigned*)cv.take(1024 * 4);
     }
     const size_t T = p->Tm;
@@ -307,13 +309,26 @@ void plan_batch(mdi_partition* p) {
     nb_max = std::max(nb_max, nb);
     if (j == 1) nb_d = nb;
   }
-  p->b_R[3] = p->b_R[1];                                        // the two residual products own the same rows
+  // The two residual products (output projection, MLP down) split their inner dimension among workgroups: groups
+  // of S workgroups share eight 16-row blocks, one block per wavefront, one column slice per workgroup; the owner
+  // of a block (workgroup = block index) adds the S partial results.
+  int ks_floats = 0;
+  {
+    const int nblk = (d + 15) / 16, octets = (nblk + kStepWavesMax - 1) / kStepWavesMax;
+    if (nblk > nwg) return;
+    const int S = std::min(16, nwg / octets);
+    const int c_max = (std::max(H * h, F) / 32 + S - 1) / S;     // column steps of the longest slice: 1 KiB of LDS each
+    p->b_S = S; p->b_oct = octets;
+    p->b_R[1] = p->b_R[3] = 16;
+    nb_d = 1;
+    ks_floats = S * 256 + c_max * 256;
+  }
   p->b_lds_xres = 128;
   p->b_lds_sq = p->b_lds_xres + nb_d * 256;
   p->b_lds_part = p->b_lds_sq + std::max(nb_d * 128, 128);
   const int Gmax = (H / K) % 4 == 0 ? 4 : p->G;
   const int attn_floats = std::max(Gmax * h, kStepWavesMax * Gmax * (h + 2)) + 64;
-  const int part_floats = std::max(nb_max * 2048, attn_floats);
+  const int part_floats = std::max(std::max(nb_max * 2048, attn_floats), ks_floats);
   p->b_lds = (size_t)(p->b_lds_part + part_floats) * sizeof(float);
   if (p->b_lds > 160 * 1024) return;
   if (p->b_lds > 64 * 1024 && !step_batch_allow_lds(p->b_lds)) return;
@@ -497,6 +512,7 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
       launch_fill_u32(p->stream, (uint32_t*)p->b_slot0, (long)(p->b_stride * kMaxBatch / 4), 0u);
       launch_fill_u32(p->stream, (uint32_t*)p->b_xn, (long)p->b_vec_words * 2, 0u);
       launch_fill_u32(p->stream, (uint32_t*)p->b_ssq, (long)kMaxBatch * 1024 * 2, 0u);
+      launch_fill_u32(p->stream, (uint32_t*)p->b_ppart, (long)((d + 15) / 16) * 16 * 256 * 2, 0u);
       launch_fill_u32(p->stream, p->b_flags, 1024, 1u);
       p->b_epoch = 1;
     }
@@ -906,6 +922,7 @@ mdi_status launch_batch(mdi_partition* p, int n, const uint32_t* seqs, const Mes
   a.slot0 = p->b_slot0; a.slot_stride = (long)p->b_stride;
   a.off_q = (long)p->b_off_q; a.off_part = (long)p->b_off_part; a.off_knew = (long)p->b_off_knew; a.off_tickets = (long)p->b_off_tickets;
   a.ssq = p->b_ssq; a.flags = p->b_flags;
+  a.ppart = p->b_ppart; a.str_S = p->b_S; a.str_oct = p->b_oct;
   for (int j = 0; j < 4; ++j) a.R[j] = p->b_R[j];
   a.lds_xres = p->b_lds_xres; a.lds_sq = p->b_lds_sq; a.lds_part = p->b_lds_part;
   a.trace = p->trace;

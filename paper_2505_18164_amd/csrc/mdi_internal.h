@@ -261,6 +261,7 @@ struct BatchArgs {
   char* slot0; long slot_stride;
   long off_q, off_part, off_knew, off_tickets;
   tagged_t* ssq;                     // [kMaxBatch][nwg] per-workgroup sums of squares of the residual rows they own
+  tagged_t* ppart; int str_S, str_oct; // products split among workgroups along the inner dimension: partials [block][S][256], slices per block, block octets
   unsigned* flags;                   // [nwg] phase counters of the workgroups
   int R[4];                          // rows per matrix-instruction block in the QKV / output / up / down products (8 or 16)
   int lds_xres, lds_sq, lds_part;    // LDS layout in floats

@@ -24,7 +24,8 @@
 //   * The residual stream never leaves the workgroup that owns its rows: it stays in LDS for the whole launch.
 //   * Products whose input is the d-sized normalised vector (QKV, MLP up) keep each wavefront's column slice of all
 //     messages in registers for all the blocks of the phase; the others (output projection, MLP down: one block per
-//     workgroup at the benchmark shapes) stream the vectors beside the weights.
+//     workgroup at the benchmark shapes, a long inner dimension) split the inner dimension among workgroups, so
+//     that a workgroup reads a fraction of the vectors, and exchange 16 x 16 partial results (see KsGeo).
 // Needs bf16 storage, RMSNorm, and widths that are multiples of 32; other shapes keep one pass per message.
 //
 // Included by step_w8.hip after step_impl.h (shares its exchange, attention and barrier helpers).
@@ -76,7 +77,6 @@ __device__ __forceinline__ BatchView view_of(const BatchArgs& a, int j, tagged_t
   return v;
 }
 
-constexpr int kStrSteps = 4;            // column steps per tile of a streamed product
 
 // ---------------------------------------------------------------------------
 // geometry of a product (all values uniform across the wavefront)
@@ -87,7 +87,6 @@ struct BGeo {
   int rope_sh;          // >= 0: rows pair as RoPE partners (i, i + h/2), h = 2 << rope_sh; -1: rows (2p, 2p + 1)
   int nb_local;         // this workgroup's blocks: its block lb is block lb * nwg + wg of the matrix
   int ks0, nks;         // this wavefront's column steps [ks0, ks0 + nks), 32 columns each (products with a resident operand)
-  int ktot, slice, snks; // streamed products: the wavefront's i-th step is step 4 * (8 * (i / 4) + slice) + i % 4 of ktot
 };
 __device__ __forceinline__ BGeo make_bgeo(const void* W, int N, int Kd, int R, int rope_h, int wg, int nwg, int wave) {
   BGeo g;
@@ -102,13 +101,6 @@ __device__ __forceinline__ BGeo make_bgeo(const void* W, int N, int Kd, int R, i
   g.ks0 = ((wave + wg) & (kStepWaves - 1)) * c;
   g.nks = max(0, min(c, total - g.ks0));
   if (g.nks == 0) g.ks0 = 0;          // a wavefront without columns still issues its (unused) loads inside the matrix
-  // Streamed products deal tiles of 4 column steps round-robin to the wavefronts instead: at any moment the eight
-  // wavefronts then read 2 KiB that lie next to each other in every one of the block's rows (long rows cut into
-  // eight far-apart slices made every access open another DRAM page).
-  g.ktot = total;
-  g.slice = (wave + wg) & (kStepWaves - 1);
-  const int tiles = (total + kStrSteps - 1) / kStrSteps;
-  g.snks = tiles > g.slice ? ((tiles - g.slice + kStepWaves - 1) / kStepWaves) * kStrSteps : 0;
   return g;
 }
 // Row of the matrix that row i (< R) of block `block` stands for.  With RoPE pairing a block is R/2 consecutive
@@ -151,96 +143,66 @@ __device__ __forceinline__ void res_compute(const Tile& t, const BGeo& g, int lb
   }
 }
 
-// products whose second operand streams beside the weights (output projection, MLP down): tiles of 4 column steps,
-// three in flight.  A tile is issued in two parts: the weights (addresses depend on nothing another workgroup
-// writes, so the first tiles are requested before the barrier) and the vectors.  Every address is a uniform base
-// that advances with the column step plus a per-lane offset that is fixed for the block: the loop spends its
-// instructions on loads and products, not on 64-bit address arithmetic per lane.
-struct StrTile { u32x4 w[kStrSteps]; tagged_t b[kStrSteps][4]; };
-// lane offset (bytes) of this lane's row and column group inside the matrix, for block lb
-__device__ __forceinline__ uint32_t lane_w_off(const BGeo& g, int lb, int wg, int nwg, int lane) {
-  const int i = lane & (g.R - 1) & 15, kg = lane >> 4;
-  const int row = min(block_row(g, lb * nwg + wg, i), g.N - 1);
-  return (uint32_t)row * (uint32_t)g.row_bytes + (uint32_t)(kg << 4);
-}
-// The column step of the matrix that the wavefront's i-th step stands for (i is a multiple of 4 plus s < 4); steps past
-// the end repeat the last column step of the matrix (their products are skipped).
-__device__ __forceinline__ int str_k(const BGeo& g, int i, int s) {
-  return min((((i >> 2) * kStepWaves + g.slice) << 2) + s, g.ktot - 1);
-}
-// Steps i .. i + 3 (i a multiple of 4) of the block whose lane offset is woff.
-__device__ __forceinline__ void str_issue_w(StrTile& t, const BGeo& g, uint32_t woff, int i) {
-  const MDI_GLOBAL char* base = (const MDI_GLOBAL char*)g.W;
-  const int it = min(i, max(g.snks - kStrSteps, 0));
-#pragma unroll
-  for (int s = 0; s < kStrSteps; ++s)
-    t.w[s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(base + ((long)str_k(g, it, s) << 6) + woff);
-}
-// bvec: this phase's [pair of columns][16 messages] array; boff: this lane's (column group, message) offset in words.
-// A lane's eight columns of a step are four words 16 apart.
-__device__ __forceinline__ void str_issue_b(StrTile& t, const BGeo& g, const tagged_t* bvec, uint32_t boff, int i) {
-  const MDI_GLOBAL tagged_t* base = (const MDI_GLOBAL tagged_t*)bvec;
-  const int it = min(i, max(g.snks - kStrSteps, 0));
-#pragma unroll
-  for (int s = 0; s < kStrSteps; ++s) {
-    const MDI_GLOBAL tagged_t* p = base + ((long)str_k(g, it, s) << 8) + boff;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) t.b[s][e] = ld_word(p + (e << 4));
-  }
-}
 // Four tagged words -> the matrix instruction's second operand; `bad` collects whether any of them does not carry the
-// counter `tag` (a store not yet visible on this die: the rare case).  No load is retried here: a reload inside
-// the pipelined loop would cost the compiler its count of the loads in flight, and with it the overlap of the tiles;
-// the caller repeats the whole pass over the block instead.
+// counter `tag` (a store not yet visible on this die: the rare case).  No load is retried here; the caller repeats
+// its loads the slow, sure way instead.
 __device__ __forceinline__ bf16x8 take4(tagged_t r0, tagged_t r1, tagged_t r2, tagged_t r3, unsigned tag, uint32_t& bad) {
   bad |= (((uint32_t)(r0 >> 32) ^ tag) | ((uint32_t)(r1 >> 32) ^ tag)) | (((uint32_t)(r2 >> 32) ^ tag) | ((uint32_t)(r3 >> 32) ^ tag));
   return __builtin_bit_cast(bf16x8, u32x4{(uint32_t)r0, (uint32_t)r1, (uint32_t)r2, (uint32_t)r3});
 }
-__device__ __forceinline__ void str_compute(const StrTile& t, const BGeo& g, int i, unsigned tag, f32x4& acc, uint32_t& bad) {
-  if (i >= g.snks) return;                                       // uniform
+
+// ---------------------------------------------------------------------------
+// Streamed products with the inner dimension split among workgroups.  Every workgroup used to read the whole
+// vector of all messages for its one block of rows: 256 copies of it through the dies' L2s, twice the bytes of
+// the matrix itself in the MLP down projection.  Here workgroup (q, s) takes column slice s of the eight row
+// blocks 8 q .. 8 q + 7, one block per wavefront: it reads 1 / S of the vector - once, validated, into LDS, from
+// where its eight wavefronts take the matrix instruction's second operand - and hands the 16 x 16 partial result
+// of every block, as tagged words, to the workgroup that owns the block's residual rows, which adds the S partials
+// in slice order.
+struct KsGeo {
+  int S, q, s;          // slices per block; this workgroup's block octet and slice (q >= octets: no work)
+  int k0, nk;           // the slice: column steps [k0, k0 + nk)
+  int blk, nblk;        // this wavefront's block; blocks of the product
+  bool live;            // this wavefront has columns and a block
+};
+__device__ __forceinline__ KsGeo make_ksgeo(int N, int Kd, int S, int octets, int wg, int wave) {
+  KsGeo g;
+  g.S = S; g.q = wg / S; g.s = wg - g.q * S;
+  const int ktot = Kd >> 5, c = (ktot + S - 1) / S;
+  g.k0 = min(g.s * c, ktot);
+  g.nk = g.q < octets ? max(0, min(c, ktot - g.s * c)) : 0;
+  g.nblk = (N + 15) >> 4;
+  g.blk = g.q * kStepWaves + wave;
+  g.live = g.nk > 0 && g.blk < g.nblk;
+  return g;
+}
+// column steps 8 t .. 8 t + 7 of the slice (steps past its end repeat its last one)
+__device__ __forceinline__ void ks_issue(Tile& t, const KsGeo& g, const char* W, uint32_t woff, int ti) {
+  const MDI_GLOBAL char* base = (const MDI_GLOBAL char*)W + ((long)g.k0 << 6);
+  const int last = max(g.nk - 1, 0);
 #pragma unroll
-  for (int s = 0; s < kStrSteps; ++s) {
-    const int k = (((i >> 2) * kStepWaves + g.slice) << 2) + s;
-    if (k < g.ktot)                                              // uniform
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.w[s]),
-                                                   take4(t.b[s][0], t.b[s][1], t.b[s][2], t.b[s][3], tag, bad), acc, 0, 0, 0);
+  for (int s = 0; s < 8; ++s)
+    t.r[s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(base + ((long)min(ti * 8 + s, last) << 6) + woff);
+}
+__device__ __forceinline__ void ks_compute(const Tile& t, const KsGeo& g, const u32x4* Bs, int ti, int lane, f32x4& acc) {
+  const int n = lane & 15, kg = lane >> 4;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const int ks = ti * 8 + s;
+    if (ks < g.nk) {                                             // uniform
+      const int gi = ks * 4 + kg;
+      const u32x4 b = Bs[gi * 16 + (n ^ (gi & 15))];
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.r[s]), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+    }
   }
 }
-// One pass over a block's columns: three tiles in flight, each consumed while the other two's loads arrive.  The
-// first tiles are already requested when `issued` (before the barrier: weights; right after it: vectors).  Nothing in
-// here branches around a load: with a conditional load in the loop the compiler no longer knows how many loads are in
-// flight where a tile is consumed, and waits for (nearly) all of them.
-__device__ __forceinline__ void str_pass(StrTile& T0, StrTile& T1, StrTile& T2, const BGeo& g, const tagged_t* bvec, uint32_t woff, uint32_t boff,
-                                         unsigned tag, f32x4& acc, uint32_t& bad, bool issued) {
-  if (!issued) {
-    str_issue_w(T0, g, woff, 0); str_issue_w(T1, g, woff, kStrSteps); str_issue_w(T2, g, woff, 2 * kStrSteps);
-    str_issue_b(T0, g, bvec, boff, 0); str_issue_b(T1, g, bvec, boff, kStrSteps); str_issue_b(T2, g, bvec, boff, 2 * kStrSteps);
-  }
-#pragma nounroll
-  for (int ks = 0; ks < g.snks; ks += 3 * kStrSteps) {
-    str_compute(T0, g, ks, tag, acc, bad);
-    str_issue_w(T0, g, woff, ks + 3 * kStrSteps); str_issue_b(T0, g, bvec, boff, ks + 3 * kStrSteps);
-    str_compute(T1, g, ks + kStrSteps, tag, acc, bad);
-    str_issue_w(T1, g, woff, ks + 4 * kStrSteps); str_issue_b(T1, g, bvec, boff, ks + 4 * kStrSteps);
-    str_compute(T2, g, ks + 2 * kStrSteps, tag, acc, bad);
-    str_issue_w(T2, g, woff, ks + 5 * kStrSteps); str_issue_b(T2, g, bvec, boff, ks + 5 * kStrSteps);
-  }
-}
-// The same pass the slow, sure way - one column step at a time, vector words loaded at agent scope until they carry
-// the counter - for the rare block whose first look through L2 met words that were not there yet.
-__device__ __forceinline__ void str_pass_coherent(const BGeo& g, const tagged_t* bvec, uint32_t woff, uint32_t boff, unsigned tag, f32x4& acc,
-                                                  int spin_limit, int* err) {
-#pragma nounroll
-  for (int i = 0; i < g.snks; ++i) {
-    const int k = (((i >> 2) * kStepWaves + g.slice) << 2) + (i & 3);
-    if (k >= g.ktot) continue;                                   // uniform
-    const u32x4 w = *reinterpret_cast<const MDI_GLOBAL u32x4*>((const MDI_GLOBAL char*)g.W + ((long)k << 6) + woff);
-    const tagged_t* p = bvec + ((long)k << 8) + boff;
-    u32x4 bw;
-    bw.x = settle_bits(p, ld_raw(p), tag, spin_limit, err); bw.y = settle_bits(p + 16, ld_raw(p + 16), tag, spin_limit, err);
-    bw.z = settle_bits(p + 32, ld_raw(p + 32), tag, spin_limit, err); bw.w = settle_bits(p + 48, ld_raw(p + 48), tag, spin_limit, err);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, bw), acc, 0, 0, 0);
-  }
+// Sum over n partials of element (row i, message j): partial w at part + 256 w, element order as the matrix
+// instruction leaves it (lane = 16 (i / 4) + j, register i % 4).
+__device__ __forceinline__ float part_sum_n(const float* part, int i, int j, int n) {
+  const float* p = part + ((((i >> 2) << 4) + j) << 2) + (i & 3);
+  float v = 0.f;
+  for (int w = 0; w < n; ++w) v += p[w << 8];
+  return v;
 }
 
 // Sum over the wavefronts of element (row i, message j) of local block lb.
@@ -569,29 +531,76 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
             }
           }
         } else {
-          // ---- a product whose second operand streams beside the weights
-          StrTile T0, T1, T2;
-          uint32_t woff = lane_w_off(g, 0, wg, nwg, lane);
-          const uint32_t boff = (uint32_t)((kg << 6) + lane_msg);
-          str_issue_w(T0, g, woff, 0); str_issue_w(T1, g, woff, kStrSteps); str_issue_w(T2, g, woff, 2 * kStrSteps);
-          if (!barrier(epoch)) return;
-          bstamp(a, layer, ph, 1);
-          const tagged_t* bvec = ph == PH_OPROJ ? ob_l : ub_l;
-          str_issue_b(T0, g, bvec, boff, 0); str_issue_b(T1, g, bvec, boff, kStrSteps); str_issue_b(T2, g, bvec, boff, 2 * kStrSteps);
-          bstamp(a, layer, ph, 2);
-#pragma nounroll
-          for (int lb = 0; lb < g.nb_local; ++lb) {
-            if (lb) woff = lane_w_off(g, lb, wg, nwg, lane);
-            uint32_t bad = 0u;
-            acc = f32x4{0.f, 0.f, 0.f, 0.f};
-            str_pass(T0, T1, T2, g, bvec, woff, boff, epoch, acc, bad, lb == 0);
-            if (__any(bad != 0u)) {                                // rare: the block once more, the slow and sure way
-              acc = f32x4{0.f, 0.f, 0.f, 0.f};
-              str_pass_coherent(g, bvec, woff, boff, epoch, acc, a.spin_limit, a.err);
+          {
+            // ---- a product whose inner dimension is split among workgroups (see KsGeo)
+            const KsGeo kq = make_ksgeo(N, Kd, a.str_S, a.str_oct, wg, wave);
+            Tile A, B;
+            const uint32_t woff = (uint32_t)min(kq.blk * 16 + (lane & 15), N - 1) * (uint32_t)g.row_bytes + (uint32_t)(kg << 4);
+            ks_issue(A, kq, g.W, woff, 0);
+            ks_issue(B, kq, g.W, woff, 1);
+            if (!barrier(epoch)) return;
+            bstamp(a, layer, ph, 1);
+            // the slice of every message's vector, validated word by word, to LDS as [group of 8 columns][message]
+            u32x4* Bs = reinterpret_cast<u32x4*>(part + (a.str_S << 8));
+            {
+              const tagged_t* bvec = ph == PH_OPROJ ? ob_l : ub_l;
+              for (int u0 = threadIdx.x; u0 < kq.nk * 64; u0 += 2 * kStepThreads) {
+                tagged_t raw[2][4];
+                const tagged_t* src[2];
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                  const int u = min(u0 + r * kStepThreads, kq.nk * 64 - 1);
+                  const int gi = u >> 4, n = min(u & 15, m - 1);
+                  src[r] = bvec + ((long)(kq.k0 * 4 + gi) << 6) + n;       // pairs 4 (4 k0 + gi) .. + 3, 16 words apart
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) raw[r][e] = ld_raw(src[r] + (e << 4));
+                }
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                  const int u = u0 + r * kStepThreads;
+                  u32x4 v;
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) v[e] = settle_bits(src[r] + (e << 4), raw[r][e], epoch, a.spin_limit, a.err);
+                  if (u < kq.nk * 64) { const int gi = u >> 4; Bs[gi * 16 + ((u & 15) ^ (gi & 15))] = v; }
+                }
+              }
             }
-            // the wavefront's share of the block (zeros when it has no columns)
-            *reinterpret_cast<f32x4*>(part + (((lb * kStepWaves + wave) << 6) + lane) * 4) = acc;
+            __syncthreads();
+            bstamp(a, layer, ph, 2);
             acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (kq.live) {                                             // uniform per wavefront
+              const int nt = ((kq.nk + 7) >> 3) + 1 & ~1;
+#pragma nounroll
+              for (int t = 0; t < nt; t += 2) {
+                ks_compute(A, kq, Bs, t, lane, acc);
+                ks_issue(A, kq, g.W, woff, t + 2);
+                ks_compute(B, kq, Bs, t + 1, lane, acc);
+                ks_issue(B, kq, g.W, woff, t + 3);
+              }
+            }
+            // the partial of (block, slice), zeros from a slice without columns, to the block's owner
+            if (kq.q < a.str_oct && kq.blk < kq.nblk) {
+              tagged_t* dst = a.ppart + (((long)kq.blk * kq.S + kq.s) << 8) + (lane << 2);
+#pragma unroll
+              for (int r = 0; r < 4; ++r) st_tag(dst + r, acc[r], wtag);
+            }
+            acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            bstamp(a, layer, ph, 7);
+            // the owner of block wg collects its S partials into the slots the epilogue adds up
+            if (wg < kq.nblk) {
+              const tagged_t* srcp = a.ppart + ((long)wg * kq.S << 8);
+              for (int u0 = threadIdx.x; u0 < (kq.S << 8); u0 += 4 * kStepThreads) {
+                tagged_t raw[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) raw[r] = ld_raw(srcp + min(u0 + r * kStepThreads, (kq.S << 8) - 1));
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                  const int u = u0 + r * kStepThreads;
+                  const float v = settle(srcp + min(u, (kq.S << 8) - 1), raw[r], wtag, a.spin_limit, a.err);
+                  if (u < (kq.S << 8)) part[u] = v;
+                }
+              }
+            }
           }
         }
         bstamp(a, layer, ph, 3);
@@ -670,8 +679,9 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
             float s2 = 0.f;
             if (r0 < g.N) {
               float* xr = xres + ((lb << 4) + 2 * p) * 16 + j;
-              const float x0 = xr[0] + part_sum(part, lb, 2 * p, j) + (bias ? bias[r0] : 0.f);
-              const float x1 = xr[16] + part_sum(part, lb, 2 * p + 1, j) + (bias ? bias[r0 + 1] : 0.f);
+              const float d0 = part_sum_n(part, 2 * p, j, a.str_S), d1 = part_sum_n(part, 2 * p + 1, j, a.str_S);
+              const float x0 = xr[0] + d0 + (bias ? bias[r0] : 0.f);
+              const float x1 = xr[16] + d1 + (bias ? bias[r0 + 1] : 0.f);
               xr[0] = x0; xr[16] = x1;
               if (last) {
                 store_kind(sl.out[j], a.act_kind, r0, x0); store_kind(sl.out[j], a.act_kind, r0 + 1, x1);

@@ -24,9 +24,10 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as
 
 constexpr int kHbGroups = 9;          // 16-byte groups of an activation per lane: widths up to 64 * 9 * 8 = 4608
 // Where a wavefront is in its stream: block, how many of the block's column tiles are done, and the tile it started
-// the block with.  Rows are a power of two apart in memory: if every wavefront walked its rows from column 0, all of
-// them would ask the same few memory channels at the same time (measured: 70 us for 33 MB); block b starts at tile
-// b mod (tiles per row) and wraps, so at any moment the grid's reads are spread over a whole row's width.
+// the block with.  Rows are a power of two apart in memory; block b starts at tile b mod (tiles per row) and wraps,
+// so that at any moment the grid's reads are spread over a whole row's width instead of all wavefronts asking for
+// the same columns (a precaution against crowding a few memory channels; on this chip it measured neither faster
+// nor slower than starting every block at column 0).
 struct HbCursor { int blk, tin, rot; };
 __device__ __forceinline__ int hb_tile(const HbCursor& c, int nt) { const int t = c.tin + c.rot; return t >= nt ? t - nt : t; }
 __device__ __forceinline__ void hb_next(HbCursor& c, int nt, int stride_blk) {
@@ -34,9 +35,10 @@ __device__ __forceinline__ void hb_next(HbCursor& c, int nt, int stride_blk) {
 }
 
 __device__ __forceinline__ void hb_issue(Tile& t, const LogitsBatchArgs& a, HbCursor& c, int nt, int nsteps, int stride_blk, int lane) {
-  // Loaded with four neighbouring lanes on one row (64 contiguous bytes): a load instruction then touches 16 cache
-  // lines, one per row, instead of 64 quarter-used ones (in the matrix instruction's own operand order the 16 lanes
-  // of a quarter wavefront sit on 16 different rows); hb_operand moves the data to the operand order afterwards.
+  // Loaded in the matrix instruction's own operand order: lane (i = lane mod 16, kg = lane div 16) takes 16 bytes of
+  // row i at column group kg.  (Loading with four neighbouring lanes per row - 16 instead of 64 cache lines touched
+  // per instruction - and permuting to operand order with ds_bpermute measured -2.5 % on the largest head and +5 %
+  // on a narrow one: not kept.)
   const int i = lane & 15, kg = lane >> 4;
   const int row = min(c.blk * 16 + i, a.N - 1);
   const uint32_t off = (uint32_t)row * (uint32_t)(2 * a.Kd) + (uint32_t)(kg << 4);
@@ -47,16 +49,6 @@ __device__ __forceinline__ void hb_issue(Tile& t, const LogitsBatchArgs& a, HbCu
   for (int s = 0; s < 8; ++s)
     t.r[s] = *reinterpret_cast<const MDI_GLOBAL u32x4*>(base + ((long)min(s, last) << 6) + off);
   hb_next(c, nt, stride_blk);
-}
-
-// Lane (row i = lane & 15, column group kg = lane >> 4) of the matrix instruction's first operand takes what lane
-// 4 i + kg loaded.
-__device__ __forceinline__ bf16x8 hb_operand(const u32x4& v, int lane) {
-  const int src = ((lane & 15) * 4 + (lane >> 4)) << 2;
-  u32x4 o;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) o[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)v[e]);
-  return __builtin_bit_cast(bf16x8, o);
 }
 
 __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_logits_batch(LogitsBatchArgs a) {

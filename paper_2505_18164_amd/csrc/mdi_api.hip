@@ -928,8 +928,6 @@ mdi_status launch_batch(mdi_partition* p, int n, const uint32_t* seqs, const Mes
   a.trace = p->trace;
   // Attention work items: (message, head group, context split).  Splits of about equal length over all messages,
   // as many items as there are workgroups when the contexts allow it, no split shorter than 128 positions.
-  const long h = c.head_dim;
-  (void)h;
   int chunk = (int)std::max<long>(128, (ctx_sum * a.n_hg + a.nwg - 1) / a.nwg);
   chunk = (chunk + 15) / 16 * 16;
   auto items_at = [&](int ch) { long t = 0; for (int j = 0; j < n; ++j) t += (long)a.n_hg * std::min(kMaxSplits, (mp[j].ctx + ch - 1) / ch); return t; };

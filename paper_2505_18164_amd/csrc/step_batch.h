@@ -490,15 +490,20 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
             uint32_t bad = 0u;
 #pragma unroll
             for (int h0 = 0; h0 < kResSteps; h0 += 4) {
-              tagged_t raw[4][4];
+              if (h0 == 0 || h0 < g.nks) {           // uniform: a batch of steps that lies past the slice costs no round trip
+                tagged_t raw[4][4];
 #pragma unroll
-              for (int s = 0; s < 4; ++s) {          // steps past the slice repeat its last one: every register gets a value
-                const MDI_GLOBAL tagged_t* p = bbase + ((long)min(h0 + s, last) << 8) + boff;
+                for (int s = 0; s < 4; ++s) {        // steps past the slice repeat its last one: every register gets a value
+                  const MDI_GLOBAL tagged_t* p = bbase + ((long)min(h0 + s, last) << 8) + boff;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) raw[s][e] = ld_word(p + (e << 4));
+                  for (int e = 0; e < 4; ++e) raw[s][e] = ld_word(p + (e << 4));
+                }
+#pragma unroll
+                for (int s = 0; s < 4; ++s) Bv[h0 + s] = take4(raw[s][0], raw[s][1], raw[s][2], raw[s][3], epoch, bad);
+              } else {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) Bv[h0 + s] = Bv[0];
               }
-#pragma unroll
-              for (int s = 0; s < 4; ++s) Bv[h0 + s] = take4(raw[s][0], raw[s][1], raw[s][2], raw[s][3], epoch, bad);
             }
             if (__any(bad != 0u)) {                  // rare: every step again at agent scope, until its words carry the counter
 #pragma unroll

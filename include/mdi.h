@@ -245,9 +245,11 @@ MDI_API mdi_status mdi_decode_steps(mdi_partition *part, uint32_t n, const uint3
  * paper's one-message-at-a-time rule: the traffic of a pass is the weights
  * once plus every sample's cache, instead of the weights once per message.
  * More than 16 messages take several passes; a lone message is forwarded as
- * by mdi_decode_step.  Needs bf16 storage, RMSNorm, the persistent decode
- * path and d_model, n_head * head_dim, d_ff multiples of 32 (d_model at most
- * 4096); other partitions forward the messages as mdi_decode_steps does
+ * by mdi_decode_step.  Needs bf16 storage, the persistent decode path,
+ * d_model, n_head * head_dim, d_ff multiples of 32 (d_model at most 4096) and
+ * either RMSNorm or LayerNorm with a GELU MLP (the GPT-2 and the Llama
+ * families; LayerNorm with SwiGLU is not covered); other partitions forward
+ * the messages as mdi_decode_steps does
  * (mdi_partition_info(4) tells).  Vectors between the matrix products are
  * rounded to bf16 here (as in a first visit), so a sample's result agrees with
  * mdi_decode_step's within the bf16 parity bar, not to the last bits; for a
@@ -316,7 +318,7 @@ MDI_API mdi_status mdi_sample_topk_static(mdi_partition *part, uint32_t seq_id, 
  * of mdi_sample_topk per sample with counter (seq_ids[i], steps[i]).
  * seq_ids, acts_in, steps: HOST arrays of n; acts_in[i]: device, [d] in
  * cfg.dtype.  tokens_out: device int32[n].  logits_out: device float[n][V]
- * (row i = sample i) or NULL.  Needs bf16 storage, RMSNorm, d_model a
+ * (row i = sample i) or NULL.  Needs bf16 storage, d_model a
  * multiple of 32 (at most 4608), activations aligned to 16 bytes and the
  * persistent decode path; otherwise, and for n = 1, the samples are served
  * one by one exactly as mdi_sample_greedy / mdi_sample_topk would

@@ -292,6 +292,25 @@ __global__ __launch_bounds__(1024) void k_sample_topk_batch(SampleBatchArgs b) {
 void launch_sample_topk(hipStream_t s, const SampleArgs& a) { hipLaunchKernelGGL(k_sample_topk, dim3(1), dim3(1024), 0, s, a); }
 void launch_sample_topk_batch(hipStream_t s, int m, const SampleBatchArgs& a) { hipLaunchKernelGGL(k_sample_topk_batch, dim3(m), dim3(1024), 0, s, a); }
 
+// c1[r] = sum_k W[r][k] g[k], c2[r] = sum_k W[r][k] b[k] for a bf16 matrix W [N, Kd]: what LayerNorm's mean and bias
+// contribute to a product whose input travels as x * gain (the batched decode pass).  One wavefront per row.
+__global__ __launch_bounds__(256) void k_row_dots(const bf16_t* W, int N, int Kd, const float* g, const float* b, float* c1, float* c2) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= N) return;
+  float s1 = 0.f, s2 = 0.f;
+  for (int k = lane; k < Kd; k += 64) {
+    const float w = load_kind(W, IN_BF16, (long)row * Kd + k);
+    s1 += w * g[k];
+    s2 += w * (b ? b[k] : 0.f);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) { s1 += __shfl_xor(s1, off, 64); s2 += __shfl_xor(s2, off, 64); }
+  if (lane == 0) { c1[row] = s1; c2[row] = s2; }
+}
+void launch_row_dots(hipStream_t s, const void* W, int N, int Kd, const float* g, const float* b, float* c1, float* c2) {
+  hipLaunchKernelGGL(k_row_dots, dim3((N + 3) / 4), dim3(256), 0, s, (const bf16_t*)W, N, Kd, g, b, c1, c2);
+}
+
 int gemv_grid(int N) {
   const int n_groups = (N + 3) / 4;
   const int blocks = (n_groups + 3) / 4;

@@ -1,4 +1,4 @@
-// Output layers for several samples with ONE pass over the vocabulary matrix (bf16 storage, RMSNorm).
+// Output layers for several samples with ONE pass over the vocabulary matrix (bf16 storage).
 //
 // Alg. 1 runs the output layers once per returning sample ("process output layers ... get token").  When several
 // samples' last hidden states wait at the starter together (Sec. III-C: several samples are in flight), their
@@ -6,7 +6,7 @@
 // normalised activations on the matrix cores (v_mfma_f32_16x16x32_bf16: first operand = 16 rows x 32 columns of
 // the matrix straight from row-major memory, second = 32 columns x 16 samples, read from LDS).
 //
-//   * Every workgroup normalises all activations itself (final RMSNorm, gain folded in, rounded to bf16 once) and
+//   * Every workgroup normalises all activations itself (final RMSNorm or LayerNorm, rounded to bf16 once) and
 //     keeps them in LDS as [group of 8 columns][sample] 16-byte units (the sample index xor-ed with the group's, so
 //     that the staging's writes of one sample's groups spread over the banks): a wavefront's read of one column
 //     step is one contiguous KiB.
@@ -82,34 +82,47 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
       xa[j] = x0[gi]; xb[j] = x1[gi];
       glo[j] = gp[2 * gi]; ghi[j] = gp[2 * gi + 1];
     }
-    float sa = 0.f, sb = 0.f;
+    const f32x4* bp = reinterpret_cast<const f32x4*>(a.b);   // LayerNorm's bias, or nullptr
+    float sa = 0.f, sb = 0.f, ma = 0.f, mb = 0.f;
 #pragma unroll
     for (int j = 0; j < kHbGroups; ++j) {
       const float live = lane + 64 * j < ngroups ? 1.f : 0.f;
-      float ta = 0.f, tb = 0.f;
+      float ta = 0.f, tb = 0.f, ua = 0.f, ub = 0.f;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float al = bf16_bits_to_f32(xa[j][e] & 0xFFFFu), ah = bf16_bits_to_f32(xa[j][e] >> 16);
         const float bl = bf16_bits_to_f32(xb[j][e] & 0xFFFFu), bh = bf16_bits_to_f32(xb[j][e] >> 16);
         ta += al * al + ah * ah; tb += bl * bl + bh * bh;
+        ua += al + ah; ub += bl + bh;
       }
-      sa += live * ta; sb += live * tb;
+      sa += live * ta; sb += live * tb; ma += live * ua; mb += live * ub;
     }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) { sa += __shfl_xor(sa, off, 64); sb += __shfl_xor(sb, off, 64); }
-    // samples beyond the call's count are zero columns
-    const float ra = n0 < a.m ? 1.0f / sqrtf(sa / (float)a.Kd + a.eps) : 0.f;
-    const float rb = n0 + 1 < a.m ? 1.0f / sqrtf(sb / (float)a.Kd + a.eps) : 0.f;
+    for (int off = 32; off >= 1; off >>= 1) {
+      sa += __shfl_xor(sa, off, 64); sb += __shfl_xor(sb, off, 64);
+      ma += __shfl_xor(ma, off, 64); mb += __shfl_xor(mb, off, 64);
+    }
+    // RMSNorm: x / rms * g.  LayerNorm: (x - mean) / std * g + b (biased variance).  Samples beyond the call's count
+    // are zero columns.
+    const bool ln = a.norm_kind == MDI_NORM_LAYERNORM;
+    const float inv_n = 1.0f / (float)a.Kd;
+    const float mua = ln ? ma * inv_n : 0.f, mub = ln ? mb * inv_n : 0.f;
+    const float ra = n0 < a.m ? 1.0f / sqrtf(fmaxf(sa * inv_n - mua * mua, 0.f) + a.eps) : 0.f;
+    const float rb = n0 + 1 < a.m ? 1.0f / sqrtf(fmaxf(sb * inv_n - mub * mub, 0.f) + a.eps) : 0.f;
+    const float ka = n0 < a.m ? 1.f : 0.f, kb = n0 + 1 < a.m ? 1.f : 0.f;     // bias only into live columns
 #pragma unroll
     for (int j = 0; j < kHbGroups; ++j) {
       const int gi = lane + 64 * j;
       if (gi < ngroups) {
+        f32x4 blo = {0.f, 0.f, 0.f, 0.f}, bhi = {0.f, 0.f, 0.f, 0.f};
+        if (bp) { blo = bp[2 * gi]; bhi = bp[2 * gi + 1]; }
         u32x4 oa, ob;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float g0 = e < 2 ? glo[j][2 * e] : ghi[j][2 * e - 4], g1 = e < 2 ? glo[j][2 * e + 1] : ghi[j][2 * e - 3];
-          oa[e] = pack_bf16x2(bf16_bits_to_f32(xa[j][e] & 0xFFFFu) * ra * g0, bf16_bits_to_f32(xa[j][e] >> 16) * ra * g1);
-          ob[e] = pack_bf16x2(bf16_bits_to_f32(xb[j][e] & 0xFFFFu) * rb * g0, bf16_bits_to_f32(xb[j][e] >> 16) * rb * g1);
+          const float b0 = e < 2 ? blo[2 * e] : bhi[2 * e - 4], b1 = e < 2 ? blo[2 * e + 1] : bhi[2 * e - 3];
+          oa[e] = pack_bf16x2((bf16_bits_to_f32(xa[j][e] & 0xFFFFu) - mua) * ra * g0 + ka * b0, (bf16_bits_to_f32(xa[j][e] >> 16) - mua) * ra * g1 + ka * b1);
+          ob[e] = pack_bf16x2((bf16_bits_to_f32(xb[j][e] & 0xFFFFu) - mub) * rb * g0 + kb * b0, (bf16_bits_to_f32(xb[j][e] >> 16) - mub) * rb * g1 + kb * b1);
         }
         Bs[gi * 16 + (n0 ^ (gi & 15))] = oa; Bs[gi * 16 + ((n0 + 1) ^ (gi & 15))] = ob;
       }

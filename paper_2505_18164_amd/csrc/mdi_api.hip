@@ -95,6 +95,7 @@ struct mdi_partition {
   tagged_t *b_xn = nullptr, *b_ob = nullptr, *b_ub = nullptr;   // [pair of columns][kMaxBatch messages]
   size_t b_vec_words = 0;
   tagged_t* b_ssq = nullptr;
+  tagged_t* b_ssum = nullptr; float* b_nc = nullptr; size_t b_nc_stride = 0;   // LayerNorm in the batched pass (BatchArgs)
   tagged_t* b_ppart = nullptr; int b_S = 0, b_oct = 0;   // streamed products split among workgroups (plan_batch)
   unsigned* b_flags = nullptr;
   unsigned b_epoch = 0;
@@ -166,7 +167,7 @@ size_t carve(mdi_partition* p, void* arena) {
     p->logits = (float*)cv.take(V * 4);
     p->cand = (tagged_t*)cv.take(1024 * 2 * sizeof(tagged_t));
     p->herr = (int*)cv.take(256);
-    if (c.dtype == MDI_BF16 && !ln) {
+    if (c.dtype == MDI_BF16) {
       p->hb_cand = (tagged_t*)cv.take((size_t)kMaxBatch * 1024 * 2 * sizeof(tagged_t));
       p->hb_logits = (float*)cv.take((size_t)kMaxBatch * V * 4);
     }
@@ -205,7 +206,7 @@ size_t carve(mdi_partition* p, void* arena) {
       sc.part = (tagged_t*)cv.take(H * kMaxSplits * (h + 2) * 8);
       sc.knew = (tagged_t*)cv.take(2 * K * h * 8);
     }
-    p->batch_region = c.dtype == MDI_BF16 && c.norm_kind == MDI_NORM_RMSNORM;
+    p->batch_region = c.dtype == MDI_BF16 && (c.norm_kind == MDI_NORM_RMSNORM || !swiglu);
     if (p->batch_region) {
       // one block per message of a batched launch, all laid out alike, so that message j's vectors are message
       // 0's advanced by j strides
@@ -222,6 +223,11 @@ size_t carve(mdi_partition* p, void* arena) {
       p->b_ob = p->b_xn ? p->b_xn + d / 2 * kMaxBatch : nullptr;
       p->b_ub = p->b_xn ? p->b_ob + H * h / 2 * kMaxBatch : nullptr;
       p->b_ssq = (tagged_t*)cv.take((size_t)kMaxBatch * 1024 * 8);
+      if (ln) {
+        p->b_ssum = (tagged_t*)cv.take((size_t)kMaxBatch * 1024 * 8);
+        p->b_nc_stride = 2 * (nqkv + nup);
+        p->b_nc = (float*)cv.take(p->n_local * p->b_nc_stride * 4);
+      }
       p->b_ppart = (tagged_t*)cv.take((size_t)((d + 15) / 16) * 16 * 256 * 8);   // [block][up to 16 slices][256]
       p->b_flags = (unsigned*)cv.take(1024 * 4);
     }
@@ -512,6 +518,16 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
       launch_fill_u32(p->stream, (uint32_t*)p->b_slot0, (long)(p->b_stride * kMaxBatch / 4), 0u);
       launch_fill_u32(p->stream, (uint32_t*)p->b_xn, (long)p->b_vec_words * 2, 0u);
       launch_fill_u32(p->stream, (uint32_t*)p->b_ssq, (long)kMaxBatch * 1024 * 2, 0u);
+      if (p->b_ssum) {
+        launch_fill_u32(p->stream, (uint32_t*)p->b_ssum, (long)kMaxBatch * 1024 * 2, 0u);
+        const int nq = (int)((H + 2 * K) * h), nu = (int)(c.mlp_kind == MDI_MLP_SWIGLU ? 2 * F : F);
+        for (int i = 0; i < p->n_local; ++i) {       // what the mean and the norm's bias add to the two normed products
+          const LayerPacked& L = p->layers[i];
+          float* nc = p->b_nc + (size_t)i * p->b_nc_stride;
+          launch_row_dots(p->stream, L.wqkv, nq, (int)d, L.ln1_g, L.ln1_b, nc, nc + nq);
+          launch_row_dots(p->stream, L.wup, nu, (int)d, L.ln2_g, L.ln2_b, nc + 2 * nq, nc + 2 * nq + nu);
+        }
+      }
       launch_fill_u32(p->stream, (uint32_t*)p->b_ppart, (long)((d + 15) / 16) * 16 * 256 * 2, 0u);
       launch_fill_u32(p->stream, p->b_flags, 1024, 1u);
       p->b_epoch = 1;
@@ -922,6 +938,7 @@ mdi_status launch_batch(mdi_partition* p, int n, const uint32_t* seqs, const Mes
   a.slot0 = p->b_slot0; a.slot_stride = (long)p->b_stride;
   a.off_q = (long)p->b_off_q; a.off_part = (long)p->b_off_part; a.off_knew = (long)p->b_off_knew; a.off_tickets = (long)p->b_off_tickets;
   a.ssq = p->b_ssq; a.flags = p->b_flags;
+  a.norm_kind = (int)c.norm_kind; a.ssum = p->b_ssum; a.nc0 = p->b_nc; a.nc_stride = (long)p->b_nc_stride;
   a.ppart = p->b_ppart; a.str_S = p->b_S; a.str_oct = p->b_oct;
   for (int j = 0; j < 4; ++j) a.R[j] = p->b_R[j];
   a.lds_xres = p->b_lds_xres; a.lds_sq = p->b_lds_sq; a.lds_part = p->b_lds_part;
@@ -1105,7 +1122,7 @@ mdi_status mdi_sample_batch(mdi_partition* p, uint32_t n, const uint32_t* seqs, 
     LogitsBatchArgs a{};
     a.W = p->lm_head; a.N = (int)V; a.Kd = (int)c.d_model;
     for (int j = 0; j < m; ++j) a.x[j] = acts_in[i + j];
-    a.m = m; a.g = p->lnf_g; a.eps = c.norm_eps;
+    a.m = m; a.g = p->lnf_g; a.b = p->lnf_b; a.norm_kind = (int)c.norm_kind; a.eps = c.norm_eps;
     a.out = rows; a.out_stride = (long)V;
     a.cand = p->hb_cand; a.tag = next_head_tag(); a.counter = p->counters + c.n_head + 1;
     a.err = p->herr; a.spin_limit = 1 << 21;

@@ -92,6 +92,7 @@ struct SampleArgs {
   int32_t* token_out;
 };
 void launch_sample_topk(hipStream_t s, const SampleArgs& a);
+void launch_row_dots(hipStream_t s, const void* W, int N, int Kd, const float* g, const float* b, float* c1, float* c2);
 struct SampleBatchArgs {              // the same draw for up to 16 samples, one workgroup each
   float* logits; long stride;         // row j = sample j's logits [V]; destroyed like SampleArgs::logits
   int V, k; float inv_t;
@@ -261,6 +262,10 @@ struct BatchArgs {
   char* slot0; long slot_stride;
   long off_q, off_part, off_knew, off_tickets;
   tagged_t* ssq;                     // [kMaxBatch][nwg] per-workgroup sums of squares of the residual rows they own
+  // LayerNorm (norm_kind = MDI_NORM_LAYERNORM): the sums of those rows travel too, and the products of a normalised
+  // vector are corrected in the epilogue, y = rstd (W (x g)) - rstd mean (W g) + W b: per layer the four vectors
+  // [W_qkv g1 | W_qkv b1 | W_up g2 | W_up b2] (float), layer l's at nc0 + l * nc_stride floats
+  int norm_kind; tagged_t* ssum; const float* nc0; long nc_stride;
   tagged_t* ppart; int str_S, str_oct; // products split among workgroups along the inner dimension: partials [block][S][256], slices per block, block octets
   unsigned* flags;                   // [nwg] phase counters of the workgroups
   int R[4];                          // rows per matrix-instruction block in the QKV / output / up / down products (8 or 16)
@@ -269,11 +274,11 @@ struct BatchArgs {
   unsigned long long* trace;         // optional [workgroup][n_layer][5][8] timestamps (100 MHz ticks), or nullptr
   BatchSlot s[kMaxBatch];
 };
-// Output layers of up to kMaxBatch samples with one pass over the vocabulary matrix (step_w8.hip; bf16, RMSNorm).
+// Output layers of up to kMaxBatch samples with one pass over the vocabulary matrix (step_w8.hip; bf16).
 struct LogitsBatchArgs {
   const void* W; int N, Kd;          // vocabulary matrix [N, Kd] bf16; Kd a multiple of 32, N * Kd * 2 < 2^32
   const void* x[kMaxBatch]; int m;   // activations [Kd] bf16, 16-byte aligned, one per sample
-  const float* g; float eps;         // gain of the final RMSNorm
+  const float* g; const float* b; int norm_kind; float eps;   // the final norm: gain, bias (LayerNorm; may be nullptr), kind
   float* out; long out_stride;       // logits: row j = sample j, [N] floats each, rows out_stride floats apart; or nullptr
   tagged_t* cand; unsigned tag;      // candidates [kMaxBatch][workgroups][2] as (value | tag), (index | tag); tag = this call's
   unsigned* counter;                 // arrival counter, zero between calls

@@ -26,7 +26,9 @@
 //     messages in registers for all the blocks of the phase; the others (output projection, MLP down: one block per
 //     workgroup at the benchmark shapes, a long inner dimension) split the inner dimension among workgroups, so
 //     that a workgroup reads a fraction of the vectors, and exchange 16 x 16 partial results (see KsGeo).
-// Needs bf16 storage, RMSNorm, and widths that are multiples of 32; other shapes keep one pass per message.
+// Needs bf16 storage and widths that are multiples of 32 (LayerNorm only with a GELU MLP); other shapes keep one pass
+// per message.  With LayerNorm the vectors still travel as x * gain: the mean and the norm's bias enter the finished
+// products through two precomputed vectors per matrix (W g and W b), see BatchArgs.
 //
 // Included by step_w8.hip after step_impl.h (shares its exchange, attention and barrier helpers).
 namespace mdi {
@@ -318,7 +320,9 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wg = blockIdx.x, nwg = a.nwg, m = a.m;
   int* s_flag = lds_flag();
-  float* rscale = smem + 32;                     // [16] 1/rms of every message's vector in the normed products
+  float* rscale = smem + 32;                     // [16] 1/rms (LayerNorm: 1/std) of every message's vector in the normed products
+  float* rshift = smem + 64;                     // [16] LayerNorm: mean/std of every message's vector
+  const bool ln = a.norm_kind == MDI_NORM_LAYERNORM;
   float* xres = smem + a.lds_xres;               // residual rows this workgroup owns: [block][16 rows][16 messages]
   float* sq = smem + a.lds_sq;                   // squares of those rows per epilogue item; cross-wavefront sums of the first product
   float* part = smem + a.lds_part;               // the wavefronts' partial products [block][wavefront][lane][4]; attention scratch
@@ -361,6 +365,14 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
       float t = 0.f;
       for (int e = threadIdx.x; e < n_items; e += m) t += sq[e];
       st_tag(a.ssq + (long)threadIdx.x * nwg + wg, t, a.epoch0);
+      if (ln) {                                  // the rows' sum as well (from the rows kept in LDS)
+        float u = 0.f;
+        for (int e = threadIdx.x; e < n_items; e += m) {
+          const int p = (e / m) % half, lb = e / (m * half);
+          if ((lb * nwg + wg) * Rd + 2 * p < a.d) { const float* xr = xres + ((lb << 4) + 2 * p) * 16 + threadIdx.x; u += xr[0] + xr[16]; }
+        }
+        st_tag(a.ssum + (long)threadIdx.x * nwg + wg, u, a.epoch0);
+      }
     }
   }
   __syncthreads();
@@ -403,6 +415,8 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
       const int N = jm == 0 ? (a.H + 2 * a.K) * a.h : jm == 2 ? (a.mlp_kind == MDI_MLP_SWIGLU ? 2 * a.F : a.F) : a.d;
       const int Kd = jm == 1 ? a.H * a.h : jm == 3 ? a.F : a.d;
       const BGeo g = make_bgeo(layer_matrix(Lv, jm), N, Kd, a.R[jm], jm == 0 ? a.h : 0, wg, nwg, wave);
+      // LayerNorm corrections of this phase's product: [W g | W b], N floats each (QKV's first, then the up product's)
+      const float* nc = ln ? a.nc0 + (long)layer * a.nc_stride + (jm == 2 ? 2L * (a.H + 2 * a.K) * a.h : 0L) : nullptr;
       // The per-lane addresses of the exchange vectors do not change from phase to phase; computed once outside
       // the loops they would occupy dozens of registers for the whole launch, so they are derived from a value
       // the compiler cannot see through and are recomputed where they are used.
@@ -481,7 +495,23 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
               }
 #pragma unroll
               for (int off = 16; off >= 1; off >>= 1) t += __shfl_xor(t, off, 64);
-              if (j < m && c == 0) rscale[j] = 1.f / sqrtf(t / (float)a.d + a.eps);
+              if (!ln) {
+                if (j < m && c == 0) rscale[j] = 1.f / sqrtf(t / (float)a.d + a.eps);
+              } else {
+                // LayerNorm: the sums the same way, then 1/std and mean/std
+                float u = 0.f;
+                if (j < m) {
+                  const tagged_t* src = a.ssum + (long)j * nwg;
+                  for (int w0 = c; w0 < nwg; w0 += 32) u += settle(src + w0, ld_raw(src + w0), epoch, a.spin_limit, a.err);
+                }
+#pragma unroll
+                for (int off = 16; off >= 1; off >>= 1) u += __shfl_xor(u, off, 64);
+                if (j < m && c == 0) {
+                  const float mean = u / (float)a.d;
+                  const float rstd = 1.f / sqrtf(fmaxf(t / (float)a.d - mean * mean, 0.f) + a.eps);
+                  rscale[j] = rstd; rshift[j] = rstd * mean;
+                }
+              }
             }
             // the slice, as published: bf16 pairs of x * gain
             const MDI_GLOBAL tagged_t* bbase = (const MDI_GLOBAL tagged_t*)xn_in + ((long)g.ks0 << 8);
@@ -619,6 +649,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
             const int j = e % m, p = (e / m) % half, lb = e / (m * half);
             const int r0 = block_row(g, lb * nwg + wg, p), r1 = r0 + (a.h >> 1);
             float v0 = part_sum(part, lb, p, j) * rscale[j], v1 = part_sum(part, lb, p + half, j) * rscale[j];
+            if (ln) { v0 += nc[N + r0] - rshift[j] * nc[r0]; v1 += nc[N + r1] - rshift[j] * nc[r1]; }
             if (Lv.bqkv) { v0 += Lv.bqkv[r0]; v1 += Lv.bqkv[r1]; }
             const int head = r0 / a.h, i = r0 - head * a.h;
             const float2* rope = sl.rope[j];
@@ -666,6 +697,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
               const int r0 = (lb * nwg + wg) * R + 2 * p;
               if (r0 < g.N) {
                 float v0 = part_sum(part, lb, 2 * p, j) * rscale[j], v1 = part_sum(part, lb, 2 * p + 1, j) * rscale[j];
+                if (ln) { v0 += nc[N + r0] - rshift[j] * nc[r0]; v1 += nc[N + r0 + 1] - rshift[j] * nc[r0 + 1]; }
                 if (Lv.bup) { v0 += Lv.bup[r0]; v1 += Lv.bup[r0 + 1]; }
                 st_pair(ub_l + ((r0 >> 1) << 4) + j, pack_bf16x2(tanh_form ? gelu_tanh_f(v0) : gelu_erf_f(v0), tanh_form ? gelu_tanh_f(v1) : gelu_erf_f(v1)), wtag);
               }
@@ -703,6 +735,14 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
               float t = 0.f;
               for (int e = threadIdx.x; e < n_items; e += m) t += sq[e];
               st_tag(a.ssq + (long)threadIdx.x * nwg + wg, t, wtag);
+              if (ln) {
+                float u = 0.f;
+                for (int e = threadIdx.x; e < n_items; e += m) {
+                  const int p = (e / m) % half, lb = e / (m * half);
+                  if ((lb * nwg + wg) * R + 2 * p < g.N) { const float* xr = xres + ((lb << 4) + 2 * p) * 16 + threadIdx.x; u += xr[0] + xr[16]; }
+                }
+                st_tag(a.ssum + (long)threadIdx.x * nwg + wg, u, wtag);
+              }
             }
           }
         }

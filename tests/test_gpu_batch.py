@@ -24,6 +24,12 @@ SHAPES = {
     "wide": dict(d_model=256, n_head=4, n_kv_head=2, head_dim=64, d_ff=704),
     # 9 column steps of 32 in the down projection: some wavefronts of a workgroup get none
     "idle_wavefronts": dict(d_model=256, n_head=4, n_kv_head=2, head_dim=64, d_ff=288),
+    # the GPT-2 family: LayerNorm (its mean and bias enter the products through precomputed vectors), GELU, biases,
+    # learned positions
+    "gpt2_like": dict(d_model=96, n_head=6, n_kv_head=6, head_dim=16, d_ff=192, norm_kind=S.NORM_LAYERNORM,
+                      mlp_kind=S.MLP_GELU_TANH, pos_kind=S.POS_LEARNED, has_bias=1),
+    "layernorm_rope_gelu_erf": dict(d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96, norm_kind=S.NORM_LAYERNORM,
+                                    mlp_kind=S.MLP_GELU_ERF),
 }
 
 
@@ -105,7 +111,7 @@ def test_batched_pass_on_a_mid_partition_and_more_messages_than_one_pass():
 
 
 def test_shapes_that_cannot_share_a_pass_fall_back_to_one_pass_per_message():
-    for over in (dict(dtype=S.DT_F32), dict(norm_kind=S.NORM_LAYERNORM), dict(d_ff=48)):
+    for over in (dict(dtype=S.DT_F32), dict(norm_kind=S.NORM_LAYERNORM), dict(d_ff=48)):          # (LayerNorm with a SwiGLU MLP)
         cfg = S.tiny(n_layer=2, max_ctx=32, **dict(dict(dtype=S.DT_BF16, d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96), **over))
         w = scale_matrices(S.make_weights(cfg, 5, exercise=True), 3.0)
         o, g = pair(cfg, w, 0, 2, embed=True, max_seqs=3, kv_page_tokens=8)

@@ -113,6 +113,47 @@ def test_c2_gpt2_small_3x4_bf16_pipeline():
     assert torch.equal(t1, t2) and torch.equal(h1, h2)
 
 
+def test_c2_gpt2_small_3x4_bf16_shared_passes():
+    """C2 with every stage taking the three samples' messages through one pass over its weights (LayerNorm: the mean
+    and the norm's bias enter the products through precomputed vectors) and the last stage drawing the three tokens
+    with one pass over the vocabulary matrix.  The oracle follows the GPU's tokens sample by sample."""
+    wl = S.WORKLOADS[2]
+    cfg, seed = wl["cfg"](), S.workload_seed(2)
+    w = S.make_weights(cfg, seed)
+    n_seqs, n_new = wl["n_seqs"], 24
+    prompts = S.make_prompts(cfg, seed, n_seqs, wl["prompt"])
+    bounds = [0, 4, 8, 12]
+    parts = [mdi.Partition(cfg, w, bounds[i], bounds[i + 1], has_embed=i == 0, has_head=i == 2, max_seqs=n_seqs,
+                           stream=torch.cuda.Stream()) for i in range(3)]
+    assert all(p.info(4) == 16 for p in parts) and parts[2].info(6) == 16
+    toks, logits, hidden = RecurrentPipeline(parts).generate([dev_ids(p) for p in prompts], n_new, keep_logits=True,
+                                                            keep_hidden=True, drain="shared")
+    torch.cuda.synchronize()
+    for p in parts:
+        p.sync()
+    toks, logits, hidden = host(toks).astype(np.int64), host(logits), host(hidden)
+    ops = [O.Partition(cfg, w, bounds[i], bounds[i + 1], has_embed=i == 0, has_head=i == 2) for i in range(3)]
+    worst = 0.0
+    for s in range(n_seqs):
+        x = prompts[s]
+        for o in ops:
+            x = o.prefill(s, x)
+        x = x[-1]
+        for j in range(n_new):
+            worst = max(worst, check(hidden[s, j], x, cfg, ("C2 shared, hidden", s, j)))
+            want_tok, want = ops[2].sample_greedy(S.storage_round(x.astype(np.float32), cfg["dtype"]))
+            check(logits[s, j], want, cfg, ("C2 shared, logits", s, j))
+            assert toks[s, j] == int(np.flatnonzero(logits[s, j] == logits[s, j].max())[0])
+            top2 = np.sort(want)[-2:]
+            if top2[1] - top2[0] > 10 * np.abs(logits[s, j] - want).max():
+                assert toks[s, j] == want_tok
+            if j + 1 < n_new:
+                x = np.array([toks[s, j]], dtype=np.int32)
+                for o in ops:
+                    x = o.decode_step(s, x)
+    _say(f"C2 shared passes: worst hidden rel-L2 {worst:.2e}")
+
+
 # ------------------------------------------------------------------ C3
 def test_c3_tinyllama_layers_0_10_bf16():
     wl = S.WORKLOADS[3]

@@ -40,7 +40,11 @@
  * become resident, or an exchange never completes, the kernel gives up, the
  * step's outputs are invalid and mdi_partition_sync reports MDI_ERR_HIP; the
  * partition must then be destroyed (its exchange counters are no longer
- * consistent), other partitions are unaffected.
+ * consistent), other partitions are unaffected.  Two more things are kept per
+ * process: the fixed scratch array of mdi_sample_topk_static (one copy per GPU,
+ * see there), and a counter that numbers the launches of the output layers
+ * (the number travels with the per-workgroup argmax candidates, so that a
+ * candidate left behind by an earlier launch is never taken for a new one).
  *
  * Two tuning knobs are read from the environment when a partition is created:
  * MDI_GROUP_CTX = context length from which, in models whose query heads share

@@ -250,10 +250,8 @@ MDI_API mdi_status mdi_decode_steps(mdi_partition *part, uint32_t n, const uint3
  * once plus every sample's cache, instead of the weights once per message.
  * More than 16 messages take several passes; a lone message is forwarded as
  * by mdi_decode_step.  Needs bf16 storage, the persistent decode path,
- * d_model, n_head * head_dim, d_ff multiples of 32 (d_model at most 4096) and
- * either RMSNorm or LayerNorm with a GELU MLP (the GPT-2 and the Llama
- * families; LayerNorm with SwiGLU is not covered); other partitions forward
- * the messages as mdi_decode_steps does
+ * d_model, n_head * head_dim, d_ff multiples of 32 (d_model at most 4096);
+ * other partitions forward the messages as mdi_decode_steps does
  * (mdi_partition_info(4) tells).  Vectors between the matrix products are
  * rounded to bf16 here (as in a first visit), so a sample's result agrees with
  * mdi_decode_step's within the bf16 parity bar, not to the last bits; for a

@@ -206,7 +206,7 @@ size_t carve(mdi_partition* p, void* arena) {
       sc.part = (tagged_t*)cv.take(H * kMaxSplits * (h + 2) * 8);
       sc.knew = (tagged_t*)cv.take(2 * K * h * 8);
     }
-    p->batch_region = c.dtype == MDI_BF16 && (c.norm_kind == MDI_NORM_RMSNORM || !swiglu);
+    p->batch_region = c.dtype == MDI_BF16;
     if (p->batch_region) {
       // one block per message of a batched launch, all laid out alike, so that message j's vectors are message
       // 0's advanced by j strides

@@ -26,8 +26,7 @@
 //     messages in registers for all the blocks of the phase; the others (output projection, MLP down: one block per
 //     workgroup at the benchmark shapes, a long inner dimension) split the inner dimension among workgroups, so
 //     that a workgroup reads a fraction of the vectors, and exchange 16 x 16 partial results (see KsGeo).
-// Needs bf16 storage and widths that are multiples of 32 (LayerNorm only with a GELU MLP); other shapes keep one pass
-// per message.  With LayerNorm the vectors still travel as x * gain: the mean and the norm's bias enter the finished
+// Needs bf16 storage and widths that are multiples of 32; other shapes keep one pass per message.  With LayerNorm the vectors still travel as x * gain: the mean and the norm's bias enter the finished
 // products through two precomputed vectors per matrix (W g and W b), see BatchArgs.
 //
 // Included by step_w8.hip after step_impl.h (shares its exchange, attention and barrier helpers).
@@ -686,7 +685,13 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
 #pragma unroll
                 for (int w = 0; w < kStepWaves; ++w) { const f32x4 t = *reinterpret_cast<const f32x4*>(pp + (w << 8)); v += t; }
                 const float rs = rscale[j];
-                const float u0 = silu_f(v.x * rs) * (v.y * rs), u1 = silu_f(v.z * rs) * (v.w * rs);
+                v *= rs;
+                if (ln) {
+                  const float sh = rshift[j];
+                  v.x += nc[N + r0] - sh * nc[r0]; v.y += nc[N + r0 + 1] - sh * nc[r0 + 1];
+                  v.z += nc[N + r0 + 2] - sh * nc[r0 + 2]; v.w += nc[N + r0 + 3] - sh * nc[r0 + 3];
+                }
+                const float u0 = silu_f(v.x) * v.y, u1 = silu_f(v.z) * v.w;
                 st_pair(ub_l + ((r0 >> 2) << 4) + j, pack_bf16x2(u0, u1), wtag);
               }
             }

@@ -28,6 +28,7 @@ SHAPES = {
     # learned positions
     "gpt2_like": dict(d_model=96, n_head=6, n_kv_head=6, head_dim=16, d_ff=192, norm_kind=S.NORM_LAYERNORM,
                       mlp_kind=S.MLP_GELU_TANH, pos_kind=S.POS_LEARNED, has_bias=1),
+    "layernorm_swiglu": dict(d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96, norm_kind=S.NORM_LAYERNORM),
     "layernorm_rope_gelu_erf": dict(d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96, norm_kind=S.NORM_LAYERNORM,
                                     mlp_kind=S.MLP_GELU_ERF),
 }
@@ -111,7 +112,7 @@ def test_batched_pass_on_a_mid_partition_and_more_messages_than_one_pass():
 
 
 def test_shapes_that_cannot_share_a_pass_fall_back_to_one_pass_per_message():
-    for over in (dict(dtype=S.DT_F32), dict(norm_kind=S.NORM_LAYERNORM), dict(d_ff=48)):          # (LayerNorm with a SwiGLU MLP)
+    for over in (dict(dtype=S.DT_F32), dict(d_ff=48), dict(d_model=48, n_head=3, n_kv_head=3)):
         cfg = S.tiny(n_layer=2, max_ctx=32, **dict(dict(dtype=S.DT_BF16, d_model=64, n_head=4, n_kv_head=2, head_dim=16, d_ff=96), **over))
         w = scale_matrices(S.make_weights(cfg, 5, exercise=True), 3.0)
         o, g = pair(cfg, w, 0, 2, embed=True, max_seqs=3, kv_page_tokens=8)

@@ -320,7 +320,8 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
   const int wg = blockIdx.x, nwg = a.nwg, m = a.m;
   int* s_flag = lds_flag();
   float* rscale = smem + 32;                     // [16] 1/rms (LayerNorm: 1/std) of every message's vector in the normed products
-  float* rshift = smem + 64;                     // [16] LayerNorm: mean/std of every message's vector
+  float* rshift = smem + 64;                     // [16] LayerNorm: (mean - centre) / std of every message's vector
+  float* rcen = smem + 80;                       // [16] LayerNorm: the centre the vectors are published around (see below)
   const bool ln = a.norm_kind == MDI_NORM_LAYERNORM;
   float* xres = smem + a.lds_xres;               // residual rows this workgroup owns: [block][16 rows][16 messages]
   float* sq = smem + a.lds_sq;                   // squares of those rows per epilogue item; cross-wavefront sums of the first product
@@ -342,6 +343,22 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
   // as the launch's inputs.  They are also published exactly as a down projection publishes its result - pairs of
   // x times the first layer's gain, this workgroup's share of the sums of squares, both with the counter the
   // first phase expects - so that the first layer's QKV product is like any other.
+  // LayerNorm: a vector travels as (x - c) g in bf16, c a number per message that every workgroup knows: rounding
+  // x g itself would cost accuracy whenever |mean| >> std.  c is the mean of the message's vector at the previous
+  // norm of the launch (every workgroup computes it, from the same sums in the same order), for the first norm the
+  // mean of the input vector, which every workgroup forms here for itself.
+  if (!ln) {
+    if (threadIdx.x < kMaxBatch) rcen[threadIdx.x] = 0.f;
+  } else {
+    for (int j = wave; j < m; j += kStepWaves) {
+      float u = 0.f;
+      for (int r = lane; r < a.d; r += 64) u += batch_input(a, sl, j, r);
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) u += __shfl_xor(u, off, 64);
+      if (lane == 0) rcen[j] = u / (float)a.d;
+    }
+  }
+  __syncthreads();
   {
     const int Rd = a.R[1], half = Rd >> 1;
     const BGeo gd = make_bgeo(nullptr, a.d, a.H * a.h, Rd, 0, wg, nwg, wave);
@@ -354,7 +371,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
         const float x0 = batch_input(a, sl, j, r0), x1 = batch_input(a, sl, j, r0 + 1);
         float* xr = xres + ((lb << 4) + 2 * p) * 16 + j;
         xr[0] = x0; xr[16] = x1;
-        st_pair(a.xn + ((r0 >> 1) << 4) + j, pack_bf16x2(x0 * a.l0.ln1_g[r0], x1 * a.l0.ln1_g[r0 + 1]), a.epoch0);
+        st_pair(a.xn + ((r0 >> 1) << 4) + j, pack_bf16x2((x0 - rcen[j]) * a.l0.ln1_g[r0], (x1 - rcen[j]) * a.l0.ln1_g[r0 + 1]), a.epoch0);
         s2 = x0 * x0 + x1 * x1;
       }
       sq[e] = s2;
@@ -508,7 +525,8 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
                 if (j < m && c == 0) {
                   const float mean = u / (float)a.d;
                   const float rstd = 1.f / sqrtf(fmaxf(t / (float)a.d - mean * mean, 0.f) + a.eps);
-                  rscale[j] = rstd; rshift[j] = rstd * mean;
+                  rscale[j] = rstd; rshift[j] = rstd * (mean - rcen[j]);
+                  rcen[j] = mean;                      // what the next norm's vector is published around
                 }
               }
             }
@@ -728,7 +746,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
               if (last) {
                 store_kind(sl.out[j], a.act_kind, r0, x0); store_kind(sl.out[j], a.act_kind, r0 + 1, x1);
               } else {
-                st_pair(xn_out + ((r0 >> 1) << 4) + j, pack_bf16x2(x0 * gain[r0], x1 * gain[r0 + 1]), wtag);
+                st_pair(xn_out + ((r0 >> 1) << 4) + j, pack_bf16x2((x0 - rcen[j]) * gain[r0], (x1 - rcen[j]) * gain[r0 + 1]), wtag);
                 s2 = x0 * x0 + x1 * x1;
               }
             }

@@ -213,3 +213,36 @@ def test_driver_with_shared_passes_on_a_three_node_ring():
             assert int(t2[s, j]) in pmf
             if np.abs(np.cumsum(list(pmf.values())) - u).min() > 1e-5:
                 assert int(t2[s, j]) == O.sample_topk(lg2[s, j], 0.9, 8, u), (s, j)
+
+
+def test_layernorm_vectors_far_from_zero_mean():
+    """LayerNorm in the shared pass publishes (x - c) g in bf16 with c close to the vector's mean.  With a residual
+    stream whose mean is far from zero (embeddings with a large common offset) the bf16 hand-off itself limits what
+    any path can deliver, so the measure is the error relative to the centred vector - the part that carries
+    information - next to that of the one-message path on the same inputs: the shared pass must not be worse by
+    more than a half, which x g rounded to bf16 would be several times over."""
+    cfg = S.tiny(n_layer=3, dtype=S.DT_BF16, max_ctx=64, vocab=211, **SHAPES["gpt2_like"])
+    w = scale_matrices(S.make_weights(cfg, 53, exercise=True), 2.0)
+    w["wte"] = S.storage_round(w["wte"] + np.float32(6.0), cfg["dtype"])      # mean / std of an embedding row: about 150
+    n = 6
+    o, g = pair(cfg, w, 0, 3, embed=True, max_seqs=n, kv_page_tokens=8)
+    g1 = mdi.Partition(cfg, w, 0, 3, has_embed=True, max_seqs=n, kv_page_tokens=8)
+    assert g.info(4) == 16
+    prompts = S.make_prompts(cfg, 53, n, 9)
+    for s in range(n):
+        check(g.prefill(s, dev_ids(prompts[s])), o.prefill(s, prompts[s]), cfg, ("prefill", s))
+        g1.prefill(s, dev_ids(prompts[s]))
+    rng = np.random.default_rng(8)
+    worst, worst1 = 0.0, 0.0
+    for step in range(6):
+        toks = [int(rng.integers(0, cfg["vocab"])) for _ in range(n)]
+        outs = g.decode_batch(list(range(n)), [dev_ids([t]) for t in toks])
+        for s, t, got in zip(range(n), toks, outs):
+            want = o.decode_step(s, t)
+            scale = np.linalg.norm(want - want.mean())
+            worst = max(worst, float(np.linalg.norm(host(got).astype(np.float64) - want) / scale))
+            worst1 = max(worst1, float(np.linalg.norm(host(g1.decode_step(s, dev_ids([t]))).astype(np.float64) - want) / scale))
+    g.sync()
+    g1.sync()
+    print(f"far-from-zero mean: worst error relative to the centred vector {worst:.2e} (one message at a time: {worst1:.2e})", flush=True)
+    assert worst < 1.5 * worst1 + 2e-3

@@ -77,3 +77,21 @@ def test_tinyllama_shape_paper_splits_bf16():
         worst_l = max(rel_l2(logits[s][j], logits_o[s][j]) for s in range(n_seqs) for j in range(n_new))
         _say(f"tinyllama {name}: worst rel-L2 hidden {worst:.2e}, logits {worst_l:.2e}")
         assert worst <= 2e-2 and worst_l <= 2e-2
+
+
+def test_paper_rate_experiment_runs_on_the_nanollama_shape():
+    """bench.py --paper-run (Sec. IV-B: three samples from one-token prompts, the paper's cuts and an unbalanced one)
+    with a handful of tokens: every cut and driver mode produces a rate, the stage times are positive, and the rate
+    bound for one GPU per stage is highest for the balanced three-node cut and lowest for a single node."""
+    import bench
+    args = bench.parse(["--paper-run", "nanollama", "--paper-tokens", "6"])
+    out = bench.paper_run(args, torch, mdi, S)
+    assert out["unit"] == "tokens/s" and out["value"] > 0 and len(out["runs"]) == 8
+    for r in out["runs"]:
+        modes = [k for k, v in r.items() if isinstance(v, dict) and "tokens_per_s" in v]
+        assert len(modes) >= 2 and all(r[k]["tokens_per_s"] > 0 for k in modes)
+        assert ("bf16" in r["storage"]) == (len(modes) == 3)            # the shared pass needs bf16 storage
+        assert all(t > 0 for t in r["stage_ms_per_message"]) and max(r["stage_busy_fraction_on_its_own_gpu"]) == 1.0
+    bf = {r["cut"]: r["tokens_per_s_bound_with_a_gpu_per_stage"] for r in out["runs"] if "bf16" in r["storage"]}
+    assert bf["3 nodes 2/5/5"] > bf["2 nodes 5/7"] > bf["1 node"]
+    assert bf["3 nodes 1/1/10 (unbalanced)"] < bf["3 nodes 2/5/5"]

@@ -229,7 +229,7 @@ size_t carve(mdi_partition* p, void* arena) {
         p->b_nc = (float*)cv.take(p->n_local * p->b_nc_stride * 4);
       }
       p->b_ppart = (tagged_t*)cv.take((size_t)((d + 15) / 16) * 16 * 256 * 8);   // [block][up to 16 slices][256]
-      p->b_flags = (unsigned*)cv.take(1024 * 4);
+      p->b_flags = (unsigned*)cv.take((size_t)1024 * kFlagStride * 4);
     }
     const size_t T = p->Tm;
     p->p_xres = (float*)cv.take(T * d * 4);
@@ -529,7 +529,7 @@ mdi_status mdi_partition_create(const mdi_config* cfg, uint32_t layer_lo, uint32
         }
       }
       launch_fill_u32(p->stream, (uint32_t*)p->b_ppart, (long)((d + 15) / 16) * 16 * 256 * 2, 0u);
-      launch_fill_u32(p->stream, p->b_flags, 1024, 1u);
+      launch_fill_u32(p->stream, p->b_flags, 1024L * kFlagStride, 1u);
       p->b_epoch = 1;
     }
     launch_fill_u32(p->stream, p->bar_flags, 1024, 1u);     // phase counters start at 1: tag 0 marks "never written"

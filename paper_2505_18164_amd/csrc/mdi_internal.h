@@ -231,6 +231,7 @@ void launch_logits(hipStream_t s, int dtype, int nwg, size_t lds_bytes, const Lo
 // The messages waiting in the node's input queue (Sec. III-A; several samples are in flight, Sec. III-C) are
 // taken through every layer together: a weight tile is fetched once and multiplied with all their vectors on the
 // matrix cores (the messages are the second operand's columns), attention stays per sample.
+constexpr int kFlagStride = 32;       // a workgroup's phase counter has a 128-byte line to itself
 constexpr int kMaxBatch = 16;        // messages one pass can carry: the matrix instruction's column count
 
 struct BatchSlot {                   // what belongs to one message of the launch

@@ -403,7 +403,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
       while (true) {
         bool all = true;
         for (int i = threadIdx.x; i < nwg; i += 64) {
-          const unsigned v = __hip_atomic_load(a.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const unsigned v = __hip_atomic_load(a.flags + i * kFlagStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           all = all && ((int)(v - epoch) >= 0);
         }
         if (__all(all)) break;
@@ -776,7 +776,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(2,
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __syncthreads();
       bstamp(a, layer, ph, 6);
-      if (threadIdx.x == 0) __hip_atomic_store(a.flags + wg, epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (threadIdx.x == 0) __hip_atomic_store(a.flags + wg * kFlagStride, epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }

@@ -165,6 +165,8 @@ void launch_flash_prefill(hipStream_t s, const FlashArgs& a);
 // ---- whole decode step as one persistent launch ------------------------------
 constexpr int kStepWavesMax = 8;     // wavefronts per workgroup: 8 (one workgroup per compute unit) or 4 (two)
 constexpr int kMaxSlots = 8;         // messages one launch can carry
+constexpr int kFlagStride = 32;      // batched pass: a workgroup's phase counter has a 128-byte line to itself (in 4-byte words);
+                                     // measured on the one-message kernels as well: no gain there, their counters stay packed
 
 typedef unsigned long long tagged_t;  // low half: the value's bits, high half: the phase counter it was written in
 
@@ -231,7 +233,6 @@ void launch_logits(hipStream_t s, int dtype, int nwg, size_t lds_bytes, const Lo
 // The messages waiting in the node's input queue (Sec. III-A; several samples are in flight, Sec. III-C) are
 // taken through every layer together: a weight tile is fetched once and multiplied with all their vectors on the
 // matrix cores (the messages are the second operand's columns), attention stays per sample.
-constexpr int kFlagStride = 32;       // a workgroup's phase counter has a 128-byte line to itself
 constexpr int kMaxBatch = 16;        // messages one pass can carry: the matrix instruction's column count
 
 struct BatchSlot {                   // what belongs to one message of the launch

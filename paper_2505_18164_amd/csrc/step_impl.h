@@ -523,15 +523,61 @@ __device__ __forceinline__ void attn_update(AttnState<WT, G>& st, const AttnGeo&
   attn_update_f<WT, G>(st, g, h, kf, vf, valid, qs);
 }
 
+// One tile = kTile cached positions per lane group.  The scores of all of them first, then ONE rescaling of the running
+// sums to the new maximum, then the weighted values: a rescaling per position (as attn_update_f does for the single
+// newest row) costs as many multiplications as the values themselves.
 template <typename WT, int G>
 __device__ __forceinline__ void attn_compute(AttnState<WT, G>& st, const Tile& t, const AttnGeo& g, int h, int ti, int wave,
                                              const float* qs) {
+  constexpr int V = Storage<WT>::kVec;
+  float sc[kTile][G];
+  bool ok[kTile];
 #pragma unroll
   for (int s = 0; s < kTile; ++s) {
     const int k = ti * kTile + s;
-    if (k < g.n_k) {
-      const int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
-      attn_update<WT, G>(st, g, h, t.r[2 * s], t.r[2 * s + 1], tok < g.s1p, qs);
+    const int tok = g.s0 + (k * kStepWaves + wave) * g.tpw + g.sub;
+    ok[s] = k < g.n_k && tok < g.s1p;
+    if (k < g.n_k) {                                     // uniform
+      float kf[V];
+      Unpack<WT>::go(t.r[2 * s], kf);
+#pragma unroll
+      for (int gi = 0; gi < G; ++gi) {
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < V; e += 4) {
+          const float4 q4 = *reinterpret_cast<const float4*>(qs + gi * h + g.hoff + e);
+          d = fmaf(q4.x, kf[e], d); d = fmaf(q4.y, kf[e + 1], d); d = fmaf(q4.z, kf[e + 2], d); d = fmaf(q4.w, kf[e + 3], d);
+        }
+        sc[s][gi] = group_sum_lanes(d, g);
+      }
+    } else {
+#pragma unroll
+      for (int gi = 0; gi < G; ++gi) sc[s][gi] = -1e30f;
+    }
+  }
+#pragma unroll
+  for (int gi = 0; gi < G; ++gi) {
+    float mn = st.m[gi];
+#pragma unroll
+    for (int s = 0; s < kTile; ++s) mn = ok[s] ? fmaxf(mn, sc[s][gi]) : mn;
+    const float alpha = __expf(st.m[gi] - mn);
+    st.m[gi] = mn;
+    st.l[gi] *= alpha;
+#pragma unroll
+    for (int e = 0; e < V; ++e) st.o[gi][e] *= alpha;
+  }
+#pragma unroll
+  for (int s = 0; s < kTile; ++s) {
+    if (ti * kTile + s < g.n_k) {                        // uniform
+      float vf[V];
+      Unpack<WT>::go(t.r[2 * s + 1], vf);
+#pragma unroll
+      for (int gi = 0; gi < G; ++gi) {
+        const float p = ok[s] ? __expf(sc[s][gi] - st.m[gi]) : 0.f;
+        st.l[gi] += p;
+#pragma unroll
+        for (int e = 0; e < V; ++e) st.o[gi][e] = fmaf(p, vf[e], st.o[gi][e]);
+      }
     }
   }
 }

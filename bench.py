@@ -44,7 +44,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 # hash to what they were when it was measured; otherwise `roofline.traffic` is null.
 KERNEL_SOURCES = ("step_impl.h", "step_batch.h", "head_batch.h", "step_w4.hip", "step_w8.hip", "device_utils.h", "mdi_internal.h")
 MEASURED_TRAFFIC = {
-    (4, 8, True): {"bytes": 4.9251e9, "kernel_rev": "dde4d3c9f629",
+    (4, 8, True): {"bytes": 4.9261e9, "kernel_rev": "5a05780777ce",
                    "source": "profiles/k_step_batch_c4_decode_hbm_counters.md (FETCH_SIZE x 2.0 KiB + WRITE_SIZE x 1.0 KiB, context about 1030)"},
 }
 

@@ -279,7 +279,7 @@ def test_c4_first_visit_in_pieces_of_256():
     b = S.make_activations(cfg, seed + 5, 1, 90)
     check(g.prefill(1, dev_acts(b, cfg)), op.prefill(1, b), cfg, "other sample, first visit")
     at = 0
-    for piece in (256, 256, 300, 1, 211):                          # the verdict's 256s, a ragged one, a single position
+    for piece in (256, 256, 300, 1, 211):                          # pieces of 256, a ragged one, a single position
         got = g.prefill_chunk(0, dev_acts(a[at:at + piece], cfg))
         check(got, want[at:at + piece], cfg, ("C4 piece at", at))
         at += piece
